@@ -1,0 +1,213 @@
+/*
+ * pasta_attn.h -- C ABI of the multi-stream decode-attention step of PASTA's
+ * asynchronous decoding (arxiv 2502.11517, Section 3 "Language and Interpreter
+ * Design", paragraph "Efficiency", and Figure 2b/2c).
+ *
+ * The operation.  Several decoding threads ("streams") of one response each
+ * decode their next token in the same forward pass against ONE pre-allocated
+ * KV pool.  Streams append their K/V rows to the pool tail as they decode, so
+ * rows of concurrently active streams are physically interleaved (Section 3,
+ * Efficiency: single contiguous pre-allocated pool with an interleaved layout;
+ * Figure 2c).  A query row of stream s attends only to the tokens reachable
+ * from it in the fork graph: its own tokens plus the tokens of its ancestors
+ * that existed before the fork (Section 3, Efficiency, the attention-mask
+ * paragraph; Figure 2b).  In this library that visible set is a list
+ *
+ *     Vis(s) = [0, prefix_len_s)  U  { start_k + j*stride_k : j < count_k }_k
+ *
+ * of logical slots of the request's pool, and one decode step computes, for
+ * every active stream s and query head h (KV head g = h / (Hq/Hkv)),
+ *
+ *     z_t = softmax_scale * <q[s,h,:], K[t,g,:]>          t in Vis(s)
+ *     out[s,h,:] = sum_t softmax(z)_t * V[t,g,:]
+ *     lse[s,h]   = log sum_t exp(z_t)
+ *
+ * No KV row is ever moved or copied after it has been appended (Section 3,
+ * Efficiency, last paragraphs; contrast with the appendix "Naive Interpreter
+ * Implementation").
+ *
+ * Everything runs on one GPU (gfx950).  All entry points return a status
+ * code; none throws, aborts, or keeps global state.  "HOST" / "DEVICE" below
+ * say where a pointer must point.  The library allocates NO device memory:
+ * pool, workspace, Q and outputs are the caller's.
+ */
+#ifndef PASTA_ATTN_H
+#define PASTA_ATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pasta_attn pasta_attn; /* opaque; one per (shape, pool) */
+
+enum {
+  PASTA_OK = 0,
+  PASTA_E_INVAL = -1,    /* bad argument; nothing enqueued, no state changed */
+  PASTA_E_CAPACITY = -2, /* pool / page table / stream table / workspace full */
+  PASTA_E_NOMEM = -3,    /* host allocation failed */
+  PASTA_E_DEVICE = -4,   /* a HIP call failed (or no GPU is present) */
+  PASTA_E_STATE = -5     /* unknown stream, destroyed handle, layer order */
+};
+
+enum { PASTA_F32 = 0, PASTA_BF16 = 1 };
+
+/* Placement of one token's rows inside a layer's pool.  The paper fixes only
+ * "one contiguous pool, rows appended at the tail"; the order of the head and
+ * token axes is this library's choice and a create-time fact.
+ *
+ * Physical row of (request r, logical slot t):
+ *   contiguous mode (page_tokens == 0):  phys = r * pool_tokens + t
+ *   paged mode      (page_tokens  > 0):  phys = page_table[r][t / page_tokens]
+ *                                               * page_tokens + t % page_tokens
+ * With rows_per_layer = max_requests * pool_tokens (contiguous) or
+ * n_phys_pages * page_tokens (paged), the ELEMENT offset of (phys, kv head g)
+ * inside a layer's K (or V) pool is
+ *   TOKEN_MAJOR:              (phys * Hkv + g) * D
+ *   HEAD_MAJOR, contiguous:   (g * rows_per_layer + phys) * D
+ *   HEAD_MAJOR, paged:        ((page * Hkv + g) * page_tokens + phys % page_tokens) * D,
+ *                             page = phys / page_tokens
+ * and layer l starts at element l * rows_per_layer * Hkv * D.               */
+enum { PASTA_LAYOUT_TOKEN_MAJOR = 0, PASTA_LAYOUT_HEAD_MAJOR = 1 };
+
+typedef struct {
+  uint32_t struct_size;   /* sizeof(pasta_attn_config); ABI check */
+  int32_t dtype;          /* PASTA_F32 | PASTA_BF16: pool, Q and out element type */
+  int32_t n_q_heads;      /* Hq */
+  int32_t n_kv_heads;     /* Hkv; Hq % Hkv == 0, Hq/Hkv in {1,2,4,8} */
+  int32_t head_dim;       /* D in {64, 128} */
+  int32_t n_layers;       /* >= 1 pools that share one slot assignment */
+  int32_t max_requests;   /* 1 = the paper's batch-1 setting */
+  int32_t page_tokens;    /* 0 = contiguous; else a power of two (e.g. 16) */
+  int32_t kv_layout;      /* PASTA_LAYOUT_* */
+  int32_t n_phys_pages;   /* paged mode: physical pages per layer */
+  int32_t pages_per_request; /* paged mode: columns of page_table */
+  int32_t max_streams;    /* stream ids per request are 0 .. max_streams-1 */
+  int32_t max_ranges;     /* most range descriptors one decode_step may carry
+                             (sum over its streams) */
+  float softmax_scale;    /* applied to q.k; explicit, never implied */
+  int64_t pool_tokens;    /* contiguous mode: slots per request per layer (the
+                             paper's fixed maximum sequence length) */
+  void *k_pool;           /* DEVICE, borrowed for the handle's lifetime:
+                             n_layers * rows_per_layer * Hkv * D elements */
+  void *v_pool;           /* DEVICE, same shape */
+  const int32_t *page_table; /* HOST [max_requests][pages_per_request], copied at
+                             create (paged mode; NULL otherwise).  Entries must be
+                             distinct and in [0, n_phys_pages). */
+  void *workspace;        /* DEVICE, borrowed, 256-byte aligned */
+  uint64_t workspace_bytes; /* in: bytes provided; query mode writes bytes needed */
+  void *hip_stream;       /* hipStream_t of the caller; all work is enqueued here */
+} pasta_attn_config;
+
+/* Creates a handle.  With out == NULL ("query mode") only validates cfg and
+ * writes the required size into cfg->workspace_bytes; pointers in cfg may be
+ * NULL then.  Otherwise cfg->workspace_bytes must be at least that size.
+ * Makes no HIP call that needs a device except one synchronous copy of the
+ * page table into the workspace (paged mode).
+ * Errors: E_INVAL (shape / NULL / misaligned / bad page table), E_CAPACITY
+ * (workspace too small), E_NOMEM, E_DEVICE.                                  */
+int32_t pasta_attn_create(pasta_attn_config *cfg, pasta_attn **out);
+
+/* KV append (Section 3, Efficiency: every active thread appends its new
+ * KV-cache row to the pool tail, so rows of concurrently active threads land
+ * in neighbouring slots and alternate; Figure 2c).
+ * Row i takes logical slot tail[request_id[i]]++ in CALL ORDER -- call order
+ * IS the physical interleave.  The same slots are used for every layer: the
+ * caller issues the identical call once per layer (any layer order) and the
+ * bookkeeping (tails, visibility lists) advances when layer == n_layers-1,
+ * which must come last.  A token the interpreter defers (the paper's <sync/>
+ * row) is simply not passed until it is to enter the pool.                   */
+typedef struct {
+  uint32_t struct_size;
+  int32_t layer;
+  int32_t n_rows;               /* >= 0; 0 is a no-op */
+  const int32_t *request_id;    /* HOST [n_rows], each in [0, max_requests) */
+  const int32_t *stream_id;     /* HOST [n_rows], each in [0, max_streams) */
+  const int32_t *parent_stream; /* HOST [n_rows] or NULL.  >= 0 only on a row that
+                                   OPENS stream_id: the new stream inherits the
+                                   parent's visible set as of this row (ancestor
+                                   rule).  -1 otherwise; a row with -1 whose stream
+                                   is unknown opens a root stream (empty visible
+                                   set). */
+  const int32_t *position;      /* HOST [n_rows] or NULL: position ids (the paper's
+                                   length-predicted ids, Section 4.1); carried for
+                                   the caller, not used by the arithmetic: Q and K
+                                   arrive already rotated */
+  const void *k_new;            /* DEVICE [n_rows][Hkv][D], pool dtype */
+  const void *v_new;            /* DEVICE [n_rows][Hkv][D] */
+  int32_t *out_slot;            /* HOST [n_rows] or NULL: logical slot given to row i */
+} pasta_append_args;
+
+/* Errors: E_INVAL (NULL, ids out of range, parent unknown or equal to the
+ * stream, parent given for a stream that is already open), E_CAPACITY (pool or
+ * page table full; max_ranges exceeded), E_STATE (layer out of range),
+ * E_DEVICE.  A failing call enqueues nothing and changes no state.           */
+int32_t pasta_attn_append_kv(pasta_attn *h, const pasta_append_args *a);
+
+/* One decode step: one query token per active stream, all in one pass over
+ * the shared pool (Section 1, Interpreter: several non-contiguous chunks are
+ * decoded simultaneously; Section 3, Efficiency: masked attention over the
+ * interleaved pool).  The step attends to exactly the listed rows and nothing
+ * implicit: the caller appends the current token's K/V first if the token is
+ * to see itself.
+ *
+ * Visibility comes in one of two modes:
+ *   explicit   (range_offsets != NULL): prefix_len[n] and a CSR of
+ *              (start, count, stride) descriptors per stream, all HOST.  Within
+ *              a stream every range must start after the last slot of the one
+ *              before it, the first must start at or after prefix_len, all slots
+ *              must be < tail of the request, count >= 1, stride >= 1, and the
+ *              visible set must not be empty.
+ *   maintained (range_offsets == NULL): the lists that append_kv has been
+ *              keeping for (request_id[i], stream_id[i]).
+ * Output row i belongs to stream i of the call.                              */
+enum {
+  PASTA_DECODE_PLAN_ONLY = 1u, /* validate + plan + fill HOST debug outputs, enqueue nothing */
+  PASTA_DECODE_NO_MFMA = 2u    /* route the shared prefix through the private-segment
+                                  kernel too (the path F32 always takes) */
+};
+
+typedef struct {
+  uint32_t struct_size;
+  uint32_t flags;               /* PASTA_DECODE_* */
+  int32_t layer;
+  int32_t n_streams;            /* n >= 1 */
+  const int32_t *request_id;    /* HOST [n] */
+  const int32_t *stream_id;     /* HOST [n]; (request, stream) pairs distinct */
+  const int32_t *position;      /* HOST [n] or NULL; carried, unused */
+  const int32_t *prefix_len;    /* HOST [n]   (explicit mode) */
+  const int32_t *range_offsets; /* HOST [n+1] (explicit mode) or NULL */
+  const int32_t *range_start;   /* HOST [range_offsets[n]] */
+  const int32_t *range_count;
+  const int32_t *range_stride;
+  const void *q;                /* DEVICE [n][Hq][D], pool dtype */
+  void *out;                    /* DEVICE [n][Hq][D], pool dtype (BF16: round to
+                                   nearest even from fp32 accumulators) */
+  float *out_lse;               /* DEVICE [n][Hq] or NULL: natural-log sum-exp */
+  int64_t *dbg_gather_offsets;  /* HOST [n+1] or NULL: out, CSR over the visited rows */
+  int32_t *dbg_gather_rows;     /* DEVICE [sum |Vis(s)|] or NULL: out, the PHYSICAL
+                                   row of every visited K row in list order, as
+                                   written by the kernels that read them (kv head 0) */
+  int64_t *dbg_plan;            /* HOST [8] or NULL: out, launch plan: {prefix tiles,
+                                   prefix work-groups, private items, partial rows,
+                                   tokens per prefix chunk, common-prefix tokens
+                                   summed over requests, metadata bytes, 0} */
+  void *prof_event_start;       /* hipEvent_t or NULL: recorded on the stream right */
+  void *prof_event_stop;        /* before / after the attention-partials kernel */
+} pasta_decode_args;
+
+/* Errors: E_INVAL (see above), E_STATE (unknown stream in maintained mode,
+ * layer out of range), E_CAPACITY (more ranges than max_ranges, workspace),
+ * E_DEVICE.  Validation is complete before anything is enqueued.  Device work
+ * is asynchronous on cfg.hip_stream; the call returns without synchronising. */
+int32_t pasta_attn_decode_step(pasta_attn *h, const pasta_decode_args *a);
+
+/* Frees host state only; does not synchronise (the caller synchronises before
+ * freeing pool / workspace).  NULL is a no-op.                               */
+int32_t pasta_attn_destroy(pasta_attn *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PASTA_ATTN_H */

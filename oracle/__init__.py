@@ -1,0 +1,20 @@
+"""fp64 CPU oracle of the multi-stream decode-attention step -- TEST INFRASTRUCTURE.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+package.  It shares nothing with the HIP library (no headers, helpers or tables).
+"""
+from .pasta_oracle import (  # noqa: F401
+    Geom,
+    append,
+    attention,
+    attention_dense,
+    build,
+    elem_offset,
+    gather_map,
+    merge,
+    num_threads,
+    partial,
+    phys_row,
+    rows_per_layer,
+    visible_dense,
+)
