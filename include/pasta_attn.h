@@ -114,12 +114,21 @@ int32_t pasta_attn_create(pasta_attn_config *cfg, pasta_attn **out);
  * in neighbouring slots and alternate; Figure 2c).
  * Row i takes logical slot tail[request_id[i]]++ in CALL ORDER -- call order
  * IS the physical interleave.  The same slots are used for every layer: the
- * caller issues the identical call once per layer (any layer order) and the
- * bookkeeping (tails, visibility lists) advances when layer == n_layers-1,
- * which must come last.  A token the interpreter defers (the paper's <sync/>
+ * call with layer == 0 comes first, assigns the slots and advances the
+ * bookkeeping (tails, visibility lists), so that a decode_step on layer 0 may
+ * follow at once; the identical call for each of the layers 1 .. n_layers-1
+ * (before the next layer-0 append) writes those layers' rows to the same slots
+ * and changes no state.  A token the interpreter defers (the paper's <sync/>
  * row) is simply not passed until it is to enter the pool.                   */
+enum {
+  PASTA_APPEND_RESERVE_ONLY = 1u /* assign slots and advance the bookkeeping, copy nothing:
+                                    the caller's own kernel writes the rows (out_slot says
+                                    where); k_new / v_new may be NULL */
+};
+
 typedef struct {
   uint32_t struct_size;
+  uint32_t flags;               /* PASTA_APPEND_* */
   int32_t layer;
   int32_t n_rows;               /* >= 0; 0 is a no-op */
   const int32_t *request_id;    /* HOST [n_rows], each in [0, max_requests) */
@@ -141,8 +150,8 @@ typedef struct {
 
 /* Errors: E_INVAL (NULL, ids out of range, parent unknown or equal to the
  * stream, parent given for a stream that is already open), E_CAPACITY (pool or
- * page table full; max_ranges exceeded), E_STATE (layer out of range),
- * E_DEVICE.  A failing call enqueues nothing and changes no state.           */
+ * page table full; max_ranges exceeded), E_STATE (layer out of range; a
+ * layer > 0 call that does not replay the latest layer-0 call), E_DEVICE.  A failing call enqueues nothing and changes no state.           */
 int32_t pasta_attn_append_kv(pasta_attn *h, const pasta_append_args *a);
 
 /* One decode step: one query token per active stream, all in one pass over

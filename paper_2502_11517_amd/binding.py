@@ -1,6 +1,231 @@
-# placeholder; replaced below
-class PastaAttn: ...
-class PastaError(Exception): ...
-def build_library(): ...
-def library_path(): ...
-def load_library(): ...
+"""Thin ctypes binding of libpasta_attn.so (include/pasta_attn.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; torch is used for device memory
+and the stream.  There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_LIB = os.path.join(_HERE, "libpasta_attn.so")
+_lib = None
+
+OK, E_INVAL, E_CAPACITY, E_NOMEM, E_DEVICE, E_STATE = 0, -1, -2, -3, -4, -5
+F32, BF16 = 0, 1
+TOKEN_MAJOR, HEAD_MAJOR = 0, 1
+DECODE_PLAN_ONLY, DECODE_NO_MFMA = 1, 2
+APPEND_RESERVE_ONLY = 1
+_ERR = {E_INVAL: "E_INVAL", E_CAPACITY: "E_CAPACITY", E_NOMEM: "E_NOMEM", E_DEVICE: "E_DEVICE",
+        E_STATE: "E_STATE"}
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+class PastaError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__(f"{where}: {_ERR.get(code, code)}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compiles csrc/pasta_attn.hip for gfx950 with hipcc (cross-compiles without a GPU)."""
+    src = os.path.join(_CSRC, "pasta_attn.hip")
+    cmd = ["hipcc", *HIPCC_FLAGS, src, "-o", _LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return _LIB
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("n_q_heads", C.c_int32),
+        ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("n_layers", C.c_int32),
+        ("max_requests", C.c_int32), ("page_tokens", C.c_int32), ("kv_layout", C.c_int32),
+        ("n_phys_pages", C.c_int32), ("pages_per_request", C.c_int32), ("max_streams", C.c_int32),
+        ("max_ranges", C.c_int32), ("softmax_scale", C.c_float), ("pool_tokens", C.c_int64),
+        ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("hip_stream", C.c_void_p),
+    ]
+
+
+class AppendArgs(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("layer", C.c_int32), ("n_rows", C.c_int32),
+        ("request_id", C.c_void_p), ("stream_id", C.c_void_p), ("parent_stream", C.c_void_p),
+        ("position", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p), ("out_slot", C.c_void_p),
+    ]
+
+
+class DecodeArgs(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("layer", C.c_int32), ("n_streams", C.c_int32),
+        ("request_id", C.c_void_p), ("stream_id", C.c_void_p), ("position", C.c_void_p),
+        ("prefix_len", C.c_void_p), ("range_offsets", C.c_void_p), ("range_start", C.c_void_p),
+        ("range_count", C.c_void_p), ("range_stride", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
+        ("out_lse", C.c_void_p), ("dbg_gather_offsets", C.c_void_p), ("dbg_gather_rows", C.c_void_p),
+        ("dbg_plan", C.c_void_p), ("prof_event_start", C.c_void_p), ("prof_event_stop", C.c_void_p),
+    ]
+
+
+def load_library():
+    """Loads the built library; raises if it is missing (there is no other path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            raise RuntimeError(f"{_LIB} is not built: run __graft_entry__.build() (hipcc, gfx950)")
+        # torch bundles its own HIP runtime under the same SONAME as /opt/rocm's; importing it
+        # first makes the loader bind this library to THAT runtime, so that torch's stream and
+        # device pointers are valid in the calls below (two runtimes in one process are not).
+        import torch  # noqa: F401
+        L = C.CDLL(_LIB)
+        L.pasta_attn_create.restype = C.c_int32
+        L.pasta_attn_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
+        L.pasta_attn_append_kv.restype = C.c_int32
+        L.pasta_attn_append_kv.argtypes = [C.c_void_p, C.POINTER(AppendArgs)]
+        L.pasta_attn_decode_step.restype = C.c_int32
+        L.pasta_attn_decode_step.argtypes = [C.c_void_p, C.POINTER(DecodeArgs)]
+        L.pasta_attn_destroy.restype = C.c_int32
+        L.pasta_attn_destroy.argtypes = [C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _hp(a):
+    return None if a is None else a.ctypes.data
+
+
+def _dp(t):
+    return None if t is None else (t if isinstance(t, int) else t.data_ptr())
+
+
+def make_config(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale, *, n_layers=1, max_requests=1,
+                page_tokens=0, kv_layout=TOKEN_MAJOR, n_phys_pages=0, pages_per_request=0,
+                max_streams=2, max_ranges=1024, pool_tokens=0) -> Config:
+    c = Config()
+    c.struct_size = C.sizeof(Config)
+    c.dtype = {"f32": F32, "bf16": BF16}.get(dtype, dtype)
+    c.n_q_heads, c.n_kv_heads, c.head_dim = n_q_heads, n_kv_heads, head_dim
+    c.n_layers, c.max_requests, c.page_tokens, c.kv_layout = n_layers, max_requests, page_tokens, kv_layout
+    c.n_phys_pages, c.pages_per_request = n_phys_pages, pages_per_request
+    c.max_streams, c.max_ranges, c.softmax_scale, c.pool_tokens = max_streams, max_ranges, softmax_scale, pool_tokens
+    return c
+
+
+def query_workspace_bytes(cfg: Config) -> int:
+    rc = load_library().pasta_attn_create(C.byref(cfg), None)
+    if rc != OK:
+        raise PastaError(rc, "pasta_attn_create(query)")
+    return int(cfg.workspace_bytes)
+
+
+class PastaAttn:
+    """One handle.  `k_pool`, `v_pool`, `workspace` are device addresses (or torch tensors) owned
+    by the caller; `stream` is a hipStream_t as an int (torch.cuda.current_stream().cuda_stream)."""
+
+    def __init__(self, cfg: Config, k_pool, v_pool, workspace, workspace_bytes, stream=0, page_table=None):
+        self._lib = load_library()
+        self.cfg = cfg
+        self._keep = [k_pool, v_pool, workspace]
+        pt = _i32(page_table)
+        cfg.k_pool, cfg.v_pool, cfg.workspace = _dp(k_pool), _dp(v_pool), _dp(workspace)
+        cfg.workspace_bytes = workspace_bytes
+        cfg.hip_stream = stream
+        cfg.page_table = _hp(pt)
+        h = C.c_void_p()
+        rc = self._lib.pasta_attn_create(C.byref(cfg), C.byref(h))
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_create")
+        self._h = h
+
+    def append_kv(self, layer, request_id, stream_id, k_new, v_new, parent_stream=None, position=None,
+                  want_slots=False, flags=0):
+        rid, sid, par, pos = _i32(request_id), _i32(stream_id), _i32(parent_stream), _i32(position)
+        n = 0 if rid is None else int(rid.shape[0])
+        slots = np.full(n, -1, np.int32) if want_slots else None
+        a = AppendArgs(C.sizeof(AppendArgs), flags, layer, n, _hp(rid), _hp(sid), _hp(par), _hp(pos), _dp(k_new),
+                       _dp(v_new), _hp(slots))
+        rc = self._lib.pasta_attn_append_kv(self._h, C.byref(a))
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_append_kv")
+        return slots
+
+    def decode_step(self, layer, request_id, stream_id, q, out, *, lists=None, out_lse=None, flags=0,
+                    position=None, dbg_gather_offsets=None, dbg_gather_rows=None, dbg_plan=None,
+                    prof_events=None):
+        """lists = (prefix_len, range_offsets, start, count, stride) for explicit visibility;
+        None uses the lists append_kv has maintained."""
+        rid, sid, pos = _i32(request_id), _i32(stream_id), _i32(position)
+        n = int(rid.shape[0])
+        if lists is not None:
+            pl, offs, st, ct, sd = (_i32(x) for x in lists)
+            if st.size == 0:  # keep valid addresses for empty arrays
+                st = ct = sd = np.zeros(1, np.int32)
+        else:
+            pl = offs = st = ct = sd = None
+        ev0, ev1 = prof_events if prof_events is not None else (None, None)
+        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, n, _hp(rid), _hp(sid), _hp(pos), _hp(pl), _hp(offs),
+                       _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), _hp(dbg_gather_offsets),
+                       _dp(dbg_gather_rows), _hp(dbg_plan), ev0, ev1)
+        rc = self._lib.pasta_attn_decode_step(self._h, C.byref(a))
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_decode_step")
+
+    # ---- prepared calls: marshal once, call many times (tight serving loops) ----
+    def prepare_append(self, layer, request_id, stream_id, k_new, v_new, parent_stream=None, flags=0):
+        """Returns f() -> status that issues this exact append; arrays are kept alive by f."""
+        rid, sid, par = _i32(request_id), _i32(stream_id), _i32(parent_stream)
+        a = AppendArgs(C.sizeof(AppendArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), _hp(par),
+                       None, _dp(k_new), _dp(v_new), None)
+        fn, h, ref = self._lib.pasta_attn_append_kv, self._h, C.byref(a)
+
+        def call(_keep=(rid, sid, par, a, k_new, v_new)):
+            return fn(h, ref)
+        return call
+
+    def prepare_decode(self, layer, request_id, stream_id, q, out, *, lists=None, out_lse=None, flags=0,
+                       prof_events=None):
+        rid, sid = _i32(request_id), _i32(stream_id)
+        if lists is not None:
+            pl, offs, st, ct, sd = (_i32(x) for x in lists)
+            if st.size == 0:
+                st = ct = sd = np.zeros(1, np.int32)
+        else:
+            pl = offs = st = ct = sd = None
+        ev0, ev1 = prof_events if prof_events is not None else (None, None)
+        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), None, _hp(pl),
+                       _hp(offs), _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), None, None, None,
+                       ev0, ev1)
+        fn, h, ref = self._lib.pasta_attn_decode_step, self._h, C.byref(a)
+
+        def call(_keep=(rid, sid, pl, offs, st, ct, sd, a, q, out, out_lse)):
+            return fn(h, ref)
+        return call
+
+    def destroy(self):
+        if self._h is not None:
+            self._lib.pasta_attn_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,41 @@
+// K1 -- KV-append scatter (arxiv 2502.11517, Section 3, "Efficiency"; Figure 2c):
+// every active thread's new K/V row goes to the next free slot of the shared pool, so rows
+// of concurrently decoding threads end up in neighbouring slots.  A pure copy: each lane
+// moves one 16-byte piece of one (row, kv head) from k_new/v_new to its pool position.
+#pragma once
+#include "pasta_dev.hpp"
+
+namespace pasta {
+
+constexpr int kAppendInline = 32;  // destination rows that travel in the kernel arguments
+
+struct AppendParams {
+  const uint4* k_new;   // [n_rows][Hkv][D] as 16-byte pieces
+  const uint4* v_new;
+  void* k;              // layer base
+  void* v;
+  const int32_t* dst_rows;           // physical row per appended row (device), or null:
+  int32_t inline_rows[kAppendInline];  // then the rows are here
+  Layout lay;
+  int n_rows, Hkv;
+  int pieces_per_head;  // D * elem_bytes / 16
+  int elem_shift;       // log2(elem_bytes)
+};
+
+__global__ __launch_bounds__(256) void k_append(AppendParams p) {
+  const long long total = (long long)p.n_rows * p.Hkv * p.pieces_per_head;
+  long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= 2 * total) return;
+  const bool is_v = t >= total;
+  if (is_v) t -= total;
+  const int piece = (int)(t % p.pieces_per_head);
+  const long long rh = t / p.pieces_per_head;
+  const int g = (int)(rh % p.Hkv);
+  const int row = (int)(rh / p.Hkv);
+  const int phys = p.dst_rows ? p.dst_rows[row] : p.inline_rows[row];
+  const long long off_bytes = (elem_off(p.lay, phys, g) << p.elem_shift) + (long long)piece * 16;
+  const uint4 val = (is_v ? p.v_new : p.k_new)[t];
+  *reinterpret_cast<uint4*>(reinterpret_cast<char*>(is_v ? p.v : p.k) + off_bytes) = val;
+}
+
+}  // namespace pasta

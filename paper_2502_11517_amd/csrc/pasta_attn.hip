@@ -1,0 +1,665 @@
+// C-ABI library of the multi-stream decode-attention step (include/pasta_attn.h).
+// Host side: argument validation, the visibility lists kept per (request, stream)
+// (arxiv 2502.11517, Section 3 "Efficiency": ancestor rule of Figure 2b), slot assignment
+// at the pool tail (Figure 2c), and the launch plan.  Every step of the arithmetic runs in
+// the gfx950 kernels included below.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/pasta_attn.h"
+#include "k_append.hpp"
+#include "k_merge.hpp"
+#include "k_prefix.hpp"
+#include "k_private.hpp"
+
+using namespace pasta;
+
+namespace {
+
+constexpr uint32_t kMagic = 0x50415354u;  // "PAST"
+constexpr int kRing = 8;                  // metadata staging buffers in flight
+constexpr int kTargetPrefixWgs = 512;     // split-K parallelism aimed for (2 per CU)
+
+struct Range { int32_t start, count, stride; };
+
+struct StreamState {
+  bool open = false;
+  int32_t prefix_len = 0;        // visible head [0, prefix_len)
+  std::vector<Range> ranges;     // then these, span-ascending
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct pasta_attn {
+  uint32_t magic = kMagic;
+  pasta_attn_config cfg{};
+  int G = 1, elem = 2, page_shift = 31;
+  int64_t rows_per_layer = 0, layer_elems = 0, req_capacity = 0;
+  Layout lay{};
+  std::vector<int32_t> page_table;
+  std::vector<int64_t> tail;             // per request
+  std::vector<int64_t> tail_before;      // tails before the latest layer-0 append
+  std::vector<StreamState> streams;      // [max_requests * max_streams]
+  // workspace carve-up (byte offsets)
+  size_t off_page_table = 0, off_meta = 0, meta_bytes = 0, off_ml = 0, off_acc = 0;
+  int64_t part_rows_cap = 0;
+  // device-side readiness (deferred so that the host logic works without a GPU)
+  bool device_ready = false;
+  char* pinned = nullptr;                // kRing * meta_bytes
+  hipEvent_t ring_ev[kRing]{};
+  bool ring_used[kRing]{};
+  int ring_next = 0;
+};
+
+namespace {
+
+int64_t meta_words_cap(const pasta_attn_config& c) {
+  // streams + reqs + req_streams + ranges (+1 per stream for the uncommon prefix tail) + items
+  const int64_t ns = (int64_t)c.max_requests * c.max_streams;
+  const int64_t ranges = (int64_t)c.max_ranges + ns;
+  const int64_t cap_tokens = c.page_tokens ? (int64_t)c.pages_per_request * c.page_tokens : c.pool_tokens;
+  // items: every stream can split its private list into chunks; bounded by total tokens/chunk + streams
+  const int64_t items = ns * ((cap_tokens + kPrivChunk - 1) / kPrivChunk + 1);
+  return ns * (int64_t)(sizeof(DevStream) / 4) + (int64_t)c.max_requests * (sizeof(DevReq) / 4) + ns +
+         ranges * 4 + std::min<int64_t>(items, (int64_t)1 << 22) * 4 + 64;
+}
+
+int validate_cfg(const pasta_attn_config* c) {
+  if (!c || c->struct_size != sizeof(pasta_attn_config)) return PASTA_E_INVAL;
+  if (c->dtype != PASTA_F32 && c->dtype != PASTA_BF16) return PASTA_E_INVAL;
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return PASTA_E_INVAL;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return PASTA_E_INVAL;
+  if (c->head_dim != 64 && c->head_dim != 128) return PASTA_E_INVAL;
+  if (c->n_layers < 1 || c->max_requests < 1 || c->max_streams < 1 || c->max_ranges < 1) return PASTA_E_INVAL;
+  if (c->kv_layout != PASTA_LAYOUT_TOKEN_MAJOR && c->kv_layout != PASTA_LAYOUT_HEAD_MAJOR) return PASTA_E_INVAL;
+  if (!(c->softmax_scale > 0.f) || !std::isfinite(c->softmax_scale)) return PASTA_E_INVAL;
+  if (c->page_tokens == 0) {
+    if (c->pool_tokens < 1) return PASTA_E_INVAL;
+    if ((int64_t)c->max_requests * c->pool_tokens >= ((int64_t)1 << 31)) return PASTA_E_INVAL;
+  } else {
+    if (c->page_tokens < 1 || (c->page_tokens & (c->page_tokens - 1))) return PASTA_E_INVAL;
+    if (c->n_phys_pages < 1 || c->pages_per_request < 1) return PASTA_E_INVAL;
+    if ((int64_t)c->n_phys_pages * c->page_tokens >= ((int64_t)1 << 31)) return PASTA_E_INVAL;
+  }
+  return PASTA_OK;
+}
+
+// Partial-row budget: enough for the split-K parallelism aimed for at the largest stacked
+// row count, plus one row per (private item, query head).
+int64_t part_rows_budget(const pasta_attn_config& c) {
+  const int64_t ns = (int64_t)c.max_requests * c.max_streams;
+  const int64_t cap_tokens = c.page_tokens ? (int64_t)c.pages_per_request * c.page_tokens : c.pool_tokens;
+  const int64_t prefix = (int64_t)(kTargetPrefixWgs + c.n_kv_heads * c.max_requests) * c.max_streams *
+                         (c.n_q_heads / c.n_kv_heads) * 2;
+  const int64_t items = std::min<int64_t>(ns * ((cap_tokens + kPrivChunk - 1) / kPrivChunk + 1),
+                                          (int64_t)c.max_requests * cap_tokens / 16 + ns * 2);
+  return prefix + items * c.n_q_heads;
+}
+
+void carve(pasta_attn* h) {
+  const pasta_attn_config& c = h->cfg;
+  size_t off = 0;
+  h->off_page_table = off;
+  off += align_up((size_t)c.max_requests * (c.page_tokens ? c.pages_per_request : 0) * 4 + 4, 256);
+  h->meta_bytes = align_up((size_t)meta_words_cap(c) * 4, 256);
+  h->off_meta = off;
+  off += h->meta_bytes * kRing;
+  h->part_rows_cap = part_rows_budget(c);
+  h->off_ml = off;
+  off += align_up((size_t)h->part_rows_cap * sizeof(float2), 256);
+  h->off_acc = off;
+  off += align_up((size_t)h->part_rows_cap * c.head_dim * sizeof(float), 256);
+  h->cfg.workspace_bytes = off;
+}
+
+int ensure_device(pasta_attn* h) {
+  if (h->device_ready) return PASTA_OK;
+  if (hipHostMalloc((void**)&h->pinned, h->meta_bytes * kRing, hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    h->pinned = nullptr;
+    return PASTA_E_DEVICE;
+  }
+  for (int i = 0; i < kRing; ++i)
+    if (hipEventCreateWithFlags(&h->ring_ev[i], hipEventDisableTiming) != hipSuccess) return PASTA_E_DEVICE;
+  if (h->cfg.page_tokens) {
+    if (hipMemcpy((char*)h->cfg.workspace + h->off_page_table, h->page_table.data(),
+                  h->page_table.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
+      return PASTA_E_DEVICE;
+  }
+  h->device_ready = true;
+  return PASTA_OK;
+}
+
+// Copies `bytes` of host metadata to the next device staging slot, asynchronously on the
+// caller's stream; returns the device address.  A slot is reused only after the copy that
+// last read its pinned half has completed.
+int upload_meta(pasta_attn* h, const void* src, size_t bytes, const int32_t** dev_out) {
+  if (bytes > h->meta_bytes) return PASTA_E_CAPACITY;
+  const int s = h->ring_next;
+  h->ring_next = (s + 1) % kRing;
+  if (h->ring_used[s] && hipEventSynchronize(h->ring_ev[s]) != hipSuccess) return PASTA_E_DEVICE;
+  char* host = h->pinned + (size_t)s * h->meta_bytes;
+  std::memcpy(host, src, bytes);
+  char* dev = (char*)h->cfg.workspace + h->off_meta + (size_t)s * h->meta_bytes;
+  hipStream_t st = (hipStream_t)h->cfg.hip_stream;
+  if (hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, st) != hipSuccess) return PASTA_E_DEVICE;
+  if (hipEventRecord(h->ring_ev[s], st) != hipSuccess) return PASTA_E_DEVICE;
+  h->ring_used[s] = true;
+  *dev_out = (const int32_t*)dev;
+  return PASTA_OK;
+}
+
+inline StreamState& sstate(pasta_attn* h, int req, int sid) {
+  return h->streams[(size_t)req * h->cfg.max_streams + sid];
+}
+
+// logical slot -> physical row on the host (same formula as the header states)
+inline int64_t host_phys(const pasta_attn* h, int req, int64_t slot) {
+  if (!h->cfg.page_tokens) return (int64_t)req * h->cfg.pool_tokens + slot;
+  const int64_t pp = h->page_table[(size_t)req * h->cfg.pages_per_request + (slot >> h->page_shift)];
+  return (pp << h->page_shift) | (slot & (h->cfg.page_tokens - 1));
+}
+
+// Adds an owned slot to a stream's list (slots arrive in increasing order).
+void add_slot(StreamState& s, int32_t slot) {
+  if (s.ranges.empty() && slot == s.prefix_len) { s.prefix_len++; return; }
+  if (!s.ranges.empty()) {
+    Range& r = s.ranges.back();
+    if (r.count == 1 && slot > r.start) { r.stride = slot - r.start; r.count = 2; return; }
+    if (slot == r.start + (int64_t)r.count * r.stride) { r.count++; return; }
+  }
+  s.ranges.push_back({slot, 1, 1});
+}
+
+template <typename T, int D>
+int launch_private_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
+  switch (G) {
+    case 1: k_private<T, D, 1><<<grid, 256, 0, st>>>(p); break;
+    case 2: k_private<T, D, 2><<<grid, 256, 0, st>>>(p); break;
+    case 4: k_private<T, D, 4><<<grid, 256, 0, st>>>(p); break;
+    case 8: k_private<T, D, 8><<<grid, 256, 0, st>>>(p); break;
+    default: return PASTA_E_INVAL;
+  }
+  return PASTA_OK;
+}
+template <typename T, int D>
+int launch_merge_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
+  switch (G) {
+    case 1: k_merge<T, D, 1><<<grid, 256, 0, st>>>(p); break;
+    case 2: k_merge<T, D, 2><<<grid, 256, 0, st>>>(p); break;
+    case 4: k_merge<T, D, 4><<<grid, 256, 0, st>>>(p); break;
+    case 8: k_merge<T, D, 8><<<grid, 256, 0, st>>>(p); break;
+    default: return PASTA_E_INVAL;
+  }
+  return PASTA_OK;
+}
+
+int launch_private(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {
+  const int D = h->cfg.head_dim;
+  if (h->cfg.dtype == PASTA_F32)
+    return D == 64 ? launch_private_g<float, 64>(h->G, grid, st, p) : launch_private_g<float, 128>(h->G, grid, st, p);
+  return D == 64 ? launch_private_g<uint16_t, 64>(h->G, grid, st, p)
+                 : launch_private_g<uint16_t, 128>(h->G, grid, st, p);
+}
+int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {
+  const int D = h->cfg.head_dim;
+  if (h->cfg.dtype == PASTA_F32)
+    return D == 64 ? launch_merge_g<float, 64>(h->G, grid, st, p) : launch_merge_g<float, 128>(h->G, grid, st, p);
+  return D == 64 ? launch_merge_g<uint16_t, 64>(h->G, grid, st, p) : launch_merge_g<uint16_t, 128>(h->G, grid, st, p);
+}
+
+}  // namespace
+
+// =============================================================================== create
+extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
+  int rc = validate_cfg(cfg);
+  if (rc != PASTA_OK) return rc;
+  pasta_attn* h = new (std::nothrow) pasta_attn();
+  if (!h) return PASTA_E_NOMEM;
+  h->cfg = *cfg;
+  h->G = cfg->n_q_heads / cfg->n_kv_heads;
+  h->elem = cfg->dtype == PASTA_F32 ? 4 : 2;
+  const int64_t D = cfg->head_dim, H = cfg->n_kv_heads;
+  if (cfg->page_tokens) {
+    h->page_shift = 0;
+    while ((1 << h->page_shift) < cfg->page_tokens) h->page_shift++;
+    h->rows_per_layer = (int64_t)cfg->n_phys_pages * cfg->page_tokens;
+    h->req_capacity = (int64_t)cfg->pages_per_request * cfg->page_tokens;
+  } else {
+    h->rows_per_layer = (int64_t)cfg->max_requests * cfg->pool_tokens;
+    h->req_capacity = cfg->pool_tokens;
+  }
+  h->layer_elems = h->rows_per_layer * H * D;
+  Layout& L = h->lay;
+  L.paged = cfg->page_tokens ? 1 : 0;
+  L.pages_per_request = cfg->pages_per_request;
+  L.pool_tokens = (int)cfg->pool_tokens;
+  L.page_shift = cfg->page_tokens ? h->page_shift : 31;
+  L.page_mask = cfg->page_tokens ? cfg->page_tokens - 1 : 0x7fffffff;
+  if (cfg->kv_layout == PASTA_LAYOUT_TOKEN_MAJOR) {
+    L.slot_stride = (int)(H * D);
+    L.head_stride = D;
+    L.page_stride = cfg->page_tokens ? (int64_t)cfg->page_tokens * H * D : 0;
+  } else if (!cfg->page_tokens) {
+    L.slot_stride = (int)D;
+    L.head_stride = h->rows_per_layer * D;
+    L.page_stride = 0;
+  } else {
+    L.slot_stride = (int)D;
+    L.head_stride = (int64_t)cfg->page_tokens * D;
+    L.page_stride = (int64_t)cfg->page_tokens * H * D;
+  }
+  const uint64_t given = cfg->workspace_bytes;
+  carve(h);
+  if (!out) {  // query mode
+    cfg->workspace_bytes = h->cfg.workspace_bytes;
+    delete h;
+    return PASTA_OK;
+  }
+  auto fail = [&](int code) { delete h; return code; };
+  if (!cfg->k_pool || !cfg->v_pool || !cfg->workspace) return fail(PASTA_E_INVAL);
+  if (((uintptr_t)cfg->workspace & 255) || ((uintptr_t)cfg->k_pool & 15) || ((uintptr_t)cfg->v_pool & 15))
+    return fail(PASTA_E_INVAL);
+  if (given < h->cfg.workspace_bytes) return fail(PASTA_E_CAPACITY);
+  h->cfg.workspace_bytes = given;
+  if (cfg->page_tokens) {
+    if (!cfg->page_table) return fail(PASTA_E_INVAL);
+    const size_t n = (size_t)cfg->max_requests * cfg->pages_per_request;
+    h->page_table.assign(cfg->page_table, cfg->page_table + n);
+    for (int32_t pp : h->page_table)
+      if (pp < 0 || pp >= cfg->n_phys_pages) return fail(PASTA_E_INVAL);
+    h->cfg.page_table = nullptr;  // the caller's array is not kept
+  }
+  try {
+    h->tail.assign(cfg->max_requests, 0);
+    h->tail_before.assign(cfg->max_requests, 0);
+    h->streams.resize((size_t)cfg->max_requests * cfg->max_streams);
+  } catch (...) { return fail(PASTA_E_NOMEM); }
+  *out = h;
+  return PASTA_OK;
+}
+
+extern "C" int32_t pasta_attn_destroy(pasta_attn* h) {
+  if (!h) return PASTA_OK;
+  if (h->magic != kMagic) return PASTA_E_STATE;
+  h->magic = 0;
+  if (h->device_ready) {
+    for (int i = 0; i < kRing; ++i) (void)hipEventDestroy(h->ring_ev[i]);
+  }
+  if (h->pinned) (void)hipHostFree(h->pinned);
+  delete h;
+  return PASTA_OK;
+}
+
+// =============================================================================== append
+extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* a) {
+  if (!h || h->magic != kMagic) return PASTA_E_STATE;
+  if (!a || a->struct_size != sizeof(pasta_append_args)) return PASTA_E_INVAL;
+  const pasta_attn_config& c = h->cfg;
+  if (a->layer < 0 || a->layer >= c.n_layers) return PASTA_E_STATE;
+  if (a->n_rows < 0) return PASTA_E_INVAL;
+  if (a->n_rows == 0) return PASTA_OK;
+  const bool reserve_only = a->flags & PASTA_APPEND_RESERVE_ONLY;
+  if (!a->request_id || !a->stream_id) return PASTA_E_INVAL;
+  if (!reserve_only && (!a->k_new || !a->v_new)) return PASTA_E_INVAL;
+  if (!reserve_only && (((uintptr_t)a->k_new & 15) || ((uintptr_t)a->v_new & 15))) return PASTA_E_INVAL;
+  const bool commit = a->layer == 0;  // layer 0 assigns the slots; other layers replay them
+
+  // ---- dry run on copies of the touched state
+  std::unordered_map<int64_t, StreamState> touched;
+  std::vector<int64_t> t2;
+  std::vector<int32_t> dst_rows, slots;
+  try {
+    t2 = commit ? h->tail : h->tail_before;
+    dst_rows.resize(a->n_rows);
+    slots.resize(a->n_rows);
+    auto view = [&](int req, int sid) -> StreamState& {
+      const int64_t key = (int64_t)req * c.max_streams + sid;
+      auto it = touched.find(key);
+      if (it == touched.end()) it = touched.emplace(key, sstate(h, req, sid)).first;
+      return it->second;
+    };
+    for (int i = 0; i < a->n_rows; ++i) {
+      const int r = a->request_id[i], s = a->stream_id[i];
+      const int par = a->parent_stream ? a->parent_stream[i] : -1;
+      if (r < 0 || r >= c.max_requests || s < 0 || s >= c.max_streams) return PASTA_E_INVAL;
+      if (par < -1 || par >= c.max_streams || par == s) return PASTA_E_INVAL;
+      const int64_t slot = t2[r];
+      if (slot >= h->req_capacity) return PASTA_E_CAPACITY;
+      if (!commit) {  // replay: same slots as the layer-0 call, lists untouched
+        if (slot >= h->tail[r]) return PASTA_E_STATE;
+        slots[i] = (int32_t)slot;
+        dst_rows[i] = (int32_t)host_phys(h, r, slot);
+        t2[r] = slot + 1;
+        continue;
+      }
+      StreamState& st = view(r, s);
+      if (par >= 0) {
+        if (st.open) return PASTA_E_INVAL;          // parent only on the row that opens the stream
+        const StreamState& ps = view(r, par);       // may rehash: re-fetch st below
+        if (!ps.open) return PASTA_E_INVAL;
+        StreamState& st2 = view(r, s);
+        st2.prefix_len = ps.prefix_len;             // ancestor rule: inherit what the parent sees now
+        st2.ranges = ps.ranges;
+        st2.open = true;
+      } else if (!st.open) {
+        st.open = true;                             // root: empty visible set
+        st.prefix_len = 0;
+        st.ranges.clear();
+      }
+      StreamState& cur = view(r, s);
+      add_slot(cur, (int32_t)slot);
+      if ((int64_t)cur.ranges.size() > c.max_ranges) return PASTA_E_CAPACITY;
+      slots[i] = (int32_t)slot;
+      dst_rows[i] = (int32_t)host_phys(h, r, slot);
+      t2[r] = slot + 1;
+    }
+  } catch (...) { return PASTA_E_NOMEM; }
+
+  // ---- enqueue K1
+  int rc = PASTA_OK;
+  if (!reserve_only) {
+  rc = ensure_device(h);
+  if (rc != PASTA_OK) return rc;
+  hipStream_t st = (hipStream_t)c.hip_stream;
+  AppendParams p{};
+  p.k_new = (const uint4*)a->k_new;
+  p.v_new = (const uint4*)a->v_new;
+  p.k = (char*)c.k_pool + (size_t)a->layer * h->layer_elems * h->elem;
+  p.v = (char*)c.v_pool + (size_t)a->layer * h->layer_elems * h->elem;
+  p.lay = h->lay;
+  p.n_rows = a->n_rows;
+  p.Hkv = c.n_kv_heads;
+  p.pieces_per_head = c.head_dim * h->elem / 16;
+  p.elem_shift = h->elem == 4 ? 2 : 1;
+  if (a->n_rows <= kAppendInline) {
+    p.dst_rows = nullptr;
+    std::memcpy(p.inline_rows, dst_rows.data(), (size_t)a->n_rows * 4);
+    const long long total = 2ll * a->n_rows * c.n_kv_heads * p.pieces_per_head;
+    k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p);
+    if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
+  } else {
+    // large appends (prefill) go in pieces that fit one staging slot
+    const size_t per = h->meta_bytes / 4;
+    for (size_t lo = 0; lo < (size_t)a->n_rows; lo += per) {
+      const size_t n = std::min(per, (size_t)a->n_rows - lo);
+      const int32_t* dev = nullptr;
+      rc = upload_meta(h, dst_rows.data() + lo, n * 4, &dev);
+      if (rc != PASTA_OK) return rc;
+      AppendParams q = p;
+      q.dst_rows = dev;
+      q.n_rows = (int)n;
+      const size_t row_bytes = (size_t)c.n_kv_heads * c.head_dim * h->elem;
+      q.k_new = (const uint4*)((const char*)a->k_new + lo * row_bytes);
+      q.v_new = (const uint4*)((const char*)a->v_new + lo * row_bytes);
+      const long long total = 2ll * (long long)n * c.n_kv_heads * p.pieces_per_head;
+      k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(q);
+      if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
+    }
+  }
+  }
+
+  // ---- commit
+  if (a->out_slot) std::memcpy(a->out_slot, slots.data(), (size_t)a->n_rows * 4);
+  if (commit) {
+    h->tail_before = h->tail;
+    h->tail.swap(t2);
+    for (auto& kv : touched) h->streams[(size_t)kv.first] = std::move(kv.second);
+  }
+  return PASTA_OK;
+}
+
+// =============================================================================== decode
+namespace {
+
+struct ListView {  // one stream's visible list for this call
+  int32_t prefix_len;
+  const Range* ranges;   // maintained mode
+  int32_t n_ranges;
+  const int32_t *start, *count, *stride;  // explicit mode (ranges == nullptr)
+  Range at(int k) const { return ranges ? ranges[k] : Range{start[k], count[k], stride[k]}; }
+};
+
+}  // namespace
+
+extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args* a) {
+  if (!h || h->magic != kMagic) return PASTA_E_STATE;
+  if (!a || a->struct_size != sizeof(pasta_decode_args)) return PASTA_E_INVAL;
+  const pasta_attn_config& c = h->cfg;
+  if (a->layer < 0 || a->layer >= c.n_layers) return PASTA_E_STATE;
+  const int n = a->n_streams;
+  if (n < 1 || n > c.max_requests * c.max_streams) return PASTA_E_INVAL;
+  if (!a->request_id || !a->stream_id) return PASTA_E_INVAL;
+  const bool plan_only = a->flags & PASTA_DECODE_PLAN_ONLY;
+  if (!plan_only && (!a->q || !a->out)) return PASTA_E_INVAL;
+  if (!plan_only && (((uintptr_t)a->q & 15) || ((uintptr_t)a->out & 3))) return PASTA_E_INVAL;
+  const bool explicit_mode = a->range_offsets != nullptr;
+  if (explicit_mode && !a->prefix_len) return PASTA_E_INVAL;
+  const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
+
+  try {
+    // ---- lists + validation
+    std::vector<ListView> lv(n);
+    std::vector<uint8_t> seen((size_t)c.max_requests * c.max_streams, 0);
+    int64_t total_ranges = 0;
+    for (int i = 0; i < n; ++i) {
+      const int r = a->request_id[i], s = a->stream_id[i];
+      if (r < 0 || r >= c.max_requests || s < 0 || s >= c.max_streams) return PASTA_E_INVAL;
+      uint8_t& sn = seen[(size_t)r * c.max_streams + s];
+      if (sn) return PASTA_E_INVAL;
+      sn = 1;
+      ListView& v = lv[i];
+      if (explicit_mode) {
+        const int32_t r0 = a->range_offsets[i], r1 = a->range_offsets[i + 1];
+        if (r0 < 0 || r1 < r0 || (i == 0 && r0 != 0)) return PASTA_E_INVAL;
+        if (r1 > r0 && (!a->range_start || !a->range_count || !a->range_stride)) return PASTA_E_INVAL;
+        v = ListView{a->prefix_len[i], nullptr, r1 - r0, a->range_start + r0, a->range_count + r0,
+                     a->range_stride + r0};
+        const int64_t tail = h->tail[r];
+        if (v.prefix_len < 0 || v.prefix_len > tail) return PASTA_E_INVAL;
+        int64_t last = (int64_t)v.prefix_len - 1;
+        for (int k = 0; k < v.n_ranges; ++k) {
+          const Range g = v.at(k);
+          if (g.count < 1 || g.stride < 1 || g.start <= last) return PASTA_E_INVAL;
+          last = (int64_t)g.start + (int64_t)(g.count - 1) * g.stride;
+          if (last >= tail) return PASTA_E_INVAL;
+        }
+        if (v.prefix_len == 0 && v.n_ranges == 0) return PASTA_E_INVAL;
+      } else {
+        const StreamState& ss = sstate(h, r, s);
+        if (!ss.open) return PASTA_E_STATE;
+        v = ListView{ss.prefix_len, ss.ranges.data(), (int32_t)ss.ranges.size(), nullptr, nullptr, nullptr};
+        if (v.prefix_len == 0 && v.n_ranges == 0) return PASTA_E_INVAL;
+      }
+      total_ranges += v.n_ranges;
+    }
+    if (total_ranges > c.max_ranges) return PASTA_E_CAPACITY;
+
+    // ---- group by request (order of first appearance)
+    std::vector<int32_t> req_idx_of(c.max_requests, -1);
+    std::vector<DevReq> reqs;
+    std::vector<int32_t> stream_req_idx(n), stream_local(n);
+    for (int i = 0; i < n; ++i) {
+      const int r = a->request_id[i];
+      if (req_idx_of[r] < 0) {
+        req_idx_of[r] = (int32_t)reqs.size();
+        DevReq q{};
+        q.req = r;
+        q.pc = INT32_MAX;
+        reqs.push_back(q);
+      }
+      DevReq& q = reqs[req_idx_of[r]];
+      stream_req_idx[i] = req_idx_of[r];
+      stream_local[i] = q.n_streams++;
+      q.pc = std::min(q.pc, lv[i].prefix_len);
+    }
+    std::vector<int32_t> req_streams(n);
+    {
+      int32_t pos = 0;
+      for (auto& q : reqs) { q.stream0 = pos; pos += q.n_streams; }
+      for (int i = 0; i < n; ++i) req_streams[reqs[stream_req_idx[i]].stream0 + stream_local[i]] = i;
+    }
+
+    // ---- shared-prefix plan: only what the MFMA kernel takes; the rest is private
+    const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && prefix_kernel_supports(D, G);
+    int64_t pc_total = 0, max_rows = 1;
+    for (auto& q : reqs) {
+      if (!mfma || q.pc < kPrefixTile || q.n_streams * G > kPrefixMaxRows) q.pc = 0;
+      pc_total += q.pc;
+      if (q.pc) max_rows = std::max<int64_t>(max_rows, (int64_t)q.n_streams * G);
+    }
+    // private items
+    std::vector<DevStream> streams(n);
+    std::vector<DevRange> ranges;
+    std::vector<DevItem> items;
+    ranges.reserve((size_t)total_ranges + n);
+    int64_t gather_total = 0;
+    for (int i = 0; i < n; ++i) {
+      DevStream& ds = streams[i];
+      const DevReq& q = reqs[stream_req_idx[i]];
+      ds.req = q.req;
+      ds.req_idx = stream_req_idx[i];
+      ds.local = stream_local[i];
+      ds.pc = q.pc;
+      ds.range_begin = (int32_t)ranges.size();
+      int32_t cum = 0;
+      if (lv[i].prefix_len > q.pc) {
+        ranges.push_back({q.pc, lv[i].prefix_len - q.pc, 1, 0});
+        cum = lv[i].prefix_len - q.pc;
+      }
+      for (int k = 0; k < lv[i].n_ranges; ++k) {
+        const Range g = lv[i].at(k);
+        ranges.push_back({g.start, g.count, g.stride, cum});
+        cum += g.count;
+      }
+      ds.range_end = (int32_t)ranges.size();
+      ds.item_begin = (int32_t)items.size();
+      int32_t rcur = ds.range_begin;
+      for (int32_t t = 0; t < cum; t += kPrivChunk) {
+        while (rcur + 1 < ds.range_end && ranges[rcur + 1].cum <= t) rcur++;
+        items.push_back({i, t, std::min<int32_t>(kPrivChunk, cum - t), rcur});
+      }
+      ds.item_end = (int32_t)items.size();
+      if (gather_total + q.pc + cum > INT32_MAX) return PASTA_E_CAPACITY;
+      ds.gather_base = (int32_t)gather_total;
+      if (a->dbg_gather_offsets) a->dbg_gather_offsets[i] = gather_total;
+      gather_total += (int64_t)q.pc + cum;
+    }
+    if (a->dbg_gather_offsets) a->dbg_gather_offsets[n] = gather_total;
+
+    // split-K chunking: tokens per chunk, a multiple of the LDS tile, chosen so that the
+    // prefix work-groups number about kTargetPrefixWgs and the partial rows fit the workspace
+    const int64_t priv_rows = (int64_t)items.size() * c.n_q_heads;
+    int64_t chunk_tokens = kPrefixTile, n_prefix_wgs = 0, prefix_rows = 0;
+    if (pc_total > 0) {
+      const int64_t tiles_total = (pc_total + kPrefixTile - 1) / kPrefixTile * Hkv;
+      int64_t tiles_per_wg = std::max<int64_t>(1, tiles_total / kTargetPrefixWgs);
+      for (;; ++tiles_per_wg) {
+        chunk_tokens = tiles_per_wg * kPrefixTile;
+        n_prefix_wgs = 0;
+        prefix_rows = 0;
+        for (auto& q : reqs) {
+          q.n_chunks = q.pc ? (int32_t)((q.pc + chunk_tokens - 1) / chunk_tokens) : 0;
+          q.chunk_tokens = (int32_t)chunk_tokens;
+          q.wg_begin = (int32_t)n_prefix_wgs;
+          q.part_base = (int32_t)prefix_rows;
+          n_prefix_wgs += (int64_t)q.n_chunks * Hkv;
+          prefix_rows += (int64_t)q.n_chunks * Hkv * q.n_streams * G;
+        }
+        if (prefix_rows + priv_rows <= h->part_rows_cap) break;
+        if (chunk_tokens > (int64_t)1 << 30) return PASTA_E_CAPACITY;
+      }
+    } else {
+      for (auto& q : reqs) { q.n_chunks = 0; q.chunk_tokens = kPrefixTile; q.wg_begin = 0; q.part_base = 0; }
+      if (priv_rows > h->part_rows_cap) return PASTA_E_CAPACITY;
+    }
+
+    // ---- metadata blob
+    std::vector<int32_t> blob;
+    DecodeParams p{};
+    auto put = [&](const void* src, size_t bytes) -> int {
+      const int off = (int)blob.size();
+      blob.resize(blob.size() + (bytes + 3) / 4);
+      if (bytes) std::memcpy(blob.data() + off, src, bytes);
+      return off;
+    };
+    p.off_streams = put(streams.data(), streams.size() * sizeof(DevStream));
+    p.off_reqs = put(reqs.data(), reqs.size() * sizeof(DevReq));
+    p.off_req_streams = put(req_streams.data(), req_streams.size() * 4);
+    p.off_ranges = put(ranges.data(), ranges.size() * sizeof(DevRange));
+    p.off_items = put(items.data(), items.size() * sizeof(DevItem));
+    if (blob.size() * 4 > h->meta_bytes) return PASTA_E_CAPACITY;
+
+    if (a->dbg_plan) {
+      int64_t tiles = 0;
+      for (auto& q : reqs) tiles += (int64_t)(q.pc + kPrefixTile - 1) / kPrefixTile * Hkv;
+      a->dbg_plan[0] = tiles;
+      a->dbg_plan[1] = n_prefix_wgs;
+      a->dbg_plan[2] = (int64_t)items.size();
+      a->dbg_plan[3] = prefix_rows + priv_rows;
+      a->dbg_plan[4] = pc_total ? chunk_tokens : 0;
+      a->dbg_plan[5] = pc_total;
+      a->dbg_plan[6] = (int64_t)blob.size() * 4;
+      a->dbg_plan[7] = 0;
+    }
+    if (plan_only) return PASTA_OK;
+
+    // ---- enqueue
+    int rc = ensure_device(h);
+    if (rc != PASTA_OK) return rc;
+    hipStream_t st = (hipStream_t)c.hip_stream;
+    const int32_t* dev_meta = nullptr;
+    rc = upload_meta(h, blob.data(), blob.size() * 4, &dev_meta);
+    if (rc != PASTA_OK) return rc;
+    p.k = (const char*)c.k_pool + (size_t)a->layer * h->layer_elems * h->elem;
+    p.v = (const char*)c.v_pool + (size_t)a->layer * h->layer_elems * h->elem;
+    p.q = a->q;
+    p.out = a->out;
+    p.lse = a->out_lse;
+    p.dbg_rows = a->dbg_gather_rows;
+    p.meta = dev_meta;
+    p.page_table = (const int32_t*)((const char*)c.workspace + h->off_page_table);
+    p.part_acc = (float*)((char*)c.workspace + h->off_acc);
+    p.part_ml = (float2*)((char*)c.workspace + h->off_ml);
+    p.lay = h->lay;
+    p.n_streams = n;
+    p.n_reqs = (int)reqs.size();
+    p.n_items = (int)items.size();
+    p.n_prefix_wgs = (int)n_prefix_wgs;
+    p.priv_part_base = (int)prefix_rows;
+    p.Hq = c.n_q_heads;
+    p.Hkv = Hkv;
+    p.scale_log2e = c.softmax_scale * kLog2e;
+
+    if (a->prof_event_start && hipEventRecord((hipEvent_t)a->prof_event_start, st) != hipSuccess)
+      return PASTA_E_DEVICE;
+    if (n_prefix_wgs > 0) {
+      rc = launch_prefix(D, G, (int)max_rows, dim3((unsigned)n_prefix_wgs), st, p);
+      if (rc != PASTA_OK) return rc;
+    }
+    if (!items.empty()) {
+      const unsigned waves = (unsigned)items.size() * Hkv;
+      rc = launch_private(h, dim3((waves + 3) / 4), st, p);
+      if (rc != PASTA_OK) return rc;
+    }
+    if (a->prof_event_stop && hipEventRecord((hipEvent_t)a->prof_event_stop, st) != hipSuccess)
+      return PASTA_E_DEVICE;
+    rc = launch_merge(h, dim3(((unsigned)n * c.n_q_heads + 3) / 4), st, p);
+    if (rc != PASTA_OK) return rc;
+    if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
+    return PASTA_OK;
+  } catch (const std::bad_alloc&) {
+    return PASTA_E_NOMEM;
+  }
+}

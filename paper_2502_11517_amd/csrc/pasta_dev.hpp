@@ -1,0 +1,105 @@
+// Device-side structures and small helpers shared by the gfx950 kernels of the
+// multi-stream decode-attention step (arxiv 2502.11517, Section 3, "Efficiency").
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pasta {
+
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kPrivChunk = 128;      // tokens one private-segment work item walks
+constexpr int kPrefixTile = 128;     // tokens one LDS tile of the shared-prefix kernel holds
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Pool addressing, the formulas of include/pasta_attn.h folded into shifts and strides:
+//   element offset(phys, g) = (phys >> page_shift) * page_stride
+//                           + (phys & page_mask) * slot_stride + g * head_stride
+// Contiguous pools use page_shift = 31 (one page holds everything).
+struct Layout {
+  long long page_stride;  // elements
+  long long head_stride;  // elements
+  int slot_stride;        // elements
+  int page_shift;
+  int page_mask;
+  // logical slot -> physical row
+  int paged;              // 0: phys = req * pool_tokens + slot
+  int pages_per_request;  // 1: phys = page_table[req][slot >> shift] << shift | slot & mask
+  int pool_tokens;
+};
+
+__device__ __forceinline__ long long elem_off(const Layout& L, int phys, int g) {
+  return (long long)(phys >> L.page_shift) * L.page_stride +
+         (long long)(phys & L.page_mask) * L.slot_stride + (long long)g * L.head_stride;
+}
+
+__device__ __forceinline__ int phys_row(const Layout& L, const int32_t* __restrict__ page_table,
+                                        int req, int slot) {
+  if (!L.paged) return req * L.pool_tokens + slot;
+  int pp = page_table[req * L.pages_per_request + (slot >> L.page_shift)];
+  return (pp << L.page_shift) | (slot & L.page_mask);
+}
+
+// ---- per-call metadata (int32 words in one blob; offsets travel in DecodeParams) ----
+struct DevStream {      // one per decoding stream, call order
+  int32_t req;          // request id
+  int32_t req_idx;      // index into DevReq[]
+  int32_t local;        // rank among the request's streams in this call: stacked-Q row block
+  int32_t pc;           // tokens of the list handled by the shared-prefix kernel
+  int32_t range_begin;  // private list = ranges [range_begin, range_end)
+  int32_t range_end;
+  int32_t item_begin;   // private work items [item_begin, item_end)
+  int32_t item_end;
+  int32_t gather_base;  // first entry of this stream in dbg_gather_rows
+  int32_t pad[3];
+};
+struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it
+  int32_t start, count, stride, cum;
+};
+struct DevItem {        // a chunk of one stream's private token list; range_first = the
+  int32_t stream, tok_begin, tok_count, range_first;  // range that holds token tok_begin
+};
+struct DevReq {         // one per request present in the call
+  int32_t req;
+  int32_t pc;           // common prefix handled by the shared-prefix kernel
+  int32_t n_streams;    // R = n_streams * G stacked query rows
+  int32_t stream0;      // first entry in req_streams[]
+  int32_t wg_begin;     // first prefix work-group of this request
+  int32_t n_chunks;     // split-K chunks of [0, pc)
+  int32_t chunk_tokens; // tokens per chunk (multiple of kPrefixTile)
+  int32_t part_base;    // first partial row: row = part_base + ((g*n_chunks + c)*R + r)
+};
+
+struct DecodeParams {
+  const void* k;        // layer base of the K pool
+  const void* v;
+  const void* q;        // [n][Hq][D]
+  void* out;            // [n][Hq][D]
+  float* lse;           // [n][Hq] or null
+  int32_t* dbg_rows;    // or null
+  const int32_t* meta;  // blob
+  const int32_t* page_table;
+  float* part_acc;      // [rows][D]
+  float2* part_ml;      // [rows] (m in log2 units, l)
+  Layout lay;
+  int off_streams, off_reqs, off_req_streams, off_ranges, off_items;
+  int n_streams, n_reqs, n_items, n_prefix_wgs;
+  int priv_part_base;   // private partial row = priv_part_base + ((item*Hkv + g)*G + i)
+  int Hq, Hkv;
+  float scale_log2e;    // softmax_scale * log2(e): logits are kept in log2 units
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+}  // namespace pasta

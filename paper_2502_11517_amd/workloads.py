@@ -155,7 +155,7 @@ class Workload:
         for i in range(self.n):
             own = slots[(self.ev_request[:ne] == self.dec_request[i])
                         & (self.ev_stream[:ne] == self.dec_stream[i])]
-            vis = np.concatenate([np.asarray(self.anc_slots[i], np.int64), own.astype(np.int64)])
+            vis = np.sort(np.concatenate([np.asarray(self.anc_slots[i], np.int64), own.astype(np.int64)]))
             assert np.all(np.diff(vis) > 0)
             neq = np.nonzero(vis != np.arange(len(vis)))[0]
             p = int(neq[0]) if len(neq) else len(vis)

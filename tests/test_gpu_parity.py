@@ -1,0 +1,325 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle, element by
+element on the same seeded inputs.  Integer work (slots, pool bytes, gather maps) must be
+bit-exact; outputs must be within max-abs 2e-2 AND relative-L2 1e-2 for bf16, 1e-5 / 1e-5
+for fp32."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_11517_amd import binding as B
+from paper_2502_11517_amd import workloads as W
+from util import OraclePool, check_close, to_f64
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [B.TOKEN_MAJOR, B.HEAD_MAJOR]
+
+
+def _session(w, **kw):
+    from paper_2502_11517_amd.harness import Session
+    return Session(w, **kw)
+
+
+def _out64(w, t):
+    from paper_2502_11517_amd.harness import to_host_bits
+    torch.cuda.synchronize()
+    return to_f64(w, to_host_bits(t, w.dtype))
+
+
+def _check_step(w, s, op, step=0, *, explicit=True, flags=0, q=None, streams=None, what=""):
+    """Decode on the GPU, compare outputs, lse and gather maps with the oracle.
+    streams: subset of output rows to check (the oracle is slow at full size)."""
+    out, lse, (goffs, grows) = s.decode(step, explicit=explicit, flags=flags, q=q, want_gather=True)
+    got = _out64(w, out)
+    lse = lse.cpu().numpy().astype(np.float64)
+    grows = grows.cpu().numpy()
+    pl, offs, st, ct, sd = w.lists(step)
+    q = w.q(step) if q is None else q
+    sel = list(range(w.n)) if streams is None else streams
+    # oracle on the selected streams only
+    offs_sel, st_s, ct_s, sd_s = [0], [], [], []
+    for i in sel:
+        st_s += st[offs[i]:offs[i + 1]].tolist()
+        ct_s += ct[offs[i]:offs[i + 1]].tolist()
+        sd_s += sd[offs[i]:offs[i + 1]].tolist()
+        offs_sel.append(len(st_s))
+    ref, ref_lse = oracle.attention(op.g, op.k, op.v, w.dec_request[sel], pl[sel], offs_sel, st_s, ct_s, sd_s,
+                                    q[sel], w.scale)
+    res = check_close(got[sel], ref, w.dtype, what or w.name)
+    assert np.max(np.abs(lse[sel] - ref_lse)) <= (2e-2 if w.dtype == "bf16" else 1e-4), "lse"
+    for i in sel:  # gather maps: bit-exact, in list order
+        exp = oracle.gather_map(op.g, int(w.dec_request[i]), int(pl[i]), st[offs[i]:offs[i + 1]],
+                                ct[offs[i]:offs[i + 1]], sd[offs[i]:offs[i + 1]])
+        assert goffs[i + 1] - goffs[i] == len(exp)
+        assert np.array_equal(grows[goffs[i]:goffs[i + 1]].astype(np.int64), exp), f"gather map of stream {i}"
+    return res
+
+
+def _check_pool(w, s, op):
+    torch.cuda.synchronize()
+    k, v = s.pool_bits(0)
+    # compare only rows that were appended: everything else is uninitialised device memory
+    written = np.zeros(op.g.rows_per_layer(), bool)
+    tails = np.bincount(w.ev_request[:op.n_done], minlength=w.max_requests)
+    for r in range(w.max_requests):
+        for t in range(int(tails[r])):
+            written[oracle.phys_row(op.g, r, t)] = True
+    D, H = w.D, w.Hkv
+    rows = np.nonzero(written)[0]
+    for h in range(H):
+        offs = np.array([oracle.elem_offset(op.g, int(p), h) for p in rows[:: max(1, len(rows) // 400)]])
+        idx = (offs[:, None] + np.arange(D)[None, :]).ravel()
+        assert np.array_equal(k[idx], op.k[idx]) and np.array_equal(v[idx], op.v[idx])
+    if not w.page_tokens and op.g.c.head_major == 0:  # contiguous token-major: whole written prefix
+        n = int(tails[0]) * H * D
+        assert np.array_equal(k[:n], op.k[:n]) and np.array_equal(v[:n], op.v[:n])
+
+
+# ------------------------------------------------------------------------- the five configs
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_config1_tiny_fp32(layout):
+    w = W.config1()
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR)).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    _check_pool(w, s, op)
+    _check_step(w, s, op)
+    _check_step(w, s, op, explicit=False)
+    s.close()
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_config2_llama8b_prefix1k_4_streams(layout):
+    w = W.config2()
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR)).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    _check_pool(w, s, op)
+    a = _check_step(w, s, op)
+    b = _check_step(w, s, op, explicit=False)
+    c = _check_step(w, s, op, flags=B.DECODE_NO_MFMA)
+    print("cfg2 errors (mfma, maintained, no-mfma):", a, b, c)
+    s.close()
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_config3_prefix8k_8_streams_64_steps(layout):
+    w = W.config3()
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR))
+    s.append_events(w.n_prefill)
+    op.append_events(w.n_prefill)
+    for step in range(w.steps):
+        hi = w.n_events(step)
+        s.append_events(hi, chunk=w.n)  # one call of 8 rows: the step's append
+        if step in (0, 1, 31, 63):
+            op.append_events(hi)
+            _check_step(w, s, op, step, explicit=(step != 31), what=f"cfg3 step {step}")
+        else:
+            s.decode(step, explicit=False, want_lse=False)
+    _check_pool(w, s, op)
+    s.close()
+
+
+def test_config4_ragged_paged_batch():
+    w = W.config4()
+    for layout in LAYOUTS:
+        s = _session(w, kv_layout=layout)
+        op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR)).append_events(w.n_prefill)
+        s.append_events(w.n_prefill)
+        _check_pool(w, s, op)
+        sel = sorted(set(np.random.default_rng(4).choice(w.n, size=12, replace=False).tolist()))
+        _check_step(w, s, op, streams=sel)
+        _check_step(w, s, op, explicit=False, streams=sel[:4])
+        s.close()
+
+
+def test_config5_long_context_nested_fork():
+    w = W.config5()
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    # a nested child, a root-level fork, and the longest stream; all 64 heads each
+    pl, offs, st, ct, sd = w.lists(0)
+    longest = int(np.argmax([ct[offs[i]:offs[i + 1]].sum() + pl[i] for i in range(w.n)]))
+    sel = sorted({1, 9, longest})
+    res = _check_step(w, s, op, streams=sel)
+    print("cfg5 errors:", res)
+    _check_step(w, s, op, explicit=False, streams=sel[:1])
+    s.close()
+
+
+# ------------------------------------------------------------------------- shapes and edges
+@pytest.mark.parametrize("dtype,Hq,Hkv,D", [("bf16", 8, 8, 128), ("bf16", 8, 4, 128), ("bf16", 16, 2, 128),
+                                            ("bf16", 8, 2, 64), ("f32", 8, 2, 128), ("f32", 2, 2, 64),
+                                            ("bf16", 64, 8, 128)])
+def test_head_shapes(dtype, Hq, Hkv, D):
+    w = W.single_request("shape", dtype, Hq, Hkv, D, D ** -0.5, 21, 700, [40, 3, 129, 77], "random")
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    _check_step(w, s, op)
+    s.close()
+
+
+@pytest.mark.parametrize("prefix,lengths", [(128, [1]), (127, [5, 5]), (129, [200, 1]), (1000, [1, 1, 1]),
+                                            (4096 + 17, [130] * 9), (2, [300, 300]), (256, [64] * 33)])
+def test_ragged_tiles_and_stream_counts(prefix, lengths):
+    """Prefix lengths around the tile size, many streams (more stacked rows than one row tile),
+    more streams than the prefix kernel stacks (falls back to the private walk)."""
+    w = W.single_request("ragged", "bf16", 16, 4, 128, 1.0, 33, prefix, lengths, "round_robin", k_std=128 ** -0.5)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    _check_step(w, s, op)
+    _check_step(w, s, op, explicit=False)
+    s.close()
+
+
+def test_single_stream_no_fork_is_causal_decode():
+    w = W.single_request("nofork", "bf16", 32, 8, 128, 1.0, 5, 3000, [1], "random", k_std=128 ** -0.5)
+    # the only decoding stream is the root itself: replace the fork by the root's own last token
+    w.ev_stream[:] = 0
+    w.ev_parent[:] = -1
+    w.dec_stream[:] = 0
+    w.anc_slots = [[]]
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    pl, *_ = w.lists(0)
+    assert pl.tolist() == [3001]
+    _check_step(w, s, op)
+    _check_step(w, s, op, explicit=False)
+    s.close()
+
+
+def test_post_sync_stream_sees_several_forks_without_kv_movement():
+    """After the sync point the main thread lists the prefix, both forks' interleaved rows and
+    its own new token: one stream attending to several asynchronously decoded threads."""
+    w = W.single_request("sync", "bf16", 8, 2, 128, 1.0, 8, 300, [37, 22], "random", k_std=128 ** -0.5)
+    n0 = w.n_prefill
+    w.ev_request = np.append(w.ev_request[:n0], 0).astype(np.int32)
+    w.ev_stream = np.append(w.ev_stream[:n0], 0).astype(np.int32)   # the deferred sync token, root's
+    w.ev_parent = np.append(w.ev_parent[:n0], -1).astype(np.int32)
+    w.n_prefill = n0 + 1
+    w.dec_stream = np.asarray([0], np.int32)
+    w.dec_request = np.asarray([0], np.int32)
+    w.anc_slots = [list(range(300, n0))]  # the forks' rows; the root's own slots come from the history
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    pl, offs, st, ct, sd = w.lists(0)
+    assert pl.tolist() == [n0 + 1]
+    _check_step(w, s, op)  # explicit lists only: the maintained list of the root has no join yet
+    s.close()
+
+
+def test_stream_with_no_private_rows_and_request_with_no_common_prefix():
+    # (e) prefix only: a stream listing just [0, P); private only: lists that start above 0
+    w = W.single_request("edge", "bf16", 8, 2, 128, 1.0, 9, 512, [30, 40], "random", k_std=128 ** -0.5)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    from paper_2502_11517_amd.harness import to_device
+    q = w.q(0)
+    qd = to_device(q, w.dtype, s.device)
+    out = torch.empty_like(qd)
+    cases = [
+        ([512, 512], [0, 0, 0], [], [], []),                        # prefix only, both streams
+        ([0, 0], [0, 1, 2], [3, 100], [500, 400], [1, 1]),          # no common prefix at all
+        ([512, 0], [0, 0, 1], [520], [9], [2]),                     # mixed: common prefix is 0
+        ([300, 512], [0, 1, 1], [301], [70], [3]),                  # different prefix lengths
+    ]
+    for lists in cases:
+        s.h.decode_step(0, w.dec_request, w.dec_stream, qd, out, lists=lists)
+        ref, _ = oracle.attention(op.g, op.k, op.v, w.dec_request, *lists, q, w.scale)
+        check_close(_out64(w, out), ref, w.dtype, f"lists {lists[0]}")
+    s.close()
+
+
+def test_one_visible_row_returns_that_v_row_bit_exactly():
+    w = W.single_request("one", "bf16", 8, 2, 128, 1.0, 10, 200, [5], "random", k_std=128 ** -0.5)
+    s = _session(w)
+    s.append_events(w.n_prefill)
+    from paper_2502_11517_amd.harness import to_device, to_host_bits
+    qd = to_device(w.q(0), w.dtype, s.device)
+    out = torch.empty_like(qd)
+    s.h.decode_step(0, [0], [1], qd, out, lists=([0], [0, 1], [77], [1], [1]))
+    torch.cuda.synchronize()
+    _, v = w.kv_rows(0, w.n_prefill)
+    got = to_host_bits(out, w.dtype)[0]
+    for h in range(w.Hq):
+        assert np.array_equal(got[h], v[77, h // 4])
+    s.close()
+
+
+# ------------------------------------------------------------------------- numerics under stress
+@pytest.mark.parametrize("case", ["peaked", "planted", "large_v", "shifted", "membership"])
+def test_adversarial_values(case):
+    w = W.single_request("adv_" + case, "bf16", 16, 4, 128, 1.0, 44, 1500, [90, 260, 31], "random",
+                         k_std=128 ** -0.5, v_std=10.0 if case == "large_v" else 1.0)
+    q = w.q(0)
+    s = _session(w)
+    op = OraclePool(w)
+    n = w.n_prefill
+    k, v = w.kv_rows(0, n)
+    if case == "peaked":  # q x 8: softmax close to one-hot, running max rescales
+        q = W.f32_to_bf16_bits(W.bf16_bits_to_f32(q) * np.float32(8.0))
+    if case == "planted":  # one K row = +c q: near one-hot on a known row
+        qf = W.bf16_bits_to_f32(q)
+        k = k.copy()
+        k[1234, 1] = W.f32_to_bf16_bits(qf[0, 4] * np.float32(0.5))
+    if case == "shifted":  # all logits moved by about +80: max subtraction must hold
+        qf = W.bf16_bits_to_f32(q).astype(np.float64)
+        kf = W.bf16_bits_to_f32(k).astype(np.float64)
+        for g in range(w.Hkv):
+            d = qf[0, g * 4] / np.dot(qf[0, g * 4], qf[0, g * 4]) * 80.0
+            kf[:, g, :] += d
+        k = W.f32_to_bf16_bits(kf.astype(np.float32))
+    if case == "membership":  # q = 0, V[t] = e_(t mod D): out * |Vis| = class counts, exactly
+        q = np.zeros_like(q)
+        vf = np.zeros((n, w.Hkv, w.D), np.float32)
+        vf[np.arange(n), :, np.arange(n) % w.D] = 1.0
+        v = W.f32_to_bf16_bits(vf)
+    from paper_2502_11517_amd.harness import to_device
+    kd, vd = to_device(k, w.dtype, s.device), to_device(v, w.dtype, s.device)
+    s.h.append_kv(0, w.ev_request[:n], w.ev_stream[:n], kd, vd, parent_stream=w.ev_parent[:n])
+    rc, _ = oracle.append(op.g, op.k, op.v, w.ev_request[:n], k, v, op.tail)
+    assert rc == 0
+    op.n_done = n
+    res = _check_step(w, s, op, q=q)
+    print(case, res)
+    if case == "membership":
+        out, _, _ = s.decode(0, q=q)
+        got = _out64(w, out)
+        pl, offs, st, ct, sd = w.lists(0)
+        for i in range(w.n):
+            vis = oracle.gather_map(op.g, 0, int(pl[i]), st[offs[i]:offs[i + 1]], ct[offs[i]:offs[i + 1]],
+                                    sd[offs[i]:offs[i + 1]])
+            counts = np.bincount(vis % w.D, minlength=w.D)
+            assert np.max(np.abs(got[i, 0] * len(vis) - counts)) < 0.06  # bf16 output rounding of ~14/1800
+    s.close()
+
+
+def test_multi_layer_pools_share_slots():
+    w = W.single_request("layers", "bf16", 8, 2, 128, 1.0, 12, 400, [50, 60], "random", k_std=128 ** -0.5)
+    s = _session(w, n_layers=3)
+    from paper_2502_11517_amd.harness import to_device
+    n = w.n_prefill
+    k, v = w.kv_rows(0, n)
+    ops = []
+    for layer in range(3):  # layer l holds the rows rolled by l along the head-dim axis
+        kl, vl = np.roll(k, layer, axis=2), np.roll(v, layer, axis=2)
+        s.h.append_kv(layer, w.ev_request[:n], w.ev_stream[:n], to_device(kl, w.dtype, s.device),
+                      to_device(vl, w.dtype, s.device), parent_stream=w.ev_parent[:n])
+        op = OraclePool(w)
+        oracle.append(op.g, op.k, op.v, w.ev_request[:n], kl, vl, op.tail)
+        ops.append(op)
+    for layer in (2, 0, 1):
+        out, _, _ = s.decode(0, layer=layer, explicit=(layer != 1))
+        ref, _ = ops[layer].attention()
+        check_close(_out64(w, out), ref, w.dtype, f"layer {layer}")
+    s.close()

@@ -1,0 +1,236 @@
+"""CPU-only tests of the C-ABI library's host side: exported symbols, argument validation,
+slot assignment, the visibility lists it maintains (sizes against the oracle's dense mask),
+and the launch-plan arithmetic.  No kernel is launched: appends use RESERVE_ONLY, decode steps
+use PLAN_ONLY, and the pool / workspace addresses are never dereferenced."""
+from __future__ import annotations
+
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_11517_amd import binding as B
+from paper_2502_11517_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7000_0000_0000  # aligned, never dereferenced in these tests
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(B.library_path()):
+        B.build_library()
+
+
+def _handle(dtype="bf16", Hq=32, Hkv=8, D=128, *, n_layers=1, max_requests=1, page_tokens=0,
+            n_phys_pages=0, pages_per_request=0, max_streams=12, max_ranges=4096, pool_tokens=16384,
+            page_table=None, layout=B.TOKEN_MAJOR, scale=1.0):
+    cfg = B.make_config(dtype, Hq, Hkv, D, scale, n_layers=n_layers, max_requests=max_requests,
+                        page_tokens=page_tokens, kv_layout=layout, n_phys_pages=n_phys_pages,
+                        pages_per_request=pages_per_request, max_streams=max_streams, max_ranges=max_ranges,
+                        pool_tokens=pool_tokens)
+    ws = B.query_workspace_bytes(cfg)
+    return B.PastaAttn(cfg, FAKE, FAKE, FAKE, ws, page_table=page_table)
+
+
+def _reserve(h, req, sid, par=None, layer=0):
+    return h.append_kv(layer, req, sid, None, None, parent_stream=par, want_slots=True,
+                       flags=B.APPEND_RESERVE_ONLY)
+
+
+def _plan(h, req, sid, lists=None, flags=0):
+    n = len(req)
+    goffs, plan = np.zeros(n + 1, np.int64), np.zeros(8, np.int64)
+    h.decode_step(0, req, sid, None, None, lists=lists, flags=flags | B.DECODE_PLAN_ONLY,
+                  dbg_gather_offsets=goffs, dbg_plan=plan)
+    return goffs, plan
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "pasta_attn.h")).read()
+    declared = set(re.findall(r"\bint32_t\s+(pasta_attn_\w+)\s*\(", hdr))
+    assert declared == {"pasta_attn_create", "pasta_attn_append_kv", "pasta_attn_decode_step", "pasta_attn_destroy"}
+    syms = subprocess.run(["nm", "-D", "--defined-only", B.library_path()], capture_output=True, text=True).stdout
+    exported = {l.split()[-1] for l in syms.splitlines() if " T " in l}
+    assert declared <= exported
+    lib = B.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_create_validation_and_query_mode():
+    ok = dict(dtype="bf16", n_q_heads=32, n_kv_heads=8, head_dim=128, softmax_scale=1.0, pool_tokens=1024)
+    assert B.query_workspace_bytes(B.make_config(**ok)) > 0
+    bad = [dict(n_q_heads=30), dict(head_dim=96), dict(n_kv_heads=0), dict(softmax_scale=0.0), dict(pool_tokens=0),
+           dict(dtype=7), dict(n_q_heads=24, n_kv_heads=8), dict(n_layers=0), dict(max_streams=0),
+           dict(page_tokens=12, n_phys_pages=4, pages_per_request=4), dict(kv_layout=5)]
+    for b in bad:
+        with pytest.raises(B.PastaError) as e:
+            B.query_workspace_bytes(B.make_config(**{**ok, **b}))
+        assert e.value.code == B.E_INVAL, b
+    cfg = B.make_config(**ok)
+    ws = B.query_workspace_bytes(cfg)
+    with pytest.raises(B.PastaError) as e:
+        B.PastaAttn(cfg, FAKE, FAKE, FAKE, ws - 1)
+    assert e.value.code == B.E_CAPACITY
+    with pytest.raises(B.PastaError) as e:
+        B.PastaAttn(cfg, FAKE, FAKE, FAKE + 8, ws)  # misaligned workspace
+    assert e.value.code == B.E_INVAL
+    with pytest.raises(B.PastaError) as e:
+        B.PastaAttn(B.make_config(**ok), None, FAKE, FAKE, ws)
+    assert e.value.code == B.E_INVAL
+    # page table entries must be inside the page pool
+    pc = B.make_config(**{**ok, "page_tokens": 16, "n_phys_pages": 4, "pages_per_request": 2})
+    with pytest.raises(B.PastaError) as e:
+        B.PastaAttn(pc, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc), page_table=[[0, 4]])
+    assert e.value.code == B.E_INVAL
+
+
+def test_slots_follow_call_order_per_request():
+    """Single active thread: contiguous slots; two active threads: neighbouring slots that
+    alternate (Section 3, Efficiency)."""
+    h = _handle(max_requests=2, pool_tokens=64)
+    assert _reserve(h, [0] * 5, [0] * 5).tolist() == [0, 1, 2, 3, 4]
+    s = _reserve(h, [0, 0, 1, 0, 0, 1], [1, 2, 0, 1, 2, 0], par=[0, 0, -1, -1, -1, -1])
+    assert s.tolist() == [5, 6, 0, 7, 8, 1]
+    with pytest.raises(B.PastaError) as e:  # 64-slot pool: 56 more fit, 57 do not
+        _reserve(h, [0] * 57, [1] * 57)
+    assert e.value.code == B.E_CAPACITY
+    assert _reserve(h, [0], [1]).tolist() == [9]  # the failed call changed nothing
+
+
+def test_append_argument_errors():
+    h = _handle(pool_tokens=64, max_streams=4)
+    _reserve(h, [0, 0], [0, 0])
+    for req, sid, par, code in [([1], [0], None, B.E_INVAL), ([0], [4], None, B.E_INVAL),
+                                ([0], [1], [1], B.E_INVAL),      # parent == stream
+                                ([0], [1], [2], B.E_INVAL),      # parent not open
+                                ([0], [0], [0], B.E_INVAL),      # parent == itself
+                                ([0, 0], [1, 1], [0, 0], B.E_INVAL)]:  # parent on an open stream
+        with pytest.raises(B.PastaError) as e:
+            _reserve(h, req, sid, par)
+        assert e.value.code == code, (req, sid, par)
+    with pytest.raises(B.PastaError) as e:
+        h.append_kv(3, [0], [0], None, None, flags=B.APPEND_RESERVE_ONLY)
+    assert e.value.code == B.E_STATE
+    with pytest.raises(B.PastaError) as e:  # a real append needs device rows
+        h.append_kv(0, [0], [0], None, None)
+    assert e.value.code == B.E_INVAL
+    assert _reserve(h, [0], [0]).tolist() == [2]
+
+
+def test_layer_replay_reuses_the_slots():
+    h = _handle(n_layers=3, pool_tokens=64)
+    with pytest.raises(B.PastaError) as e:  # nothing to replay yet
+        _reserve(h, [0], [0], layer=1)
+    assert e.value.code == B.E_STATE
+    assert _reserve(h, [0, 0, 0], [0, 0, 0], layer=0).tolist() == [0, 1, 2]
+    assert _reserve(h, [0, 0, 0], [0, 0, 0], layer=1).tolist() == [0, 1, 2]
+    assert _reserve(h, [0, 0, 0], [0, 0, 0], layer=2).tolist() == [0, 1, 2]
+    assert _reserve(h, [0, 0], [1, 0], par=[0, -1], layer=0).tolist() == [3, 4]
+    assert _reserve(h, [0, 0], [1, 0], layer=2).tolist() == [3, 4]
+    with pytest.raises(B.PastaError) as e:  # more rows than layer 0 appended
+        _reserve(h, [0, 0, 0], [1, 0, 0], layer=1)
+    assert e.value.code == B.E_STATE
+
+
+def test_paper_worked_example_through_the_maintained_lists():
+    """The 28-slot scenario of Section 3 (Efficiency): sizes of what each thread sees."""
+    h = _handle(pool_tokens=64, max_streams=3)
+    _reserve(h, [0] * 22, [0] * 22)                       # prompt .. <promise/> #1
+    _reserve(h, [0, 0, 0, 0, 0, 0], [1, 1, 0, 2, 1, 2], par=[0, -1, -1, 0, -1, -1])
+    goffs, _ = _plan(h, [0, 0, 0], [1, 2, 0])
+    assert np.diff(goffs).tolist() == [25, 25, 23]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_maintained_list_sizes_equal_dense_mask_on_random_fork_histories(seed):
+    ev_s, ev_p = W.random_fork_history(100 + seed, n_slots=80, max_streams=8)
+    n_streams = int(ev_s.max()) + 1
+    h = _handle(pool_tokens=128, max_streams=n_streams)
+    _reserve(h, np.zeros(len(ev_s), np.int32), ev_s, ev_p)
+    parent = np.full(n_streams, -1, np.int32)
+    spawn = np.zeros(n_streams, np.int64)
+    seen = set()
+    for t, (s, p) in enumerate(zip(ev_s.tolist(), ev_p.tolist())):
+        if s not in seen:
+            seen.add(s)
+            parent[s], spawn[s] = p, t
+    sids = np.arange(n_streams, dtype=np.int32)
+    goffs, _ = _plan(h, np.zeros(n_streams, np.int32), sids)
+    for s in range(n_streams):
+        assert goffs[s + 1] - goffs[s] == int(oracle.visible_dense(ev_s, parent, spawn, s).sum())
+
+
+def test_explicit_list_validation():
+    h = _handle(pool_tokens=256, max_streams=4)
+    _reserve(h, [0] * 100, [0] * 100)
+    ok = ([10], [0, 2], [20, 40], [3, 2], [4, 1])
+    goffs, _ = _plan(h, [0], [1], ok)
+    assert goffs.tolist() == [0, 15]
+    bad = [
+        ([10], [0, 1], [5], [1], [1]),        # range inside the prefix
+        ([10], [0, 2], [20, 28], [3, 1], [4, 1]),  # second range starts at the first one's last slot
+        ([10], [0, 1], [99], [2], [1]),       # runs past the tail
+        ([10], [0, 1], [20], [0], [1]),       # empty range
+        ([10], [0, 1], [20], [2], [0]),       # stride 0
+        ([101], [0, 0], [], [], []),          # prefix beyond the tail
+        ([0], [0, 0], [], [], []),            # nothing visible
+        ([-1], [0, 0], [], [], []),
+    ]
+    for lists in bad:
+        with pytest.raises(B.PastaError) as e:
+            _plan(h, [0], [1], lists)
+        assert e.value.code == B.E_INVAL, lists
+    with pytest.raises(B.PastaError) as e:  # the same (request, stream) twice
+        _plan(h, [0, 0], [1, 1], ([10, 10], [0, 0, 0], [], [], []))
+    assert e.value.code == B.E_INVAL
+    with pytest.raises(B.PastaError) as e:  # maintained mode, stream never opened
+        _plan(h, [0], [2])
+    assert e.value.code == B.E_STATE
+    small = _handle(pool_tokens=256, max_streams=4, max_ranges=2)
+    _reserve(small, [0] * 100, [0] * 100)
+    with pytest.raises(B.PastaError) as e:
+        _plan(small, [0], [1], ([10], [0, 3], [20, 30, 40], [1, 1, 1], [1, 1, 1]))
+    assert e.value.code == B.E_CAPACITY
+
+
+def test_plan_arithmetic_on_the_8k_prefix_8_stream_shape():
+    w = W.config3(steps=2)
+    h = _handle(pool_tokens=w.pool_tokens, max_streams=w.max_streams)
+    ne = w.n_events(0)
+    _reserve(h, w.ev_request[:ne], w.ev_stream[:ne], w.ev_parent[:ne])
+    pl, offs, st, ct, sd = w.lists(0)
+    for lists in (None, (pl, offs, st, ct, sd)):  # maintained and explicit agree
+        goffs, plan = _plan(h, w.dec_request, w.dec_stream, lists)
+        vis = [pl[i] + int(ct[offs[i]:offs[i + 1]].sum()) for i in range(w.n)]
+        assert np.diff(goffs).tolist() == vis
+        priv = [v - 8192 for v in vis]
+        assert plan[5] == 8192 and plan[0] == 8192 // 128 * 8
+        assert plan[1] == -(-8192 // plan[4]) * 8 and plan[4] % 128 == 0
+        assert plan[2] == sum(-(-p // 128) for p in priv)
+        assert plan[3] == plan[1] * 32 + plan[2] * 32
+    # fp32 handles and NO_MFMA route everything through the private-segment kernel
+    _, plan = _plan(h, w.dec_request, w.dec_stream, None, flags=B.DECODE_NO_MFMA)
+    assert plan[5] == 0 and plan[1] == 0 and plan[2] == sum(-(-v // 128) for v in vis)
+
+
+def test_nested_fork_common_prefix_is_the_minimum():
+    w = W.single_request("nested", "bf16", 8, 2, 128, 1.0, 5, 300, [6, 4, 5, 3, 7], "round_robin", nested=(200, 2))
+    h = _handle(Hq=8, Hkv=2, pool_tokens=w.pool_tokens, max_streams=w.max_streams)
+    _reserve(h, w.ev_request, w.ev_stream, w.ev_parent)
+    goffs, plan = _plan(h, w.dec_request, w.dec_stream)
+    pl, offs, st, ct, sd = w.lists(0)
+    assert pl.tolist() == [500, 500, 300, 300, 300]
+    assert plan[5] == 300
+    assert np.diff(goffs).tolist() == [pl[i] + int(ct[offs[i]:offs[i + 1]].sum()) for i in range(w.n)]
+
+
+def test_destroy_and_stale_handle():
+    h = _handle(pool_tokens=64)
+    lib = B.load_library()
+    assert lib.pasta_attn_destroy(None) == B.OK
+    h.destroy()
