@@ -1,69 +1,87 @@
 // K4 -- log-sum-exp merge of the split partials.  Splitting a stream's visible set between
-// the shared-prefix kernel's chunks and the private-segment items is this build's device;
-// the identity used is  sum_t e^{z_t} v_t = sum_i e^{m_i} acc_i  over the parts i, so
+// the shared-prefix chunks and the private-segment items is this build's device; the
+// identity used is  sum_t e^{z_t} v_t = sum_i e^{m_i} acc_i  over the parts i, so
 //   m = max_i m_i,  l = sum_i l_i 2^{m_i - m},  out = sum_i acc_i 2^{m_i - m} / l
 // (m in log2 units).  Parts with l_i = 0 (nothing visible in them) contribute nothing.
-// One wavefront per (stream, query head); lanes own D/64 output elements.
+// One work-group of 512 threads per (stream, query head): the threads form 512/D groups,
+// group k sums parts k, k + 512/D, ... with one head-dim element per thread (a part's row is
+// read as one coalesced 4D-byte line) and several loads in flight; the groups are then
+// added through LDS.
 #pragma once
 #include "pasta_dev.hpp"
 
 namespace pasta {
 
+constexpr int kMergeThreads = 512;
+
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void k_merge(DecodeParams p) {
-  constexpr int EPL = D / kWave;  // elements per lane (1 or 2)
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wid = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (wid >= p.n_streams * p.Hq) return;
-  const int s = wid / p.Hq, h = wid % p.Hq;
+__global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
+  constexpr int NGRP = kMergeThreads / D;
+  constexpr int UNR = 8;
+  __shared__ float red[kMergeThreads / kWave];
+  __shared__ float osum[NGRP][D];
+  __shared__ float lsum[NGRP];
+  const int tid = threadIdx.x;
+  const int s = blockIdx.x / p.Hq, h = blockIdx.x % p.Hq;
   const int g = h / G, gi = h % G;
-  const DevStream st = reinterpret_cast<const DevStream*>(p.meta + p.off_streams)[s];
-  const DevReq rq = reinterpret_cast<const DevReq*>(p.meta + p.off_reqs)[st.req_idx];
+  const int32_t* meta = meta_of(p);
+  const DevStream st = reinterpret_cast<const DevStream*>(meta + p.off_streams)[s];
+  const DevReq rq = reinterpret_cast<const DevReq*>(meta + p.off_reqs)[st.req_idx];
   const int R = rq.n_streams * G;
   const int n_pre = rq.n_chunks;
   const int n_parts = n_pre + (st.item_end - st.item_begin);
+  const int pre0 = rq.part_base + g * rq.n_chunks * R + st.local * G + gi;       // + i * R
+  const int priv0 = p.priv_part_base + (st.item_begin * p.Hkv + g) * G + gi;     // + j * Hkv * G
   auto part_row = [&](int i) -> int {
-    if (i < n_pre) return rq.part_base + (g * rq.n_chunks + i) * R + st.local * G + gi;
-    return p.priv_part_base + ((st.item_begin + (i - n_pre)) * p.Hkv + g) * G + gi;
+    return i < n_pre ? pre0 + i * R : priv0 + (i - n_pre) * p.Hkv * G;
   };
 
+  // ---- global max over the parts that hold something
   float mx = -INFINITY;
-  for (int i = lane; i < n_parts; i += kWave) {
+  for (int i = tid; i < n_parts; i += kMergeThreads) {
     const float2 ml = p.part_ml[part_row(i)];
     if (ml.y > 0.f) mx = fmaxf(mx, ml.x);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-
-  float L = 0.f, o[EPL];
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
+  __syncthreads();
 #pragma unroll
-  for (int x = 0; x < EPL; ++x) o[x] = 0.f;
-  for (int i = 0; i < n_parts; ++i) {
-    const int row = part_row(i);
-    const float2 ml = p.part_ml[row];
-    const float w = (ml.y > 0.f) ? fast_exp2(ml.x - mx) : 0.f;
-    L += ml.y * w;
-    const float* a = p.part_acc + (long long)row * D + lane * EPL;
-    if (EPL == 2) {
-      const float2 av = *reinterpret_cast<const float2*>(a);
-      o[0] = fmaf(av.x, w, o[0]);
-      o[EPL - 1] = fmaf(av.y, w, o[EPL - 1]);
-    } else {
-      o[0] = fmaf(a[0], w, o[0]);
+  for (int i = 0; i < kMergeThreads / kWave; ++i) mx = fmaxf(mx, red[i]);
+
+  // ---- weighted sums, one head-dim element per thread, parts strided over the groups
+  const int grp = tid / D, d = tid % D;
+  float o = 0.f, L = 0.f;
+  for (int i0 = grp; i0 < n_parts; i0 += NGRP * UNR) {
+    float2 ml[UNR];
+    float a[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int i = i0 + u * NGRP;
+      const int row = part_row(i < n_parts ? i : i0);
+      ml[u] = p.part_ml[row];
+      a[u] = p.part_acc[(long long)row * D + d];
+      if (i >= n_parts) ml[u].y = 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const float wgt = (ml[u].y > 0.f) ? fast_exp2(ml[u].x - mx) : 0.f;
+      L = fmaf(ml[u].y, wgt, L);
+      o = fmaf(a[u], wgt, o);
     }
   }
-  const float inv = 1.f / L;
-  const long long ob = ((long long)s * p.Hq + h) * D + lane * EPL;
-  if constexpr (sizeof(T) == 4) {
-    float* out = reinterpret_cast<float*>(p.out) + ob;
+  osum[grp][d] = o;
+  if (d == 0) lsum[grp] = L;
+  __syncthreads();
+  if (grp == 0) {
 #pragma unroll
-    for (int x = 0; x < EPL; ++x) out[x] = o[x] * inv;
-  } else {
-    uint16_t* out = reinterpret_cast<uint16_t*>(p.out) + ob;
-#pragma unroll
-    for (int x = 0; x < EPL; ++x) out[x] = f32_to_bf16_rne(o[x] * inv);
+    for (int k = 1; k < NGRP; ++k) { o += osum[k][d]; L += lsum[k]; }
+    const long long ob = ((long long)s * p.Hq + h) * D + d;
+    const float val = o / L;
+    if constexpr (sizeof(T) == 4) reinterpret_cast<float*>(p.out)[ob] = val;
+    else reinterpret_cast<uint16_t*>(p.out)[ob] = f32_to_bf16_rne(val);
+    if (p.lse && d == 0) p.lse[(long long)s * p.Hq + h] = (mx + __log2f(L)) * kLn2;
   }
-  if (p.lse && lane == 0) p.lse[(long long)s * p.Hq + h] = (mx + __log2f(L)) * kLn2;
 }
 
 }  // namespace pasta

@@ -1,6 +1,8 @@
-// K3 -- per-stream private-segment partial attention (arxiv 2502.11517, Section 3,
-// "Efficiency": a thread attends only to its own rows of the interleaved pool plus the
-// spawning thread's rows that existed before the fork; Figure 2b/2c).
+// K3, vector-ALU form -- per-stream private-segment partial attention (arxiv 2502.11517,
+// Section 3, "Efficiency": a thread attends only to its own rows of the interleaved pool
+// plus the spawning thread's rows that existed before the fork; Figure 2b/2c).  This form
+// serves fp32 pools, D = 64, and the whole visible list when the matrix-core kernel is
+// switched off; bf16 D = 128 private segments normally go through k_attn's gather items.
 //
 // One wavefront walks one work item = (stream, kv head, chunk of <= 128 tokens of the
 // stream's private list).  The list is a sequence of (start, count, stride) ranges of
@@ -54,9 +56,10 @@ __device__ __forceinline__ void private_item(const DecodeParams& p, PrivLds& lds
   const int wave = threadIdx.x >> 6;
   const int sub = lane / LPR, dl = lane % LPR;
 
-  const DevItem it = reinterpret_cast<const DevItem*>(p.meta + p.off_items)[item_idx];
-  const DevStream st = reinterpret_cast<const DevStream*>(p.meta + p.off_streams)[it.stream];
-  const DevRange* ranges = reinterpret_cast<const DevRange*>(p.meta + p.off_ranges);
+  const int32_t* meta = meta_of(p);
+  const DevItem it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item_idx];
+  const DevStream st = reinterpret_cast<const DevStream*>(meta + p.off_streams)[it.stream];
+  const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
   const int cnt = it.tok_count;
 
   // -- the ranges this chunk overlaps: [range_first, range_first + nr), at most cnt

@@ -16,8 +16,8 @@
 
 #include "../../include/pasta_attn.h"
 #include "k_append.hpp"
+#include "k_attn.hpp"
 #include "k_merge.hpp"
-#include "k_prefix.hpp"
 #include "k_private.hpp"
 
 using namespace pasta;
@@ -26,7 +26,8 @@ namespace {
 
 constexpr uint32_t kMagic = 0x50415354u;  // "PAST"
 constexpr int kRing = 8;                  // metadata staging buffers in flight
-constexpr int kTargetPrefixWgs = 512;     // split-K parallelism aimed for (2 per CU)
+constexpr int kNumCUs = 256;              // MI355X
+constexpr int kTargetPrefixWgs = 768;     // most shared-prefix work-groups budgeted for
 
 struct Range { int32_t start, count, stride; };
 
@@ -53,6 +54,7 @@ struct pasta_attn {
   // workspace carve-up (byte offsets)
   size_t off_page_table = 0, off_meta = 0, meta_bytes = 0, off_ml = 0, off_acc = 0;
   int64_t part_rows_cap = 0;
+  int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // PASTA_PREFIX_CHUNK / PASTA_PRIV_CHUNK (tokens; 0 = heuristic)
   // device-side readiness (deferred so that the host logic works without a GPU)
   bool device_ready = false;
   char* pinned = nullptr;                // kRing * meta_bytes
@@ -196,10 +198,10 @@ int launch_private_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
 template <typename T, int D>
 int launch_merge_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
   switch (G) {
-    case 1: k_merge<T, D, 1><<<grid, 256, 0, st>>>(p); break;
-    case 2: k_merge<T, D, 2><<<grid, 256, 0, st>>>(p); break;
-    case 4: k_merge<T, D, 4><<<grid, 256, 0, st>>>(p); break;
-    case 8: k_merge<T, D, 8><<<grid, 256, 0, st>>>(p); break;
+    case 1: k_merge<T, D, 1><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 2: k_merge<T, D, 2><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 4: k_merge<T, D, 4><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 8: k_merge<T, D, 8><<<grid, kMergeThreads, 0, st>>>(p); break;
     default: return PASTA_E_INVAL;
   }
   return PASTA_OK;
@@ -212,7 +214,7 @@ int launch_private(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeP
   return D == 64 ? launch_private_g<uint16_t, 64>(h->G, grid, st, p)
                  : launch_private_g<uint16_t, 128>(h->G, grid, st, p);
 }
-int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {
+int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {  // grid = n * Hq
   const int D = h->cfg.head_dim;
   if (h->cfg.dtype == PASTA_F32)
     return D == 64 ? launch_merge_g<float, 64>(h->G, grid, st, p) : launch_merge_g<float, 128>(h->G, grid, st, p);
@@ -281,6 +283,8 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
       if (pp < 0 || pp >= cfg->n_phys_pages) return fail(PASTA_E_INVAL);
     h->cfg.page_table = nullptr;  // the caller's array is not kept
   }
+  if (const char* e = std::getenv("PASTA_PREFIX_CHUNK")) h->tune_prefix_chunk = std::atoi(e);
+  if (const char* e = std::getenv("PASTA_PRIV_CHUNK")) h->tune_priv_chunk = std::atoi(e);
   try {
     h->tail.assign(cfg->max_requests, 0);
     h->tail_before.assign(cfg->max_requests, 0);
@@ -511,13 +515,30 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       for (int i = 0; i < n; ++i) req_streams[reqs[stream_req_idx[i]].stream0 + stream_local[i]] = i;
     }
 
-    // ---- shared-prefix plan: only what the MFMA kernel takes; the rest is private
-    const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && prefix_kernel_supports(D, G);
-    int64_t pc_total = 0, max_rows = 1;
+    // ---- shared-prefix plan: only what the matrix-core kernel takes; the rest is private
+    const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G);
+    int64_t pc_total = 0, max_rows = 1, priv_total = 0;
     for (auto& q : reqs) {
-      if (!mfma || q.pc < kPrefixTile || q.n_streams * G > kPrefixMaxRows) q.pc = 0;
+      if (!mfma || q.pc < kTile || q.n_streams * G > kAttnMaxRows) q.pc = 0;
       pc_total += q.pc;
       if (q.pc) max_rows = std::max<int64_t>(max_rows, (int64_t)q.n_streams * G);
+    }
+    for (int i = 0; i < n; ++i) {
+      int64_t cnt = lv[i].prefix_len - reqs[stream_req_idx[i]].pc;
+      for (int k = 0; k < lv[i].n_ranges; ++k) cnt += lv[i].at(k).count;
+      priv_total += cnt;
+    }
+    // Chunking.  All work-groups of the step should be resident at once (3 per CU with up to
+    // 32 stacked rows, else 2), so tokens per work item ~ total tokens * Hkv / resident slots,
+    // rounded up to the 64-token tile.
+    int64_t priv_chunk = kPrivChunk, chunk_tokens = kTile;
+    if (mfma) {
+      const int64_t slots = (int64_t)(max_rows <= 32 ? 3 : 2) * kNumCUs;
+      const int64_t want = ((pc_total + priv_total) * Hkv + slots - 1) / slots;
+      chunk_tokens = std::max<int64_t>(kTile, (want + kTile - 1) / kTile * kTile);
+      priv_chunk = std::min<int64_t>(chunk_tokens, kGatherMax);
+      if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
+      if (h->tune_priv_chunk >= kTile) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / kTile * kTile, kGatherMax);
     }
     // private items
     std::vector<DevStream> streams(n);
@@ -546,9 +567,9 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       ds.range_end = (int32_t)ranges.size();
       ds.item_begin = (int32_t)items.size();
       int32_t rcur = ds.range_begin;
-      for (int32_t t = 0; t < cum; t += kPrivChunk) {
+      for (int32_t t = 0; t < cum; t += (int32_t)priv_chunk) {
         while (rcur + 1 < ds.range_end && ranges[rcur + 1].cum <= t) rcur++;
-        items.push_back({i, t, std::min<int32_t>(kPrivChunk, cum - t), rcur});
+        items.push_back({i, t, std::min<int32_t>((int32_t)priv_chunk, cum - t), rcur});
       }
       ds.item_end = (int32_t)items.size();
       if (gather_total + q.pc + cum > INT32_MAX) return PASTA_E_CAPACITY;
@@ -558,15 +579,11 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     }
     if (a->dbg_gather_offsets) a->dbg_gather_offsets[n] = gather_total;
 
-    // split-K chunking: tokens per chunk, a multiple of the LDS tile, chosen so that the
-    // prefix work-groups number about kTargetPrefixWgs and the partial rows fit the workspace
+    // split-K chunks of the common prefixes; grow the chunk until the partial rows fit
     const int64_t priv_rows = (int64_t)items.size() * c.n_q_heads;
-    int64_t chunk_tokens = kPrefixTile, n_prefix_wgs = 0, prefix_rows = 0;
+    int64_t n_prefix_wgs = 0, prefix_rows = 0;
     if (pc_total > 0) {
-      const int64_t tiles_total = (pc_total + kPrefixTile - 1) / kPrefixTile * Hkv;
-      int64_t tiles_per_wg = std::max<int64_t>(1, tiles_total / kTargetPrefixWgs);
-      for (;; ++tiles_per_wg) {
-        chunk_tokens = tiles_per_wg * kPrefixTile;
+      for (;; chunk_tokens += kTile) {
         n_prefix_wgs = 0;
         prefix_rows = 0;
         for (auto& q : reqs) {
@@ -581,7 +598,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         if (chunk_tokens > (int64_t)1 << 30) return PASTA_E_CAPACITY;
       }
     } else {
-      for (auto& q : reqs) { q.n_chunks = 0; q.chunk_tokens = kPrefixTile; q.wg_begin = 0; q.part_base = 0; }
+      for (auto& q : reqs) { q.n_chunks = 0; q.chunk_tokens = kTile; q.wg_begin = 0; q.part_base = 0; }
       if (priv_rows > h->part_rows_cap) return PASTA_E_CAPACITY;
     }
 
@@ -603,7 +620,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
 
     if (a->dbg_plan) {
       int64_t tiles = 0;
-      for (auto& q : reqs) tiles += (int64_t)(q.pc + kPrefixTile - 1) / kPrefixTile * Hkv;
+      for (auto& q : reqs) tiles += (int64_t)(q.pc + kTile - 1) / kTile * Hkv;
       a->dbg_plan[0] = tiles;
       a->dbg_plan[1] = n_prefix_wgs;
       a->dbg_plan[2] = (int64_t)items.size();
@@ -619,16 +636,21 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     int rc = ensure_device(h);
     if (rc != PASTA_OK) return rc;
     hipStream_t st = (hipStream_t)c.hip_stream;
-    const int32_t* dev_meta = nullptr;
-    rc = upload_meta(h, blob.data(), blob.size() * 4, &dev_meta);
-    if (rc != PASTA_OK) return rc;
+    if (blob.size() <= (size_t)kInlineMetaWords) {  // small plan: rides in the kernel arguments
+      p.meta = nullptr;
+      std::memcpy(p.inline_meta, blob.data(), blob.size() * 4);
+    } else {
+      const int32_t* dev_meta = nullptr;
+      rc = upload_meta(h, blob.data(), blob.size() * 4, &dev_meta);
+      if (rc != PASTA_OK) return rc;
+      p.meta = dev_meta;
+    }
     p.k = (const char*)c.k_pool + (size_t)a->layer * h->layer_elems * h->elem;
     p.v = (const char*)c.v_pool + (size_t)a->layer * h->layer_elems * h->elem;
     p.q = a->q;
     p.out = a->out;
     p.lse = a->out_lse;
     p.dbg_rows = a->dbg_gather_rows;
-    p.meta = dev_meta;
     p.page_table = (const int32_t*)((const char*)c.workspace + h->off_page_table);
     p.part_acc = (float*)((char*)c.workspace + h->off_acc);
     p.part_ml = (float2*)((char*)c.workspace + h->off_ml);
@@ -636,6 +658,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     p.n_streams = n;
     p.n_reqs = (int)reqs.size();
     p.n_items = (int)items.size();
+    p.n_mfma_items = mfma ? (int)items.size() : 0;
     p.n_prefix_wgs = (int)n_prefix_wgs;
     p.priv_part_base = (int)prefix_rows;
     p.Hq = c.n_q_heads;
@@ -644,18 +667,18 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
 
     if (a->prof_event_start && hipEventRecord((hipEvent_t)a->prof_event_start, st) != hipSuccess)
       return PASTA_E_DEVICE;
-    if (n_prefix_wgs > 0) {
-      rc = launch_prefix(D, G, (int)max_rows, dim3((unsigned)n_prefix_wgs), st, p);
+    if (mfma) {
+      const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
+      rc = launch_attn((int)max_rows, dim3(grid), st, p);
       if (rc != PASTA_OK) return rc;
-    }
-    if (!items.empty()) {
+    } else if (!items.empty()) {
       const unsigned waves = (unsigned)items.size() * Hkv;
       rc = launch_private(h, dim3((waves + 3) / 4), st, p);
       if (rc != PASTA_OK) return rc;
     }
     if (a->prof_event_stop && hipEventRecord((hipEvent_t)a->prof_event_stop, st) != hipSuccess)
       return PASTA_E_DEVICE;
-    rc = launch_merge(h, dim3(((unsigned)n * c.n_q_heads + 3) / 4), st, p);
+    rc = launch_merge(h, dim3((unsigned)n * c.n_q_heads), st, p);
     if (rc != PASTA_OK) return rc;
     if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
     return PASTA_OK;

@@ -7,8 +7,8 @@
 namespace pasta {
 
 constexpr int kWave = 64;            // CDNA wavefront
-constexpr int kPrivChunk = 128;      // tokens one private-segment work item walks
-constexpr int kPrefixTile = 128;     // tokens one LDS tile of the shared-prefix kernel holds
+constexpr int kPrivChunk = 128;      // tokens one work item of the vector-ALU private kernel walks
+constexpr int kInlineMetaWords = 768; // per-call metadata up to this size rides in the kernel arguments
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -66,7 +66,7 @@ struct DevReq {         // one per request present in the call
   int32_t stream0;      // first entry in req_streams[]
   int32_t wg_begin;     // first prefix work-group of this request
   int32_t n_chunks;     // split-K chunks of [0, pc)
-  int32_t chunk_tokens; // tokens per chunk (multiple of kPrefixTile)
+  int32_t chunk_tokens; // tokens per chunk (multiple of the LDS tile)
   int32_t part_base;    // first partial row: row = part_base + ((g*n_chunks + c)*R + r)
 };
 
@@ -84,10 +84,17 @@ struct DecodeParams {
   Layout lay;
   int off_streams, off_reqs, off_req_streams, off_ranges, off_items;
   int n_streams, n_reqs, n_items, n_prefix_wgs;
+  int n_mfma_items;     // private items taken by the matrix-core kernel (all or none)
   int priv_part_base;   // private partial row = priv_part_base + ((item*Hkv + g)*G + i)
   int Hq, Hkv;
   float scale_log2e;    // softmax_scale * log2(e): logits are kept in log2 units
+  int32_t inline_meta[kInlineMetaWords];  // the blob itself when meta == nullptr (small plans:
+                                          // no host-to-device copy on the step's critical path)
 };
+
+__device__ __forceinline__ const int32_t* meta_of(const DecodeParams& p) {
+  return p.meta ? p.meta : p.inline_meta;
+}
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

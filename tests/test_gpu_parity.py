@@ -323,3 +323,32 @@ def test_multi_layer_pools_share_slots():
         ref, _ = ops[layer].attention()
         check_close(_out64(w, out), ref, w.dtype, f"layer {layer}")
     s.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_maintained_lists_on_random_fork_histories_equal_dense_mask(seed):
+    """Every live thread keeps decoding, forks open from any thread (nested too): the lists the
+    library derives from parent_stream must name exactly the ancestor-rule set, and the
+    outputs must match the brute-force dense-mask attention."""
+    ev_s, ev_p = W.random_fork_history(500 + seed, n_slots=700, max_streams=9, p_fork=0.02, p_retire=0.004)
+    n_streams = int(ev_s.max()) + 1
+    w = W.Workload(name="forks", dtype="bf16", Hq=8, Hkv=2, D=128, scale=1.0, seed=900 + seed, max_requests=1,
+                   pool_tokens=768, max_streams=n_streams, k_std=128 ** -0.5)
+    w.ev_request = np.zeros(len(ev_s), np.int32)
+    w.ev_stream, w.ev_parent, w.n_prefill = ev_s, ev_p, len(ev_s)
+    w.dec_request = np.zeros(n_streams, np.int32)
+    w.dec_stream = np.arange(n_streams, dtype=np.int32)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    out, lse, (goffs, grows) = s.decode(0, explicit=False, want_gather=True)
+    got = _out64(w, out)
+    grows = grows.cpu().numpy()
+    ss, par, sp = w.fork_tree(0)
+    q = w.q(0)
+    for i in range(n_streams):
+        mask = oracle.visible_dense(ss, par, sp, i)
+        assert np.array_equal(grows[goffs[i]:goffs[i + 1]], np.nonzero(mask)[0])
+        ref, _ = oracle.attention_dense(op.g, op.k, op.v, 0, mask, q[i], w.scale)
+        check_close(got[i], ref, w.dtype, f"stream {i}")
+    s.close()
