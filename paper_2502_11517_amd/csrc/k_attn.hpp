@@ -10,21 +10,23 @@
 //
 // K3, private segments.  A stream's own rows are interleaved with the other streams' rows
 // in the pool (Section 3, "Efficiency"; Figure 2c).  Work item = (stream, kv head, chunk of
-// the stream's private list); the list's (start, count, stride) ranges are expanded to
-// physical rows in LDS and the rows are gathered with the same 128-bit loads (16 lanes =
-// one 256-byte row of one kv head).  Only the G query rows of that stream are live.
+// the stream's private list).  A chunk that lies inside one (start, count, stride) range
+// is addressed arithmetically; otherwise its ranges are expanded to physical rows in LDS.
+// Rows are gathered with the same 128-bit loads (16 lanes = one 256-byte row of one kv
+// head).  Only the G query rows of that stream are live.
 //
-// Both kinds run the same tile loop in a work-group of two wavefronts, 64 tokens per tile:
-//   * tile loads are issued one tile ahead into registers (16 x 16 B per lane), then stored
-//     to LDS with a 16-byte XOR swizzle;
-//   * wave w computes S^T for tokens 32w..32w+31 against all rows with
-//     v_mfma_f32_32x32x16_bf16 (A = K rows, B = Q rows, both from LDS), fp32 accumulate;
-//   * the tile's row maxima are exchanged through LDS so both waves share one running max
-//     (lane shuffle across the two 32-lane halves, then LDS across waves);
-//   * P = 2^(S - m) is rounded to bf16 and parked in LDS (over the dead K tile) in B-operand
-//     order; wave w accumulates O^T for head-dim slice 64w..64w+63 over the tile's 64 tokens,
-//     A = V^T read with the transposing LDS load.  The token order inside a contraction
-//     step is a free bijection, chosen so that P needs no permutation.
+// Both kinds run the same tile loop in a work-group of four wavefronts, 64 tokens per
+// tile.  The loop is built around bytes in flight, because that is what bounds a decode
+// step: every thread keeps TWO tiles of loads (16 x 16 B) outstanding in registers while
+// the work-group computes on a third that sits in LDS.
+//   * registers -> LDS with a 16-byte XOR swizzle;
+//   * wave w computes S^T for tokens 16w..16w+15 against all rows with
+//     v_mfma_f32_16x16x32_bf16 (A = K rows, B = Q rows, both from LDS), fp32 accumulate;
+//   * row maxima: across the four 16-lane groups of a wave by lane shuffles, across the
+//     waves through LDS, so the work-group shares one running max per row;
+//   * P = 2^(S - m) is rounded to bf16 and written to LDS in B-operand order; wave w then
+//     accumulates O^T for head-dim slice 32w..32w+31 over the tile's 64 tokens with
+//     v_mfma_f32_32x32x16_bf16, A = V^T fetched with the transposing LDS read.
 // A work item ends with one partial (m, l, acc[D]) per live row for the merge kernel.
 // Logits are kept in log2 units.
 #pragma once
@@ -34,13 +36,15 @@ namespace pasta {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // a plain 16-byte register quad
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kTile = 64;            // tokens per LDS tile
-constexpr int kAttnThreads = 128;    // two wavefronts
+constexpr int kAttnThreads = 256;    // four wavefronts
 constexpr int kAttnMaxRows = 128;    // stacked query rows one work-group can carry (RT <= 4)
 constexpr int kGatherMax = 256;      // most tokens (and ranges) of one private work item
 
@@ -48,14 +52,15 @@ inline bool attn_kernel_supports(int D, int G) { return D == 128 && G >= 1; }
 
 template <int RT>
 struct AttnLds {
-  u32x4 kt[kTile * 16];   // K tile [row][16 pieces], piece p of row r at p ^ (r & 15);
-                          // reused for P: [rt][4 steps][2 halves][32 rows] pieces
-  u32x4 vt[kTile * 16];   // V tile, same swizzle
-  u32x4 q[RT * 32 * 16];  // stacked Q rows, same swizzle (rows >= R are zero)
-  float tmax[2][RT * 32]; // per-wave row maxima of the current tile
-  float lsum[2][RT * 32]; // per-wave row sums at the end of the item
-  int rows[kGatherMax];          // gather items: physical row of every token of the item
-  DevRange ranges[kGatherMax];   // gather items: the ranges the item overlaps
+  u32x4 kt[kTile * 16];     // K tile [row][16 pieces], piece p of row r at p ^ (r & 15); once
+                            // S is done it holds P^T [rt][4 steps][2 halves][32 rows]: 8 tokens
+                            // (16 B) each, RT * 4 KB
+  u32x4 vt[kTile * 16];     // V tile, same swizzle
+  u32x4 q[RT * 32 * 16];    // stacked Q rows, same swizzle (rows >= R are zero)
+  float tmax[4][RT * 32];   // per-wave row maxima of the current tile
+  float lsum[4][RT * 32];   // per-wave row sums at the end of the item
+  int rows[kGatherMax];          // listed gather items: physical row of every token
+  DevRange ranges[kGatherMax];   // listed gather items: the ranges the item overlaps
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -68,294 +73,346 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // 8-byte datum addressed by block lane 4 e + i / 4, for e = 0..3.  With block lane j
 // pointing at row (j / 4), columns 4 (j % 4).., lane i ends up with column i of 4 rows.
 __device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (s16x4 __attribute__((address_space(3)))*)(uintptr_t)(const __attribute__((address_space(3))) uint16_t*)p);
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
+
+struct TileRegs { u32x4 k[4], v[4]; };  // one thread's share of a 64-token tile
+
+// Phase clocks for kernel tuning (compiled in only with -DPASTA_PHASE_CLOCKS): thread 0 of every
+// work-group stores the 100 MHz wall clock at a few points into the tail of the partials buffer.
+#ifdef PASTA_PHASE_CLOCKS
+#define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < 1024) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
+    __builtin_bit_cast(float2, (unsigned long long)__builtin_amdgcn_s_memrealtime()); } while (0)
+#else
+#define PASTA_CLK(n) do {} while (0)
+#endif
 
 template <int RT, bool PAGED, bool GATHER>
 __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
+  constexpr int NT = 2 * RT;  // 16-row tiles of S^T
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
-  const int l32 = lane & 31, hh = lane >> 5;
+  const int c16 = lane & 15, q4 = lane >> 4;   // S^T layout: row nt*16 + c16, tokens 16 w + 4 q4 + i
+  const int l32 = lane & 31, hh = lane >> 5;   // O^T layout: row rt*32 + l32, half hh
   const int G = p.Hq / p.Hkv;
-  const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
+  PASTA_CLK(0);
 
-  // ---- decode the work item
-  int req, g, R, tok0, tok1, gather_base;
+  // ---- decode the work item.  Token j of the item is logical slot slot0 + j * stride of
+  // request `req`, except for "listed" gather items, whose rows come from LDS.
+  int req, g, R, n_tok, slot0, stride, gather_pos;
   long long part_row0;
-  const int32_t* req_streams = nullptr;  // prefix: stream of stacked row r is req_streams[r / G]
+  const int32_t* req_streams = nullptr;  // prefix, several requests: stacked row r is stream req_streams[r / G]
   int q_stream = 0;                      // gather: the one stream
   int n_req_streams = 0;
+  bool listed = false;
   if constexpr (!GATHER) {
-    const DevReq* reqs = reinterpret_cast<const DevReq*>(meta + p.off_reqs);
-    int qi = 0;
-    for (; qi < p.n_reqs - 1; ++qi) {
-      const int b = reqs[qi].wg_begin;
-      if (wi >= b && wi < b + reqs[qi].n_chunks * p.Hkv) break;
+    DevReq rq;
+    if (p.single_req) {  // scalar loads from the kernel arguments
+      rq.req = p.req0.req; rq.pc = p.req0.pc; rq.n_streams = p.req0.n_streams; rq.stream0 = 0;
+      rq.wg_begin = p.req0.wg_begin; rq.n_chunks = p.req0.n_chunks;
+      rq.chunk_tokens = p.req0.chunk_tokens; rq.part_base = p.req0.part_base;
+    } else {
+      const DevReq* reqs = reinterpret_cast<const DevReq*>(meta + p.off_reqs);
+      int qi = 0;
+      for (; qi < p.n_reqs - 1; ++qi) {
+        const int b = reqs[qi].wg_begin;
+        if (wi >= b && wi < b + reqs[qi].n_chunks * p.Hkv) break;
+      }
+      rq = reqs[qi];
+      req_streams = meta + p.off_req_streams + rq.stream0;
     }
-    const DevReq rq = reqs[qi];
     const int wl = wi - rq.wg_begin;
     const int c = wl % rq.n_chunks;
     g = wl / rq.n_chunks;
     req = rq.req;
     R = rq.n_streams * G;
     n_req_streams = rq.n_streams;
-    tok0 = c * rq.chunk_tokens;
-    tok1 = min(tok0 + rq.chunk_tokens, rq.pc);
-    req_streams = meta + p.off_req_streams + rq.stream0;
+    slot0 = c * rq.chunk_tokens;
+    stride = 1;
+    n_tok = min(rq.chunk_tokens, rq.pc - slot0);
     part_row0 = rq.part_base + (long long)(g * rq.n_chunks + c) * R;
-    gather_base = 0;
+    gather_pos = slot0;
   } else {
     const int item = wi / p.Hkv;
     g = wi % p.Hkv;
     const DevItem it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item];
-    const DevStream st = streams[it.stream];
-    req = st.req;
+    req = it.req;
     R = G;
     q_stream = it.stream;
-    tok0 = 0;
-    tok1 = it.tok_count;
+    n_tok = it.tok_count;
+    slot0 = it.slot0;
+    stride = it.stride;
     part_row0 = p.priv_part_base + (long long)(item * p.Hkv + g) * G;
-    gather_base = st.gather_base + st.pc + it.tok_begin;
-    // ranges the item overlaps -> LDS, then every token of the item -> physical row
-    const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
-    int nr = st.range_end - it.range_first;
-    if (nr > it.tok_count) nr = it.tok_count;
-    for (int r = tid; r < nr; r += kAttnThreads) lds.ranges[r] = ranges[it.range_first + r];
-    __syncthreads();
-    for (int j = tid; j < it.tok_count; j += kAttnThreads) {
-      const int tok = it.tok_begin + j;
-      int lo = 0, hi = nr - 1;  // last range with cum <= tok
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (lds.ranges[mid].cum <= tok) lo = mid; else hi = mid - 1;
+    gather_pos = it.gather_pos;
+    listed = it.n_ranges > 1;
+    if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> physical row
+      const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
+      const int nr = it.n_ranges;
+      for (int r = tid; r < nr; r += kAttnThreads) lds.ranges[r] = ranges[it.range_first + r];
+      __syncthreads();
+      for (int j = tid; j < n_tok; j += kAttnThreads) {
+        const int tok = it.tok_begin + j;
+        int lo = 0, hi = nr - 1;  // last range with cum <= tok
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (lds.ranges[mid].cum <= tok) lo = mid; else hi = mid - 1;
+        }
+        const DevRange rg = lds.ranges[lo];
+        lds.rows[j] = phys_row(p.lay, p.page_table, req, rg.start + (tok - rg.cum) * rg.stride);
       }
-      const DevRange rg = lds.ranges[lo];
-      const int phys = phys_row(p.lay, p.page_table, req, rg.start + (tok - rg.cum) * rg.stride);
-      lds.rows[j] = phys;
-      if (p.dbg_rows && g == 0) p.dbg_rows[gather_base + j] = phys;
-    }
-    // the barrier that publishes lds.rows is the one after the Q store below
-  }
-
-  // ---- stacked Q rows -> LDS
-  {
-    const u32x4* qg = reinterpret_cast<const u32x4*>(p.q);
-#pragma unroll
-    for (int i = 0; i < RT * 4; ++i) {
-      const int idx = tid + i * kAttnThreads;
-      const int r = idx >> 4, piece = idx & 15;
-      u32x4 val = {0u, 0u, 0u, 0u};
-      if (r < R) {
-        const int s = GATHER ? q_stream : req_streams[r / G];
-        val = qg[((long long)s * p.Hq + (g * G + r % G)) * 16 + piece];
-      }
-      lds.q[r * 16 + (piece ^ (r & 15))] = val;
+      __syncthreads();
     }
   }
-  if constexpr (GATHER) __syncthreads();
+  const int n_tiles = (n_tok + kTile - 1) / kTile;
 
-  // ---- tile loads: thread -> piece (tid & 15) of rows (tid >> 4) + 8 i
+  // ---- tile loads: thread -> piece (tid & 15) of rows (tid >> 4) + 16 i, i < 4
   const char* kb = reinterpret_cast<const char*>(p.k);
   const char* vb = reinterpret_cast<const char*>(p.v);
-  const int piece = tid & 15, rbase = tid >> 4;  // rbase 0..7
-  auto row_of = [&](int t) -> int {  // branch-free so that a tile's 16 loads issue together
-    if constexpr (GATHER) {
-      return lds.rows[t];
-    } else if constexpr (PAGED) {
+  const int piece = tid & 15, rbase = tid >> 4;  // rbase 0..15
+  auto row_of = [&](int j) -> int {  // branch-free so that a tile's loads issue together
+    const int t = slot0 + j * stride;
+    int phys;
+    if constexpr (PAGED) {
       const int pp = p.page_table[req * p.lay.pages_per_request + (t >> p.lay.page_shift)];
-      return (pp << p.lay.page_shift) | (t & p.lay.page_mask);
+      phys = (pp << p.lay.page_shift) | (t & p.lay.page_mask);
     } else {
-      return req * p.lay.pool_tokens + t;
+      phys = req * p.lay.pool_tokens + t;
+    }
+    if constexpr (GATHER) {
+      const int from_list = lds.rows[j];  // j < kGatherMax; unused unless listed
+      phys = listed ? from_list : phys;
+    }
+    return phys;
+  };
+  auto load_tile = [&](TileRegs& tr, int tile) {
+    long long off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = min(tile * kTile + rbase + 16 * i, n_tok - 1);  // rows past the end repeat the last one
+      off[i] = (elem_off(p.lay, row_of(j), g) + piece * 8) * 2;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      tr.k[i] = *reinterpret_cast<const u32x4*>(kb + off[i]);
+      tr.v[i] = *reinterpret_cast<const u32x4*>(vb + off[i]);
     }
   };
-  u32x4 kr[8], vr[8];
-  auto load_tile = [&](int t0) {
-    long long off[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int tok = min(t0 + rbase + 8 * i, tok1 - 1);  // rows past the end repeat the last one
-      off[i] = (elem_off(p.lay, row_of(tok), g) + piece * 8) * 2;
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      kr[i] = *reinterpret_cast<const u32x4*>(kb + off[i]);
-      vr[i] = *reinterpret_cast<const u32x4*>(vb + off[i]);
-    }
-  };
-  load_tile(tok0);
+  TileRegs ta, tb;
+  load_tile(ta, 0);  // first: nothing else on the way to these loads
+  if (n_tiles > 1) load_tile(tb, 1);
+  PASTA_CLK(1);
 
-  if constexpr (!GATHER) {
-    if (p.dbg_rows && g == 0) {
-      for (int t = tok0 + tid; t < tok1; t += kAttnThreads) {
-        const int phys = row_of(t);
-        for (int j = 0; j < n_req_streams; ++j) p.dbg_rows[streams[req_streams[j]].gather_base + t] = phys;
+  // ---- stacked Q rows -> LDS (loads issued behind the tiles', stored before them)
+  {
+    const u32x4* qg = reinterpret_cast<const u32x4*>(p.q);
+    u32x4 qr[RT * 2];
+#pragma unroll
+    for (int i = 0; i < RT * 2; ++i) {
+      const int idx = tid + i * kAttnThreads;
+      const int r = idx >> 4, pc16 = idx & 15;
+      qr[i] = u32x4{0u, 0u, 0u, 0u};
+      if (r < R) {
+        const int s = GATHER ? q_stream : (req_streams ? req_streams[r / G] : r / G);
+        qr[i] = qg[((long long)s * p.Hq + (g * G + r % G)) * 16 + pc16];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < RT * 2; ++i) {
+      const int idx = tid + i * kAttnThreads;
+      const int r = idx >> 4, pc16 = idx & 15;
+      lds.q[r * 16 + (pc16 ^ (r & 15))] = qr[i];
+    }
+  }
+
+  if (p.dbg_rows && g == 0) {
+    const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
+    for (int j = tid; j < n_tok; j += kAttnThreads) {
+      const int phys = row_of(j);
+      if constexpr (GATHER) {
+        p.dbg_rows[gather_pos + j] = phys;
+      } else {
+        for (int k = 0; k < n_req_streams; ++k)
+          p.dbg_rows[streams[req_streams ? req_streams[k] : k].gather_base + gather_pos + j] = phys;
       }
     }
   }
 
-  f32x16 O[RT][2];  // O^T for d = 64 w + 32 mt + ..., rows r
-  float m_run[RT], l_run[RT];
+  f32x16 O[RT];                 // O^T: d = 32 w + 8 (i / 4) + 4 hh + i % 4, row rt*32 + l32
+  float m_run[NT], l_run[NT];   // per 16-row tile: row nt*16 + c16 (l_run: this lane's tokens only)
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    m_run[rt] = -INFINITY;
-    l_run[rt] = 0.f;
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int i = 0; i < 16; ++i) O[rt][i] = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) O[rt][mt][i] = 0.f;
-  }
+  for (int nt = 0; nt < NT; ++nt) { m_run[nt] = -INFINITY; l_run[nt] = 0.f; }
 
   const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(lds.vt);
-  for (int t0 = tok0; t0 < tok1; t0 += kTile) {
-    // registers -> LDS: row rbase + 8 i, piece ^ (row & 15)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = rbase + 8 * i;
-      lds.kt[r * 16 + (piece ^ (r & 15))] = kr[i];
-      lds.vt[r * 16 + (piece ^ (r & 15))] = vr[i];
-    }
-    __syncthreads();
-    if (t0 + kTile < tok1) load_tile(t0 + kTile);  // next tile in flight
+  u32x4* pt = lds.kt;  // the K tile is dead once every wave has its S^T (barrier below)
+  uint16_t* pt16 = reinterpret_cast<uint16_t*>(pt);
 
-    // ---- S^T = K Q^T for this wave's 32 tokens
-    f32x16 S[RT];
+  auto compute_tile = [&](int t0) {
+    // ---- S^T = K Q^T for this wave's 16 tokens: A = K[16 tok x 32 d], B = Q^T[32 d x 16 rows]
+    f32x4 S[NT];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int nt = 0; nt < NT; ++nt) S[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int krow = 16 * w + c16;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) S[rt][i] = 0.f;
-    const int krow = 32 * w + l32;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const int pc = (2 * kk + hh) ^ (l32 & 15);
+    for (int kk = 0; kk < 4; ++kk) {
+      const int pc = (4 * kk + q4) ^ c16;  // (krow & 15) == c16, and Q row (nt*16 + c16) & 15 == c16
       const u32x4 ar = lds.kt[krow * 16 + pc];
       const bf16x8 A = *reinterpret_cast<const bf16x8*>(&ar);
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const u32x4 br = lds.q[(rt * 32 + l32) * 16 + pc];
-        S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, *reinterpret_cast<const bf16x8*>(&br), S[rt], 0, 0, 0);
+      for (int nt = 0; nt < NT; ++nt) {
+        const u32x4 br = lds.q[(nt * 16 + c16) * 16 + pc];
+        S[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, *reinterpret_cast<const bf16x8*>(&br), S[nt], 0, 0, 0);
       }
     }
     // scale to log2 units, mask the ragged end, wave-level row max
-    // S^T register i of lane (r, hh) is token 32 w + 8 (i / 4) + 4 hh + i % 4
-    const int tok_lane0 = t0 + 32 * w + 4 * hh;
+    const int tok_lane0 = t0 + 16 * w + 4 * q4;
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
+    for (int nt = 0; nt < NT; ++nt) {
       float mx = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int tok = tok_lane0 + 8 * (i >> 2) + (i & 3);
-        const float s = tok < tok1 ? S[rt][i] * p.scale_log2e : -INFINITY;
-        S[rt][i] = s;
+      for (int i = 0; i < 4; ++i) {
+        const float s = (tok_lane0 + i) < n_tok ? S[nt][i] * p.scale_log2e : -INFINITY;
+        S[nt][i] = s;
         mx = fmaxf(mx, s);
       }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      if (hh == 0) lds.tmax[w][rt * 32 + l32] = mx;
+      if (q4 == 0) lds.tmax[w][nt * 16 + c16] = mx;
     }
-    __syncthreads();  // K tile is dead from here on; tmax visible
+    __syncthreads();  // tmax visible; every wave is done with the K tile
 
-    // ---- P = 2^(S - m), parked in LDS in B-operand order; rescale O
-    u32x4* pl = lds.kt;
+    // ---- P = 2^(S - m) -> LDS in B-operand order; running sums; rescale O
+    // contraction slot (ks, hh', e) of P V is token 16 ks + 8 hh' + e; this lane's 4 tokens
+    // are ks = w, hh' = q4 / 2, e = 4 (q4 % 2) + i
+    float corr[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int r = nt * 16 + c16;
+      const float mt = fmaxf(fmaxf(lds.tmax[0][r], lds.tmax[1][r]), fmaxf(lds.tmax[2][r], lds.tmax[3][r]));
+      const float mn = fmaxf(m_run[nt], mt);  // finite: every tile holds a valid token
+      corr[nt] = fast_exp2(m_run[nt] - mn);
+      m_run[nt] = mn;
+      float e[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[i] = fast_exp2(S[nt][i] - mn);
+      l_run[nt] = l_run[nt] * corr[nt] + (e[0] + e[1]) + (e[2] + e[3]);
+      u32x2 pk;
+      pk[0] = pack_bf16x2(e[0], e[1]);
+      pk[1] = pack_bf16x2(e[2], e[3]);
+      const int rt = nt >> 1, row32 = (nt & 1) * 16 + c16;
+      *reinterpret_cast<u32x2*>(pt16 + ((((rt * 4 + w) * 2 + (q4 >> 1)) * 32 + row32) * 8 + 4 * (q4 & 1))) = pk;
+    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int r = rt * 32 + l32;
-      const float mn = fmaxf(m_run[rt], fmaxf(lds.tmax[0][r], lds.tmax[1][r]));  // finite: a tile holds a valid token
-      const float corr = fast_exp2(m_run[rt] - mn);
-      m_run[rt] = mn;
-      float ps = 0.f;
+      // this lane's O^T row is in 16-row tile 2 rt + ((lane >> 4) & 1); picked with a bit mask so
+      // that the compiler keeps corr[] in registers instead of indexing it in scratch memory
+      const uint32_t msk = 0u - (uint32_t)((lane >> 4) & 1);
+      const float cr = __uint_as_float((__float_as_uint(corr[2 * rt + 1]) & msk) | (__float_as_uint(corr[2 * rt]) & ~msk));
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float e = fast_exp2(S[rt][i] - mn);
-        S[rt][i] = e;
-        ps += e;
-      }
-      l_run[rt] = l_run[rt] * corr + ps;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) O[rt][mt][i] *= corr;
-      // contraction step ks = 2 w + s holds this wave's registers 8 s .. 8 s + 7
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        u32x4 pk;
-        pk[0] = pack_bf16x2(S[rt][8 * s + 0], S[rt][8 * s + 1]);
-        pk[1] = pack_bf16x2(S[rt][8 * s + 2], S[rt][8 * s + 3]);
-        pk[2] = pack_bf16x2(S[rt][8 * s + 4], S[rt][8 * s + 5]);
-        pk[3] = pack_bf16x2(S[rt][8 * s + 6], S[rt][8 * s + 7]);
-        pl[((rt * 4 + 2 * w + s) * 2 + hh) * 32 + l32] = pk;
-      }
+      for (int i = 0; i < 16; ++i) O[rt][i] *= cr;
     }
     __syncthreads();  // P visible
 
-    // ---- O^T[d slice of this wave][r] += V^T P^T over the tile's 64 tokens.
-    // Contraction slot (ks, hh, e) is token 32 (ks / 2) + 16 (ks % 2) + 8 (e / 4) + 4 hh + e % 4.
-    // Lane (dd, hh) of M-tile mt needs V[those 8 tokens][64 w + 32 mt + dd]: two transposing
-    // reads, each over 4 consecutive token rows x 16 columns per 16-lane block.
-    const int bl = lane & 15;                 // lane inside its 16-lane block
-    const int cblk = (lane >> 4) & 1;         // which 16 columns of the 32-wide M-tile
+    // ---- O^T[d = 32 w + dd][r] += V^T P^T over the tile's 64 tokens.
+    // Lane (dd, hh) needs V[16 ks + 8 hh + e][32 w + dd], e < 8: two transposing reads, each
+    // over 4 consecutive token rows x 16 columns per 16-lane block.
+    const int bl = lane & 15;             // lane inside its 16-lane block
+    const int cblk = (lane >> 4) & 1;     // which 16 columns of the 32-wide M-tile
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 A[2];
+      s16x4 part[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        s16x4 part[2];
-#pragma unroll
-        for (int e4 = 0; e4 < 2; ++e4) {
-          const int trow = 32 * (ks >> 1) + 16 * (ks & 1) + 8 * e4 + 4 * hh + (bl >> 2);
-          const int col = 64 * w + 32 * mt + 16 * cblk + 4 * (bl & 3);
-          part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ (trow & 15))) * 8 + (col & 7));
-        }
-        u32x4 a4;
-        a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
-        a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
-        a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
-        a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
-        A[mt] = *reinterpret_cast<const bf16x8*>(&a4);
+      for (int e4 = 0; e4 < 2; ++e4) {
+        const int trow = 16 * ks + 8 * hh + 4 * e4 + (bl >> 2);
+        const int col = 32 * w + 16 * cblk + 4 * (bl & 3);
+        part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ (trow & 15))) * 8 + (col & 7));
       }
+      u32x4 a4;
+      a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
+      a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
+      a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
+      a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
+      const bf16x8 A = *reinterpret_cast<const bf16x8*>(&a4);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        const u32x4 br = pl[((rt * 4 + ks) * 2 + hh) * 32 + l32];
-        const bf16x8 B = *reinterpret_cast<const bf16x8*>(&br);
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-          O[rt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[mt], B, O[rt][mt], 0, 0, 0);
+        const u32x4 br = pt[((rt * 4 + ks) * 2 + hh) * 32 + l32];
+        O[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, *reinterpret_cast<const bf16x8*>(&br), O[rt], 0, 0, 0);
       }
     }
-    __syncthreads();  // tile buffers free for the next round
-  }
+  };
 
-  // ---- partial out: l summed over halves and waves; O^T lane (r, hh), register i of M-tile
-  // mt is d = 64 w + 32 mt + 8 (i / 4) + 4 hh + i % 4
+  auto store_tile = [&](const TileRegs& tr) {  // rows rbase + 16 i all have (row & 15) == rbase
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const float lw = l_run[rt] + __shfl_xor(l_run[rt], 32, kWave);
-    if (hh == 0) lds.lsum[w][rt * 32 + l32] = lw;
+    for (int i = 0; i < 4; ++i) {
+      lds.kt[(rbase + 16 * i) * 16 + (piece ^ rbase)] = tr.k[i];
+      lds.vt[(rbase + 16 * i) * 16 + (piece ^ rbase)] = tr.v[i];
+    }
+  };
+
+  // two tiles of loads stay in flight while a third is computed on
+  for (int t = 0; t < n_tiles; t += 2) {
+    store_tile(ta);
+    __syncthreads();
+    if (t == 0) PASTA_CLK(2);
+    if (t + 2 < n_tiles) load_tile(ta, t + 2);
+    compute_tile(t * kTile);
+    __syncthreads();  // tile buffers free
+    if (t == 0) PASTA_CLK(3);
+    if (t + 1 < n_tiles) {
+      store_tile(tb);
+      __syncthreads();
+      if (t == 0) PASTA_CLK(4);
+      if (t + 3 < n_tiles) load_tile(tb, t + 3);
+      compute_tile((t + 1) * kTile);
+      __syncthreads();
+      if (t == 0) PASTA_CLK(5);
+    }
+  }
+  PASTA_CLK(6);
+
+  // ---- partial out: l summed over the wave's 16-lane groups and over the waves
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float lw = l_run[nt];
+    lw += __shfl_xor(lw, 16, kWave);
+    lw += __shfl_xor(lw, 32, kWave);
+    if (q4 == 0) lds.lsum[w][nt * 16 + c16] = lw;
   }
   __syncthreads();
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int r = rt * 32 + l32;
     if (r < R) {
-      float* dst = p.part_acc + (part_row0 + r) * D + 64 * w + 4 * hh;
+      float* dst = p.part_acc + (part_row0 + r) * D + 32 * w + 4 * hh;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-          *reinterpret_cast<float4*>(dst + 32 * mt + 8 * b) =
-              make_float4(O[rt][mt][4 * b], O[rt][mt][4 * b + 1], O[rt][mt][4 * b + 2], O[rt][mt][4 * b + 3]);
-      if (w == 0 && hh == 0) p.part_ml[part_row0 + r] = make_float2(m_run[rt], lds.lsum[0][r] + lds.lsum[1][r]);
+      for (int b = 0; b < 4; ++b)
+        *reinterpret_cast<float4*>(dst + 8 * b) =
+            make_float4(O[rt][4 * b], O[rt][4 * b + 1], O[rt][4 * b + 2], O[rt][4 * b + 3]);
     }
   }
+  if (w == 0 && q4 == 0) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int r = nt * 16 + c16;
+      if (r < R)
+        p.part_ml[part_row0 + r] =
+            make_float2(m_run[nt], lds.lsum[0][r] + lds.lsum[1][r] + lds.lsum[2][r] + lds.lsum[3][r]);
+    }
+  }
+  PASTA_CLK(7);
 }
 
 // One launch for all partials of a decode step: work-groups [0, n_priv_wgs) are private
 // (gather) items -- they have the longer dependency chain, so they start first -- and the
 // rest are shared-prefix items.
 template <int RT, bool PAGED>
-__global__ __launch_bounds__(kAttnThreads) void k_attn(DecodeParams p) {
+__global__ __launch_bounds__(kAttnThreads, (RT == 1 ? 3 : (RT == 2 ? 2 : 1))) void k_attn(DecodeParams p) {
   __shared__ AttnLds<RT> lds;
-  const int32_t* meta = p.meta ? p.meta : p.inline_meta;
+  const int32_t* meta = meta_of(p);
   const int n_priv_wgs = p.n_mfma_items * p.Hkv;
   if ((int)blockIdx.x < n_priv_wgs)
     attn_item<1, PAGED, true>(p, reinterpret_cast<AttnLds<1>&>(lds), meta, blockIdx.x);

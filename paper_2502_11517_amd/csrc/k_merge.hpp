@@ -17,7 +17,7 @@ constexpr int kMergeThreads = 512;
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
   constexpr int NGRP = kMergeThreads / D;
-  constexpr int UNR = 8;
+  constexpr int UNR = 16;
   __shared__ float red[kMergeThreads / kWave];
   __shared__ float osum[NGRP][D];
   __shared__ float lsum[NGRP];
@@ -26,21 +26,41 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
   const int g = h / G, gi = h % G;
   const int32_t* meta = meta_of(p);
   const DevStream st = reinterpret_cast<const DevStream*>(meta + p.off_streams)[s];
-  const DevReq rq = reinterpret_cast<const DevReq*>(meta + p.off_reqs)[st.req_idx];
-  const int R = rq.n_streams * G;
-  const int n_pre = rq.n_chunks;
+  int R, n_pre, part_base;
+  if (p.single_req) {  // scalars from the kernel arguments: one table look-up less
+    R = p.req0.n_streams * G; n_pre = p.req0.n_chunks; part_base = p.req0.part_base;
+  } else {
+    const DevReq rq = reinterpret_cast<const DevReq*>(meta + p.off_reqs)[st.req_idx];
+    R = rq.n_streams * G; n_pre = rq.n_chunks; part_base = rq.part_base;
+  }
   const int n_parts = n_pre + (st.item_end - st.item_begin);
-  const int pre0 = rq.part_base + g * rq.n_chunks * R + st.local * G + gi;       // + i * R
+  const int pre0 = part_base + g * n_pre * R + st.local * G + gi;                // + i * R
   const int priv0 = p.priv_part_base + (st.item_begin * p.Hkv + g) * G + gi;     // + j * Hkv * G
   auto part_row = [&](int i) -> int {
     return i < n_pre ? pre0 + i * R : priv0 + (i - n_pre) * p.Hkv * G;
   };
 
+  // ---- this thread's first batch of (m, l, acc) loads goes out before anything waits
+  const int grp = tid / D, d = tid % D;
+  float2 ml[UNR];
+  float a[UNR];
+  auto load_batch = [&](int i0) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int i = i0 + u * NGRP;
+      const int row = part_row(i < n_parts ? i : i0);
+      ml[u] = p.part_ml[row];
+      a[u] = p.part_acc[(long long)row * D + d];
+      if (i >= n_parts) ml[u].y = 0.f;
+    }
+  };
+  if (grp < n_parts) load_batch(grp);
+
   // ---- global max over the parts that hold something
   float mx = -INFINITY;
   for (int i = tid; i < n_parts; i += kMergeThreads) {
-    const float2 ml = p.part_ml[part_row(i)];
-    if (ml.y > 0.f) mx = fmaxf(mx, ml.x);
+    const float2 v = p.part_ml[part_row(i)];
+    if (v.y > 0.f) mx = fmaxf(mx, v.x);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
@@ -50,19 +70,9 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
   for (int i = 0; i < kMergeThreads / kWave; ++i) mx = fmaxf(mx, red[i]);
 
   // ---- weighted sums, one head-dim element per thread, parts strided over the groups
-  const int grp = tid / D, d = tid % D;
   float o = 0.f, L = 0.f;
   for (int i0 = grp; i0 < n_parts; i0 += NGRP * UNR) {
-    float2 ml[UNR];
-    float a[UNR];
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      const int i = i0 + u * NGRP;
-      const int row = part_row(i < n_parts ? i : i0);
-      ml[u] = p.part_ml[row];
-      a[u] = p.part_acc[(long long)row * D + d];
-      if (i >= n_parts) ml[u].y = 0.f;
-    }
+    if (i0 != grp) load_batch(i0);
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
       const float wgt = (ml[u].y > 0.f) ? fast_exp2(ml[u].x - mx) : 0.f;

@@ -64,8 +64,7 @@ __device__ __forceinline__ void private_item(const DecodeParams& p, PrivLds& lds
 
   // -- the ranges this chunk overlaps: [range_first, range_first + nr), at most cnt
   const int r_first = it.range_first;
-  int nr = st.range_end - r_first;
-  if (nr > cnt) nr = cnt;
+  const int nr = it.n_ranges;
   for (int r = lane; r < nr; r += kWave) lds.ranges[wave][r] = ranges[r_first + r];
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();

@@ -290,6 +290,9 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
     h->tail_before.assign(cfg->max_requests, 0);
     h->streams.resize((size_t)cfg->max_requests * cfg->max_streams);
   } catch (...) { return fail(PASTA_E_NOMEM); }
+#ifdef PASTA_PHASE_CLOCKS
+  std::fprintf(stderr, "PASTA_CLOCKS byte offset in workspace: %zu\n", h->off_ml + (size_t)(h->part_rows_cap - 8192) * 8);
+#endif
   *out = h;
   return PASTA_OK;
 }
@@ -569,7 +572,19 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       int32_t rcur = ds.range_begin;
       for (int32_t t = 0; t < cum; t += (int32_t)priv_chunk) {
         while (rcur + 1 < ds.range_end && ranges[rcur + 1].cum <= t) rcur++;
-        items.push_back({i, t, std::min<int32_t>((int32_t)priv_chunk, cum - t), rcur});
+        DevItem it{};
+        it.stream = i;
+        it.tok_begin = t;
+        it.tok_count = std::min<int32_t>((int32_t)priv_chunk, cum - t);
+        it.range_first = rcur;
+        int32_t rlast = rcur;
+        while (rlast + 1 < ds.range_end && ranges[rlast + 1].cum < t + it.tok_count) rlast++;
+        it.n_ranges = rlast - rcur + 1;
+        it.req = q.req;
+        it.gather_pos = (int32_t)(gather_total + q.pc + t);
+        it.slot0 = ranges[rcur].start + (t - ranges[rcur].cum) * ranges[rcur].stride;
+        it.stride = it.n_ranges == 1 ? ranges[rcur].stride : 0;  // 0: rows come from the expanded list
+        items.push_back(it);
       }
       ds.item_end = (int32_t)items.size();
       if (gather_total + q.pc + cum > INT32_MAX) return PASTA_E_CAPACITY;
@@ -664,6 +679,11 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     p.Hq = c.n_q_heads;
     p.Hkv = Hkv;
     p.scale_log2e = c.softmax_scale * kLog2e;
+#ifdef PASTA_PHASE_CLOCKS
+    p.clock_row0 = h->part_rows_cap - 8192;  // the last 64 KiB of the (m, l) array
+#endif
+    p.single_req = reqs.size() == 1 ? 1 : 0;
+    p.req0 = reqs[0];
 
     if (a->prof_event_start && hipEventRecord((hipEvent_t)a->prof_event_start, st) != hipSuccess)
       return PASTA_E_DEVICE;

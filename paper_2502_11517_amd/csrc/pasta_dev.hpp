@@ -56,8 +56,15 @@ struct DevStream {      // one per decoding stream, call order
 struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it
   int32_t start, count, stride, cum;
 };
-struct DevItem {        // a chunk of one stream's private token list; range_first = the
-  int32_t stream, tok_begin, tok_count, range_first;  // range that holds token tok_begin
+struct DevItem {        // a chunk of one stream's private token list
+  int32_t stream, tok_begin, tok_count;
+  int32_t range_first;  // the range that holds token tok_begin
+  int32_t n_ranges;     // ranges the chunk overlaps
+  int32_t req;          // request of the stream
+  int32_t gather_pos;   // first entry of this chunk in dbg_gather_rows
+  int32_t slot0;        // n_ranges == 1: token j of the chunk is logical slot slot0 + j*stride
+  int32_t stride;
+  int32_t pad[3];
 };
 struct DevReq {         // one per request present in the call
   int32_t req;
@@ -88,12 +95,25 @@ struct DecodeParams {
   int priv_part_base;   // private partial row = priv_part_base + ((item*Hkv + g)*G + i)
   int Hq, Hkv;
   float scale_log2e;    // softmax_scale * log2(e): logits are kept in log2 units
+#ifdef PASTA_PHASE_CLOCKS
+  long long clock_row0; // first float2 slot of the phase-clock area (tuning builds only)
+#endif
+  int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
+  DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way
+                        //    to the first K/V load)
   int32_t inline_meta[kInlineMetaWords];  // the blob itself when meta == nullptr (small plans:
                                           // no host-to-device copy on the step's critical path)
 };
 
+// The metadata blob: device memory, or the copy inside the kernel arguments.  The inline copy
+// is addressed through the kernarg segment pointer (DecodeParams is always the first kernel
+// parameter, at offset 0), never through the address of the by-value parameter: taking that
+// address makes the compiler copy all of it to scratch memory.
 __device__ __forceinline__ const int32_t* meta_of(const DecodeParams& p) {
-  return p.meta ? p.meta : p.inline_meta;
+  if (p.meta) return p.meta;
+  typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+  kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, inline_meta));
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
