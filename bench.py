@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--event-every", type=int, default=8, help="time the attention kernels of every n-th step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB device copy (3x) before the loop: the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -100,6 +103,14 @@ def main():
         calls.append((s.h.prepare_append(l, req_step, ev_step, k_steps[t][l], v_steps[t][l]),
                       s.h.prepare_decode(l, w.dec_request, w.dec_stream, q_steps[t], out[l], flags=flags,
                                          prof_events=pe)))
+
+    if args.calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- warm-up: decode only (no state change), cycling the layers
     warm = [s.h.prepare_decode(l % L, w.dec_request, w.dec_stream, q_steps[0], out[l % L], flags=flags)

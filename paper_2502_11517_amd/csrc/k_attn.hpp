@@ -382,16 +382,28 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
     lw += __shfl_xor(lw, 32, kWave);
     if (q4 == 0) lds.lsum[w][nt * 16 + c16] = lw;
   }
-  __syncthreads();
+  // O^T goes through LDS (over the dead K/V tiles: 32 rows x 128 floats = 16 KB per row tile)
+  // so that every partial row leaves as one coalesced 512-byte line.  The stores are
+  // non-temporal: partials are read once, by the merge kernel, from another XCD, so there is
+  // no point in leaving them dirty in this XCD's L2 for the end-of-kernel write-back.
+  float* ot = reinterpret_cast<float*>(lds.kt);  // [32 rows][128 + 4 pad]
+  constexpr int OTS = 132;
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int r = rt * 32 + l32;
-    if (r < R) {
-      float* dst = p.part_acc + (part_row0 + r) * D + 32 * w + 4 * hh;
+    __syncthreads();  // rt == 0: lsum visible and tiles dead; rt > 0: previous row tile stored
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-        *reinterpret_cast<float4*>(dst + 8 * b) =
-            make_float4(O[rt][4 * b], O[rt][4 * b + 1], O[rt][4 * b + 2], O[rt][4 * b + 3]);
+    for (int b = 0; b < 4; ++b)
+      *reinterpret_cast<f32x4*>(ot + l32 * OTS + 32 * w + 8 * b + 4 * hh) =
+          f32x4{O[rt][4 * b], O[rt][4 * b + 1], O[rt][4 * b + 2], O[rt][4 * b + 3]};
+    __syncthreads();
+    // 256 threads = 8 rows x 32 lanes x 16 B per pass, 4 passes for the 32 rows
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int rr = pass * 8 + (tid >> 5), r = rt * 32 + rr;
+      if (r < R) {
+        const f32x4 val = *reinterpret_cast<const f32x4*>(ot + rr * OTS + 4 * (tid & 31));
+        __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + r) * D + 4 * (tid & 31)));
+      }
     }
   }
   if (w == 0 && q4 == 0) {

@@ -520,26 +520,21 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
 
     // ---- shared-prefix plan: only what the matrix-core kernel takes; the rest is private
     const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G);
-    int64_t pc_total = 0, max_rows = 1, priv_total = 0;
+    int64_t pc_total = 0, max_rows = 1;
     for (auto& q : reqs) {
       if (!mfma || q.pc < kTile || q.n_streams * G > kAttnMaxRows) q.pc = 0;
       pc_total += q.pc;
       if (q.pc) max_rows = std::max<int64_t>(max_rows, (int64_t)q.n_streams * G);
     }
-    for (int i = 0; i < n; ++i) {
-      int64_t cnt = lv[i].prefix_len - reqs[stream_req_idx[i]].pc;
-      for (int k = 0; k < lv[i].n_ranges; ++k) cnt += lv[i].at(k).count;
-      priv_total += cnt;
-    }
-    // Chunking.  All work-groups of the step should be resident at once (3 per CU with up to
-    // 32 stacked rows, else 2), so tokens per work item ~ total tokens * Hkv / resident slots,
-    // rounded up to the 64-token tile.
+    // Chunking.  Every chunk costs one partial row per stacked query row (written here, read
+    // by the merge), so chunks should be long; but the step wants at least one shared-prefix
+    // work-group per CU to keep enough loads in flight.  Tokens per chunk = the largest
+    // multiple of the 64-token tile that still gives kNumCUs prefix work-groups.  Private
+    // items stay at 128 tokens: they are few and their rows are scattered.
     int64_t priv_chunk = kPrivChunk, chunk_tokens = kTile;
     if (mfma) {
-      const int64_t slots = (int64_t)(max_rows <= 32 ? 3 : 2) * kNumCUs;
-      const int64_t want = ((pc_total + priv_total) * Hkv + slots - 1) / slots;
-      chunk_tokens = std::max<int64_t>(kTile, (want + kTile - 1) / kTile * kTile);
-      priv_chunk = std::min<int64_t>(chunk_tokens, kGatherMax);
+      chunk_tokens = std::max<int64_t>(kTile, pc_total * Hkv / kNumCUs / kTile * kTile);
+      priv_chunk = 128;
       if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
       if (h->tune_priv_chunk >= kTile) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / kTile * kTile, kGatherMax);
     }

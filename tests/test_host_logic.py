@@ -211,8 +211,8 @@ def test_plan_arithmetic_on_the_8k_prefix_8_stream_shape():
         priv = [v - 8192 for v in vis]
         assert plan[5] == 8192 and plan[0] == 8192 // 64 * 8
         assert plan[1] == -(-8192 // plan[4]) * 8 and plan[4] % 64 == 0
-        pchunk = min(int(plan[4]), 256)  # private items: same chunk, at most 256 tokens
-        assert plan[2] == sum(-(-p // pchunk) for p in priv)
+        assert plan[4] == 8192 * 8 // 256  # one prefix work-group per CU
+        assert plan[2] == sum(-(-p // 128) for p in priv)  # private items: 128 tokens
         assert plan[3] == plan[1] * 32 + plan[2] * 32
     # fp32 handles and NO_MFMA route everything through the private-segment kernel
     _, plan = _plan(h, w.dec_request, w.dec_stream, None, flags=B.DECODE_NO_MFMA)
