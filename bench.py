@@ -181,6 +181,13 @@ def main():
         got = W.bf16_bits_to_f32(to_host_bits(chk, w.dtype)).astype(np.float64)
         result_extra["parity_vs_oracle"] = {"max_abs": float(np.max(np.abs(got - ref))),
                                             "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+    # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (if present)
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "k_attn_config3.txt")
+    if os.path.exists(prof) and not args.no_mfma:
+        for line in open(prof):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                traffic = float(line.split("=")[1])
     res = {
         "metric": "multi-stream decode-attention stream-tokens/s (append + decode step, per layer)",
         "value": w.n * args.steps / elapsed,
@@ -199,8 +206,8 @@ def main():
                    "n_layers_cycled": L, "kv_layout": args.layout, "visibility": "maintained lists",
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "attention partials (k_prefix + k_private)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "k_attn (shared-prefix + private-segment partials, one launch)",
                      "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
         "whole_step": {"algorithmic_GBps": alg_bytes / (elapsed / args.steps) / 1e9},
         "cpu_baseline": cpu,
