@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--event-every", type=int, default=8, help="time the attention kernels of every n-th step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
+    ap.add_argument("--eager-append", action="store_true",
+                    help="run the KV-append as a launch of its own instead of letting it ride with the decode launch")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (3x) before the loop: the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -100,7 +102,8 @@ def main():
     for i in range(args.steps):
         t, l = divmod(i, L)
         pe = (evs[2 * (i // args.event_every)], evs[2 * (i // args.event_every) + 1]) if i % args.event_every == 0 else None
-        calls.append((s.h.prepare_append(l, req_step, ev_step, k_steps[t][l], v_steps[t][l]),
+        calls.append((s.h.prepare_append(l, req_step, ev_step, k_steps[t][l], v_steps[t][l],
+                                         flags=0 if args.eager_append else B.APPEND_DEFER),
                       s.h.prepare_decode(l, w.dec_request, w.dec_stream, q_steps[t], out[l], flags=flags,
                                          prof_events=pe)))
 
@@ -204,6 +207,7 @@ def main():
         "config": {"workload": "config 3: bf16 32q/8kv heads D=128, prefix 8192, 8 streams L~U[64,512] "
                                "right-aligned round-robin, append+decode per step",
                    "n_layers_cycled": L, "kv_layout": args.layout, "visibility": "maintained lists",
+                   "append": "eager (own launch)" if args.eager_append else "deferred (rides with the decode launch)",
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -121,9 +121,17 @@ int32_t pasta_attn_create(pasta_attn_config *cfg, pasta_attn **out);
  * and changes no state.  A token the interpreter defers (the paper's <sync/>
  * row) is simply not passed until it is to enter the pool.                   */
 enum {
-  PASTA_APPEND_RESERVE_ONLY = 1u /* assign slots and advance the bookkeeping, copy nothing:
+  PASTA_APPEND_RESERVE_ONLY = 1u, /* assign slots and advance the bookkeeping, copy nothing:
                                     the caller's own kernel writes the rows (out_slot says
                                     where); k_new / v_new may be NULL */
+  PASTA_APPEND_DEFER = 2u        /* bookkeeping now, copy later: the rows are copied into the
+                                    pool by the attention launch of the next decode_step on
+                                    the same layer (which reads them from k_new / v_new
+                                    wherever its lists name them), or by a small launch of
+                                    their own at the next call on the handle that cannot
+                                    take them along.  k_new / v_new must stay valid and
+                                    unchanged until that work has run.  Saves one launch
+                                    per append + decode step; ignored for more than 32 rows. */
 };
 
 typedef struct {

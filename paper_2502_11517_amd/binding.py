@@ -20,7 +20,7 @@ OK, E_INVAL, E_CAPACITY, E_NOMEM, E_DEVICE, E_STATE = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
 DECODE_PLAN_ONLY, DECODE_NO_MFMA = 1, 2
-APPEND_RESERVE_ONLY = 1
+APPEND_RESERVE_ONLY, APPEND_DEFER = 1, 2
 _ERR = {E_INVAL: "E_INVAL", E_CAPACITY: "E_CAPACITY", E_NOMEM: "E_NOMEM", E_DEVICE: "E_DEVICE",
         E_STATE: "E_STATE"}
 

@@ -100,7 +100,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
 
   // ---- decode the work item.  Token j of the item is logical slot slot0 + j * stride of
   // request `req`, except for "listed" gather items, whose rows come from LDS.
-  int req, g, R, n_tok, slot0, stride, gather_pos;
+  int req, g, R, n_tok, slot0, stride, gather_pos, pend0, pend_src0;
   long long part_row0;
   const int32_t* req_streams = nullptr;  // prefix, several requests: stacked row r is stream req_streams[r / G]
   int q_stream = 0;                      // gather: the one stream
@@ -112,6 +112,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
       rq.req = p.req0.req; rq.pc = p.req0.pc; rq.n_streams = p.req0.n_streams; rq.stream0 = 0;
       rq.wg_begin = p.req0.wg_begin; rq.n_chunks = p.req0.n_chunks;
       rq.chunk_tokens = p.req0.chunk_tokens; rq.part_base = p.req0.part_base;
+      rq.pend0 = p.req0.pend0; rq.pend_src0 = p.req0.pend_src0;
     } else {
       const DevReq* reqs = reinterpret_cast<const DevReq*>(meta + p.off_reqs);
       int qi = 0;
@@ -133,6 +134,8 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
     n_tok = min(rq.chunk_tokens, rq.pc - slot0);
     part_row0 = rq.part_base + (long long)(g * rq.n_chunks + c) * R;
     gather_pos = slot0;
+    pend0 = rq.pend0;
+    pend_src0 = rq.pend_src0;
   } else {
     const int item = wi / p.Hkv;
     g = wi % p.Hkv;
@@ -145,6 +148,8 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
     stride = it.stride;
     part_row0 = p.priv_part_base + (long long)(item * p.Hkv + g) * G;
     gather_pos = it.gather_pos;
+    pend0 = it.pend0;
+    pend_src0 = it.pend_src0;
     listed = it.n_ranges > 1;
     if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> physical row
       const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
@@ -159,7 +164,11 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
           if (lds.ranges[mid].cum <= tok) lo = mid; else hi = mid - 1;
         }
         const DevRange rg = lds.ranges[lo];
-        lds.rows[j] = phys_row(p.lay, p.page_table, req, rg.start + (tok - rg.cum) * rg.stride);
+        const int slot = rg.start + (tok - rg.cum) * rg.stride;
+        const int phys = phys_row(p.lay, p.page_table, req, slot);
+        // rows of a deferred append are kept as -(1 + row in k_pend)
+        lds.rows[j] = slot >= pend0 ? -1 - (pend_src0 + (slot - pend0)) : phys;
+        if (p.dbg_rows && g == 0) p.dbg_rows[gather_pos + j] = phys;
       }
       __syncthreads();
     }
@@ -170,32 +179,44 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
   const char* kb = reinterpret_cast<const char*>(p.k);
   const char* vb = reinterpret_cast<const char*>(p.v);
   const int piece = tid & 15, rbase = tid >> 4;  // rbase 0..15
-  auto row_of = [&](int j) -> int {  // branch-free so that a tile's loads issue together
+  const char* kpend = reinterpret_cast<const char*>(p.k_pend);
+  const char* vpend = reinterpret_cast<const char*>(p.v_pend);
+  auto phys_of = [&](int j) -> int {  // physical pool row of token j (not for listed items)
     const int t = slot0 + j * stride;
-    int phys;
     if constexpr (PAGED) {
       const int pp = p.page_table[req * p.lay.pages_per_request + (t >> p.lay.page_shift)];
-      phys = (pp << p.lay.page_shift) | (t & p.lay.page_mask);
+      return (pp << p.lay.page_shift) | (t & p.lay.page_mask);
     } else {
-      phys = req * p.lay.pool_tokens + t;
+      return req * p.lay.pool_tokens + t;
     }
+  };
+  // Source of token j's row: the pool, or the rows of a deferred append.  Branch-free so that
+  // a tile's loads issue together.  Returns the byte offset; is_pend picks the base.
+  auto src_of = [&](int j, bool& is_pend) -> long long {
+    const int t = slot0 + j * stride;
+    int phys = phys_of(j);
+    int pidx = pend_src0 + (t - pend0);
+    is_pend = t >= pend0;
     if constexpr (GATHER) {
-      const int from_list = lds.rows[j];  // j < kGatherMax; unused unless listed
-      phys = listed ? from_list : phys;
+      const int code = lds.rows[j];  // j < kGatherMax; meaningful only for listed items
+      if (listed) { is_pend = code < 0; pidx = -1 - code; phys = code; }
     }
-    return phys;
+    const long long off_pool = (elem_off(p.lay, is_pend ? 0 : phys, g) + piece * 8) * 2;
+    const long long off_pend = (((long long)pidx * p.Hkv + g) * D + piece * 8) * 2;
+    return is_pend ? off_pend : off_pool;
   };
   auto load_tile = [&](TileRegs& tr, int tile) {
     long long off[4];
+    bool pnd[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = min(tile * kTile + rbase + 16 * i, n_tok - 1);  // rows past the end repeat the last one
-      off[i] = (elem_off(p.lay, row_of(j), g) + piece * 8) * 2;
+      off[i] = src_of(j, pnd[i]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      tr.k[i] = *reinterpret_cast<const u32x4*>(kb + off[i]);
-      tr.v[i] = *reinterpret_cast<const u32x4*>(vb + off[i]);
+      tr.k[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? kpend : kb) + off[i]);
+      tr.v[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? vpend : vb) + off[i]);
     }
   };
   TileRegs ta, tb;
@@ -225,10 +246,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
     }
   }
 
-  if (p.dbg_rows && g == 0) {
+  if (p.dbg_rows && g == 0 && !listed) {  // listed items reported their rows while expanding
     const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
     for (int j = tid; j < n_tok; j += kAttnThreads) {
-      const int phys = row_of(j);
+      const int phys = phys_of(j);
       if constexpr (GATHER) {
         p.dbg_rows[gather_pos + j] = phys;
       } else {
@@ -425,6 +446,22 @@ template <int RT, bool PAGED>
 __global__ __launch_bounds__(kAttnThreads, (RT == 1 ? 3 : (RT == 2 ? 2 : 1))) void k_attn(DecodeParams p) {
   __shared__ AttnLds<RT> lds;
   const int32_t* meta = meta_of(p);
+  if (p.pend_n > 0) {
+    // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads
+    // those pool rows -- lists that name them are served from k_pend / v_pend -- so the copy
+    // needs no ordering against the rest of the launch.
+    const int pieces = p.Hkv * 16;  // 16-byte pieces per row
+    const int total = 2 * p.pend_n * pieces;
+    const int32_t* dst = pend_dst_of(p);
+    for (int t = blockIdx.x * kAttnThreads + threadIdx.x; t < total; t += gridDim.x * kAttnThreads) {
+      const bool is_v = t >= total / 2;
+      const int u = is_v ? t - total / 2 : t;
+      const int row = u / pieces, gh = (u % pieces) >> 4, pc16 = u & 15;
+      const u32x4 val = reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
+      char* base = reinterpret_cast<char*>(const_cast<void*>(is_v ? p.v : p.k));
+      *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, dst[row], gh) + pc16 * 8) * 2) = val;
+    }
+  }
   const int n_priv_wgs = p.n_mfma_items * p.Hkv;
   if ((int)blockIdx.x < n_priv_wgs)
     attn_item<1, PAGED, true>(p, reinterpret_cast<AttnLds<1>&>(lds), meta, blockIdx.x);

@@ -54,6 +54,14 @@ struct pasta_attn {
   // workspace carve-up (byte offsets)
   size_t off_page_table = 0, off_meta = 0, meta_bytes = 0, off_ml = 0, off_acc = 0;
   int64_t part_rows_cap = 0;
+  // a deferred append (PASTA_APPEND_DEFER): its copy is done by the next decode_step's launch
+  struct Pending {
+    bool active = false;
+    int layer = 0, n_rows = 0;
+    const void *k_new = nullptr, *v_new = nullptr;
+    int32_t dst_rows[kAppendInline]{};
+    std::vector<int32_t> req_pend0, req_src0;  // per request: first deferred slot, its row in k_new
+  } pending;
   int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // PASTA_PREFIX_CHUNK / PASTA_PRIV_CHUNK (tokens; 0 = heuristic)
   // device-side readiness (deferred so that the host logic works without a GPU)
   bool device_ready = false;
@@ -221,6 +229,54 @@ int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodePar
   return D == 64 ? launch_merge_g<uint16_t, 64>(h->G, grid, st, p) : launch_merge_g<uint16_t, 128>(h->G, grid, st, p);
 }
 
+int launch_append(pasta_attn* h, int layer, int n_rows, const void* k_new, const void* v_new,
+                  const int32_t* dst_rows) {
+  const pasta_attn_config& c = h->cfg;
+  hipStream_t st = (hipStream_t)c.hip_stream;
+  AppendParams p{};
+  p.k = (char*)c.k_pool + (size_t)layer * h->layer_elems * h->elem;
+  p.v = (char*)c.v_pool + (size_t)layer * h->layer_elems * h->elem;
+  p.lay = h->lay;
+  p.Hkv = c.n_kv_heads;
+  p.pieces_per_head = c.head_dim * h->elem / 16;
+  p.elem_shift = h->elem == 4 ? 2 : 1;
+  const size_t row_bytes = (size_t)c.n_kv_heads * c.head_dim * h->elem;
+  if (n_rows <= kAppendInline) {
+    p.k_new = (const uint4*)k_new;
+    p.v_new = (const uint4*)v_new;
+    p.n_rows = n_rows;
+    p.dst_rows = nullptr;
+    std::memcpy(p.inline_rows, dst_rows, (size_t)n_rows * 4);
+    const long long total = 2ll * n_rows * c.n_kv_heads * p.pieces_per_head;
+    k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p);
+    return hipGetLastError() == hipSuccess ? PASTA_OK : PASTA_E_DEVICE;
+  }
+  // large appends (prefill) go in pieces that fit one staging slot
+  const size_t per = h->meta_bytes / 4;
+  for (size_t lo = 0; lo < (size_t)n_rows; lo += per) {
+    const size_t n = std::min(per, (size_t)n_rows - lo);
+    const int32_t* dev = nullptr;
+    int rc = upload_meta(h, dst_rows + lo, n * 4, &dev);
+    if (rc != PASTA_OK) return rc;
+    p.dst_rows = dev;
+    p.n_rows = (int)n;
+    p.k_new = (const uint4*)((const char*)k_new + lo * row_bytes);
+    p.v_new = (const uint4*)((const char*)v_new + lo * row_bytes);
+    const long long total = 2ll * (long long)n * c.n_kv_heads * p.pieces_per_head;
+    k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p);
+    if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
+  }
+  return PASTA_OK;
+}
+
+// Performs a deferred append's copy with K1 (when no decode_step took it along).
+int flush_pending(pasta_attn* h) {
+  if (!h->pending.active) return PASTA_OK;
+  h->pending.active = false;
+  return launch_append(h, h->pending.layer, h->pending.n_rows, h->pending.k_new, h->pending.v_new,
+                       h->pending.dst_rows);
+}
+
 }  // namespace
 
 // =============================================================================== create
@@ -300,6 +356,7 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
 extern "C" int32_t pasta_attn_destroy(pasta_attn* h) {
   if (!h) return PASTA_OK;
   if (h->magic != kMagic) return PASTA_E_STATE;
+  if (h->device_ready) (void)flush_pending(h);  // a deferred append still owes its copy
   h->magic = 0;
   if (h->device_ready) {
     for (int i = 0; i < kRing; ++i) (void)hipEventDestroy(h->ring_ev[i]);
@@ -374,47 +431,40 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
     }
   } catch (...) { return PASTA_E_NOMEM; }
 
-  // ---- enqueue K1
+  // ---- enqueue K1, or leave the copy to the next decode_step (PASTA_APPEND_DEFER)
   int rc = PASTA_OK;
   if (!reserve_only) {
-  rc = ensure_device(h);
-  if (rc != PASTA_OK) return rc;
-  hipStream_t st = (hipStream_t)c.hip_stream;
-  AppendParams p{};
-  p.k_new = (const uint4*)a->k_new;
-  p.v_new = (const uint4*)a->v_new;
-  p.k = (char*)c.k_pool + (size_t)a->layer * h->layer_elems * h->elem;
-  p.v = (char*)c.v_pool + (size_t)a->layer * h->layer_elems * h->elem;
-  p.lay = h->lay;
-  p.n_rows = a->n_rows;
-  p.Hkv = c.n_kv_heads;
-  p.pieces_per_head = c.head_dim * h->elem / 16;
-  p.elem_shift = h->elem == 4 ? 2 : 1;
-  if (a->n_rows <= kAppendInline) {
-    p.dst_rows = nullptr;
-    std::memcpy(p.inline_rows, dst_rows.data(), (size_t)a->n_rows * 4);
-    const long long total = 2ll * a->n_rows * c.n_kv_heads * p.pieces_per_head;
-    k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p);
-    if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
-  } else {
-    // large appends (prefill) go in pieces that fit one staging slot
-    const size_t per = h->meta_bytes / 4;
-    for (size_t lo = 0; lo < (size_t)a->n_rows; lo += per) {
-      const size_t n = std::min(per, (size_t)a->n_rows - lo);
-      const int32_t* dev = nullptr;
-      rc = upload_meta(h, dst_rows.data() + lo, n * 4, &dev);
-      if (rc != PASTA_OK) return rc;
-      AppendParams q = p;
-      q.dst_rows = dev;
-      q.n_rows = (int)n;
-      const size_t row_bytes = (size_t)c.n_kv_heads * c.head_dim * h->elem;
-      q.k_new = (const uint4*)((const char*)a->k_new + lo * row_bytes);
-      q.v_new = (const uint4*)((const char*)a->v_new + lo * row_bytes);
-      const long long total = 2ll * (long long)n * c.n_kv_heads * p.pieces_per_head;
-      k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(q);
-      if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
+    rc = ensure_device(h);
+    if (rc != PASTA_OK) return rc;
+    rc = flush_pending(h);  // at most one deferred append is outstanding
+    if (rc != PASTA_OK) return rc;
+    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline;
+    std::vector<int32_t> p0, s0;
+    if (defer) {  // rows of one request must be consecutive in the call: slot t <-> row src0 + (t - pend0)
+      p0.assign(c.max_requests, INT32_MAX);
+      s0.assign(c.max_requests, 0);
+      std::vector<int32_t> last(c.max_requests, -2);
+      for (int i = 0; i < a->n_rows && defer; ++i) {
+        const int r = a->request_id[i];
+        if (p0[r] == INT32_MAX) { p0[r] = slots[i]; s0[r] = i; }
+        else if (last[r] != i - 1) defer = false;
+        last[r] = i;
+      }
     }
-  }
+    if (defer) {
+      pasta_attn::Pending& pd = h->pending;
+      pd.active = true;
+      pd.layer = a->layer;
+      pd.n_rows = a->n_rows;
+      pd.k_new = a->k_new;
+      pd.v_new = a->v_new;
+      std::memcpy(pd.dst_rows, dst_rows.data(), (size_t)a->n_rows * 4);
+      pd.req_pend0.swap(p0);
+      pd.req_src0.swap(s0);
+    } else {
+      rc = launch_append(h, a->layer, a->n_rows, a->k_new, a->v_new, dst_rows.data());
+      if (rc != PASTA_OK) return rc;
+    }
   }
 
   // ---- commit
@@ -504,6 +554,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         DevReq q{};
         q.req = r;
         q.pc = INT32_MAX;
+        q.pend0 = INT32_MAX;
         reqs.push_back(q);
       }
       DevReq& q = reqs[req_idx_of[r]];
@@ -579,6 +630,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         it.gather_pos = (int32_t)(gather_total + q.pc + t);
         it.slot0 = ranges[rcur].start + (t - ranges[rcur].cum) * ranges[rcur].stride;
         it.stride = it.n_ranges == 1 ? ranges[rcur].stride : 0;  // 0: rows come from the expanded list
+        it.pend0 = INT32_MAX;
         items.push_back(it);
       }
       ds.item_end = (int32_t)items.size();
@@ -646,6 +698,24 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     int rc = ensure_device(h);
     if (rc != PASTA_OK) return rc;
     hipStream_t st = (hipStream_t)c.hip_stream;
+    // a deferred append rides along with the matrix-core launch of its layer; otherwise K1 runs now
+    const bool take_pending = h->pending.active && mfma && h->pending.layer == a->layer;
+    if (h->pending.active && !take_pending) {
+      rc = flush_pending(h);
+      if (rc != PASTA_OK) return rc;
+    }
+    if (take_pending) {
+      const pasta_attn::Pending& pd = h->pending;
+      for (auto& q : reqs) { q.pend0 = pd.req_pend0[q.req]; q.pend_src0 = pd.req_src0[q.req]; }
+      for (auto& it : items) { it.pend0 = pd.req_pend0[it.req]; it.pend_src0 = pd.req_src0[it.req]; }
+      p.k_pend = pd.k_new;
+      p.v_pend = pd.v_new;
+      p.pend_n = pd.n_rows;
+      std::memcpy(p.pend_dst, pd.dst_rows, sizeof(p.pend_dst));
+      // the blob was built before these fields were known: patch the two tables in place
+      std::memcpy(blob.data() + p.off_reqs, reqs.data(), reqs.size() * sizeof(DevReq));
+      std::memcpy(blob.data() + p.off_items, items.data(), items.size() * sizeof(DevItem));
+    }
     if (blob.size() <= (size_t)kInlineMetaWords) {  // small plan: rides in the kernel arguments
       p.meta = nullptr;
       std::memcpy(p.inline_meta, blob.data(), blob.size() * 4);
@@ -686,6 +756,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
       rc = launch_attn((int)max_rows, dim3(grid), st, p);
       if (rc != PASTA_OK) return rc;
+      if (take_pending) h->pending.active = false;
     } else if (!items.empty()) {
       const unsigned waves = (unsigned)items.size() * Hkv;
       rc = launch_private(h, dim3((waves + 3) / 4), st, p);

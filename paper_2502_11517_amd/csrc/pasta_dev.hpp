@@ -64,7 +64,9 @@ struct DevItem {        // a chunk of one stream's private token list
   int32_t gather_pos;   // first entry of this chunk in dbg_gather_rows
   int32_t slot0;        // n_ranges == 1: token j of the chunk is logical slot slot0 + j*stride
   int32_t stride;
-  int32_t pad[3];
+  int32_t pend0;        // slots >= pend0 of the request are rows of a deferred append: slot t
+  int32_t pend_src0;    //   is row pend_src0 + (t - pend0) of k_pend / v_pend (pend0 = INT_MAX: none)
+  int32_t pad;
 };
 struct DevReq {         // one per request present in the call
   int32_t req;
@@ -75,6 +77,8 @@ struct DevReq {         // one per request present in the call
   int32_t n_chunks;     // split-K chunks of [0, pc)
   int32_t chunk_tokens; // tokens per chunk (multiple of the LDS tile)
   int32_t part_base;    // first partial row: row = part_base + ((g*n_chunks + c)*R + r)
+  int32_t pend0;        // deferred append, as in DevItem
+  int32_t pend_src0;
 };
 
 struct DecodeParams {
@@ -98,6 +102,12 @@ struct DecodeParams {
 #ifdef PASTA_PHASE_CLOCKS
   long long clock_row0; // first float2 slot of the phase-clock area (tuning builds only)
 #endif
+  // A deferred append (PASTA_APPEND_DEFER) rides along: its rows are read from k_pend / v_pend
+  // ([row][Hkv][D]) wherever a list names them, and copied to the pool by the first work-groups.
+  const void* k_pend;
+  const void* v_pend;
+  int pend_n;           // rows of the deferred append (0: none)
+  int32_t pend_dst[32]; // their physical rows
   int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
   DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way
                         //    to the first K/V load)
@@ -114,6 +124,13 @@ __device__ __forceinline__ const int32_t* meta_of(const DecodeParams& p) {
   typedef const char __attribute__((address_space(4))) * kernarg_ptr;
   kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, inline_meta));
+}
+
+__device__ __forceinline__ const int32_t* pend_dst_of(const DecodeParams& p) {
+  (void)p;
+  typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+  kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, pend_dst));
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

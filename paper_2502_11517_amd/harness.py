@@ -56,7 +56,7 @@ class Session:
                              stream=self.stream.cuda_stream, page_table=w.page_table)
         self.n_done = 0
 
-    def append_events(self, hi: int, layer: int = 0, chunk: int = 8192, lo: int | None = None):
+    def append_events(self, hi: int, layer: int = 0, chunk: int = 8192, lo: int | None = None, flags: int = 0):
         """Appends events [n_done, hi) of the workload's history (K/V rows from the generator)."""
         w = self.w
         pos = self.n_done if lo is None else lo
@@ -64,8 +64,9 @@ class Session:
             b = min(hi, pos + chunk)
             k, v = w.kv_rows(pos, b)
             kd, vd = to_device(k, w.dtype, self.device), to_device(v, w.dtype, self.device)
+            self._keep_rows = (kd, vd)  # a deferred append reads them later
             self.h.append_kv(layer, w.ev_request[pos:b], w.ev_stream[pos:b], kd, vd,
-                             parent_stream=w.ev_parent[pos:b])
+                             parent_stream=w.ev_parent[pos:b], flags=flags)
             pos = b
         if layer == 0 and lo is None:
             self.n_done = hi

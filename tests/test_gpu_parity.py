@@ -352,3 +352,75 @@ def test_maintained_lists_on_random_fork_histories_equal_dense_mask(seed):
         ref, _ = oracle.attention_dense(op.g, op.k, op.v, 0, mask, q[i], w.scale)
         check_close(got[i], ref, w.dtype, f"stream {i}")
     s.close()
+
+
+# ------------------------------------------------------------------------- deferred append
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_deferred_append_rides_with_the_decode_launch(layout):
+    """PASTA_APPEND_DEFER: the step's rows are read from k_new / v_new by the attention launch,
+    which also copies them into the pool; outputs and the final pool must be what the eager
+    append gives."""
+    w = W.config3(steps=6, prefix=1500, n_streams=5)
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR))
+    s.append_events(w.n_prefill)
+    op.append_events(w.n_prefill)
+    keep = []
+    for step in range(w.steps):
+        hi = w.n_events(step)
+        s.append_events(hi, chunk=w.n, flags=B.APPEND_DEFER)
+        keep.append(s._keep_rows)
+        op.append_events(hi)
+        _check_step(w, s, op, step, explicit=(step % 2 == 0), what=f"deferred step {step}")
+    _check_pool(w, s, op)
+    s.close()
+
+
+def test_deferred_rows_in_the_prefix_and_in_other_streams_lists():
+    from paper_2502_11517_amd.harness import to_device
+    # (a) a single stream with no fork: the deferred row is the last row of its prefix
+    w = W.single_request("nofork", "bf16", 8, 2, 128, 1.0, 5, 700, [1], "random", k_std=128 ** -0.5)
+    w.ev_stream[:] = 0
+    w.ev_parent[:] = -1
+    w.dec_stream[:] = 0
+    w.anc_slots = [[]]
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill - 1)
+    s.append_events(w.n_prefill, flags=B.APPEND_DEFER)
+    _check_step(w, s, op)
+    _check_pool(w, s, op)
+    s.close()
+    # (b) explicit lists that name rows another stream appended in the deferred call, paged pool
+    w = W.single_request("cross", "bf16", 8, 2, 128, 1.0, 6, 300, [40, 50, 60], "random", k_std=128 ** -0.5)
+    n0 = w.n_prefill
+    w.page_tokens, w.pages_per_request = 16, -(-w.pool_tokens // 16)
+    w.n_phys_pages = w.pages_per_request + 5
+    w.page_table = np.random.default_rng(3).permutation(w.n_phys_pages)[:w.pages_per_request].astype(np.int32).reshape(1, -1)
+    s = _session(w)
+    op = OraclePool(w).append_events(n0)
+    s.append_events(n0 - 3)
+    s.append_events(n0, flags=B.APPEND_DEFER)          # the last three rows are deferred
+    q = w.q(0)
+    qd = to_device(q, w.dtype, s.device)
+    out = torch.empty_like(qd)
+    lists = ([300, 300, 0], [0, 1, 2, 4], [n0 - 3, n0 - 5, 10, n0 - 2], [3, 5, 20, 2], [1, 1, 7, 1])
+    s.h.decode_step(0, w.dec_request, w.dec_stream, qd, out, lists=lists)
+    ref, _ = oracle.attention(op.g, op.k, op.v, w.dec_request, *lists, q, w.scale)
+    check_close(_out64(w, out), ref, w.dtype, "lists over deferred rows")
+    _check_pool(w, s, op)
+    s.close()
+
+
+def test_deferred_append_falls_back_when_it_cannot_ride():
+    """Interleaved requests in one call, a decode on another layer, a second append: K1 runs."""
+    w = W.config4(n_requests=3, seed=77, pmin=100, pmax=300)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill - 40)
+    lo = w.n_prefill - 40
+    s.append_events(w.n_prefill - 20, flags=B.APPEND_DEFER)   # request 2's rows only: consecutive
+    s.append_events(w.n_prefill, flags=B.APPEND_DEFER)        # flushes the first, defers the second
+    _check_step(w, s, op)
+    _check_pool(w, s, op)
+    s.close()
