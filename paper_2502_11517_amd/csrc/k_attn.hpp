@@ -81,7 +81,7 @@ struct TileRegs { u32x4 k[4], v[4]; };  // one thread's share of a 64-token tile
 // Phase clocks for kernel tuning (compiled in only with -DPASTA_PHASE_CLOCKS): thread 0 of every
 // work-group stores the 100 MHz wall clock at a few points into the tail of the partials buffer.
 #ifdef PASTA_PHASE_CLOCKS
-#define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < 1024) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
+#define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < 512) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
     __builtin_bit_cast(float2, (unsigned long long)__builtin_amdgcn_s_memrealtime()); } while (0)
 #else
 #define PASTA_CLK(n) do {} while (0)
@@ -123,9 +123,12 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
       rq = reqs[qi];
       req_streams = meta + p.off_req_streams + rq.stream0;
     }
+    // kv head = work-group index mod Hkv: with 8 kv heads every work-group of head g (private
+    // items included, their index is item * Hkv + g) lands on XCD g, whose L2 then holds all of
+    // that head's partials for the merge
     const int wl = wi - rq.wg_begin;
-    const int c = wl % rq.n_chunks;
-    g = wl / rq.n_chunks;
+    const int c = wl / p.Hkv;
+    g = wl % p.Hkv;
     req = rq.req;
     R = rq.n_streams * G;
     n_req_streams = rq.n_streams;
@@ -473,7 +476,7 @@ inline int launch_attn(int max_rows, dim3 grid, hipStream_t st, const DecodePara
   if (max_rows > kAttnMaxRows) return PASTA_E_INVAL;
   const bool paged = p.lay.paged != 0;
   if (max_rows <= 32) {
-    if (paged) k_attn<1, true><<<grid, kAttnThreads, 0, st>>>(p); else k_attn<1, false><<<grid, kAttnThreads, 0, st>>>(p);
+    return PASTA_E_INVAL;  // served by k_attn_w
   } else if (max_rows <= 64) {
     if (paged) k_attn<2, true><<<grid, kAttnThreads, 0, st>>>(p); else k_attn<2, false><<<grid, kAttnThreads, 0, st>>>(p);
   } else {

@@ -1,0 +1,386 @@
+// K2 + K3 on the matrix cores for up to 32 stacked query rows -- the wave-autonomous form.
+//
+// Same work items as k_attn (shared-prefix chunks for all stacked rows of a request,
+// arxiv 2502.11517 Section 3 "Efficiency" / the appendix on the naive interpreter; gathered
+// private rows per stream, Figure 2c), same numerics, different schedule.  A decode step is a
+// chain of latencies more than a stream of bytes: what bounds it is how many bytes are in
+// flight and how long a tile takes from "data arrived" to "accumulated".  So here every
+// WAVEFRONT is its own pipeline and there is no work-group barrier in the loop:
+//   * a wave owns 32-token blocks w, w+4, ... of the item; a block's loads (16 x 16 B per
+//     lane) land in registers, go to LDS, and the registers at once take the next block's
+//     loads, which stay in flight while the current block is computed;
+//   * block -> the wave's private LDS tile (16-byte XOR swizzle), then
+//     S^T[32 tok x 32 rows] with v_mfma_f32_32x32x16_bf16 (A = K rows, B = Q rows from LDS);
+//   * online softmax in registers: a lane holds 16 tokens of one row, its partner lane
+//     (lane ^ 32) the other 16 -- one lane exchange per block for the row max;
+//   * P = 2^(S - m) goes to bf16 IN REGISTERS: the S^T accumulator layout is already the
+//     B-operand layout of the next MFMA for a suitable token order inside the contraction
+//     (slot (ks, half, e) <-> token 16 ks + 8 (e / 4) + 4 half + e % 4), and V^T is fetched
+//     from LDS with the transposing read in exactly that order;
+//   * O^T[128 x 32 rows] += V^T P^T, four 32-row M-tiles per wave.
+// The four waves' (m, l, O) are combined once, at the end, through LDS, and leave as
+// coalesced 512-byte stores (they stay in this XCD's L2, where the merge of the same kv head looks for them).  Logits are kept in log2 units.
+#pragma once
+#include "k_attn.hpp"
+
+namespace pasta {
+
+constexpr int kWBlock = 32;  // tokens per wave block
+
+struct AttnWTile {             // one wave's 16 KB: K and V block, later its O^T on the way out
+  u32x4 kt[kWBlock * 16];      // K block [row][16 pieces], piece p of row r at p ^ (r & 15)
+  u32x4 vt[kWBlock * 16];      // V block, same swizzle
+};
+
+struct AttnWLds {
+  AttnWTile tile[4];           // first member: wave w's area starts at byte w * 16 KB
+  u32x4 q[32 * 16];            // stacked Q rows, same swizzle (rows >= R are zero)
+  float mw[4][32], lw[4][32];  // per-wave row max / row sum at the end of the item
+  int rows[kGatherMax];        // listed gather items: row code of every token
+  DevRange ranges[kGatherMax]; // listed gather items: the ranges the item overlaps
+};
+
+struct BlockRegs { u32x4 k[8], v[8]; };  // one lane's share of a 32-token block
+
+template <bool PAGED, bool GATHER>
+__device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds, const int32_t* meta, int wi) {
+  constexpr int D = 128;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int G = p.Hq / p.Hkv;
+  PASTA_CLK(0);
+
+  // ---- decode the work item (as in attn_item)
+  int req, g, R, n_tok, slot0, stride, gather_pos, pend0, pend_src0;
+  long long part_row0;
+  const int32_t* req_streams = nullptr;
+  int q_stream = 0, n_req_streams = 0;
+  bool listed = false;
+  if constexpr (!GATHER) {
+    DevReq rq;
+    if (p.single_req) {  // scalar loads from the kernel arguments
+      rq.req = p.req0.req; rq.pc = p.req0.pc; rq.n_streams = p.req0.n_streams; rq.stream0 = 0;
+      rq.wg_begin = p.req0.wg_begin; rq.n_chunks = p.req0.n_chunks;
+      rq.chunk_tokens = p.req0.chunk_tokens; rq.part_base = p.req0.part_base;
+      rq.pend0 = p.req0.pend0; rq.pend_src0 = p.req0.pend_src0;
+    } else {
+      const DevReq* reqs = reinterpret_cast<const DevReq*>(meta + p.off_reqs);
+      int qi = 0;
+      for (; qi < p.n_reqs - 1; ++qi) {
+        const int b = reqs[qi].wg_begin;
+        if (wi >= b && wi < b + reqs[qi].n_chunks * p.Hkv) break;
+      }
+      rq = reqs[qi];
+      req_streams = meta + p.off_req_streams + rq.stream0;
+    }
+    // kv head = work-group index mod Hkv: with 8 kv heads every work-group of head g (private
+    // items included, their index is item * Hkv + g) lands on XCD g, whose L2 then holds all of
+    // that head's partials for the merge
+    const int wl = wi - rq.wg_begin;
+    const int c = wl / p.Hkv;
+    g = wl % p.Hkv;
+    req = rq.req;
+    R = rq.n_streams * G;
+    n_req_streams = rq.n_streams;
+    slot0 = c * rq.chunk_tokens;
+    stride = 1;
+    n_tok = min(rq.chunk_tokens, rq.pc - slot0);
+    part_row0 = rq.part_base + (long long)(g * rq.n_chunks + c) * R;
+    gather_pos = slot0;
+    pend0 = rq.pend0;
+    pend_src0 = rq.pend_src0;
+  } else {
+    const int item = wi / p.Hkv;
+    g = wi % p.Hkv;
+    const DevItem it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item];
+    req = it.req;
+    R = G;
+    q_stream = it.stream;
+    n_tok = it.tok_count;
+    slot0 = it.slot0;
+    stride = it.stride;
+    part_row0 = p.priv_part_base + (long long)(item * p.Hkv + g) * G;
+    gather_pos = it.gather_pos;
+    pend0 = it.pend0;
+    pend_src0 = it.pend_src0;
+    listed = it.n_ranges > 1;
+    if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> row code
+      const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
+      const int nr = it.n_ranges;
+      for (int r = tid; r < nr; r += kAttnThreads) lds.ranges[r] = ranges[it.range_first + r];
+      __syncthreads();
+      for (int j = tid; j < n_tok; j += kAttnThreads) {
+        const int tok = it.tok_begin + j;
+        int lo = 0, hi = nr - 1;  // last range with cum <= tok
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (lds.ranges[mid].cum <= tok) lo = mid; else hi = mid - 1;
+        }
+        const DevRange rg = lds.ranges[lo];
+        const int slot = rg.start + (tok - rg.cum) * rg.stride;
+        const int phys = phys_row(p.lay, p.page_table, req, slot);
+        lds.rows[j] = slot >= pend0 ? -1 - (pend_src0 + (slot - pend0)) : phys;  // deferred rows: -(1 + row)
+        if (p.dbg_rows && g == 0) p.dbg_rows[gather_pos + j] = phys;
+      }
+      __syncthreads();
+    }
+  }
+  const int n_blocks = (n_tok + kWBlock - 1) / kWBlock;
+
+  // ---- block loads: lane -> piece (lane & 15) of rows (lane >> 4) + 4 i, i < 8
+  const char* kb = reinterpret_cast<const char*>(p.k);
+  const char* vb = reinterpret_cast<const char*>(p.v);
+  const char* kpend = reinterpret_cast<const char*>(p.k_pend);
+  const char* vpend = reinterpret_cast<const char*>(p.v_pend);
+  const int piece = lane & 15, rbase = lane >> 4;  // rbase 0..3
+  auto phys_of = [&](int j) -> int {  // physical pool row of token j (not for listed items)
+    const int t = slot0 + j * stride;
+    if constexpr (PAGED) {
+      const int pp = p.page_table[req * p.lay.pages_per_request + (t >> p.lay.page_shift)];
+      return (pp << p.lay.page_shift) | (t & p.lay.page_mask);
+    } else {
+      return req * p.lay.pool_tokens + t;
+    }
+  };
+  auto src_of = [&](int j, bool& is_pend) -> long long {  // branch-free: a block's loads issue together
+    const int t = slot0 + j * stride;
+    int phys = phys_of(j);
+    int pidx = pend_src0 + (t - pend0);
+    is_pend = t >= pend0;
+    if constexpr (GATHER) {
+      const int code = lds.rows[j];  // j < kGatherMax; meaningful only for listed items
+      if (listed) { is_pend = code < 0; pidx = -1 - code; phys = code; }
+    }
+    const long long off_pool = (elem_off(p.lay, is_pend ? 0 : phys, g) + piece * 8) * 2;
+    const long long off_pend = (((long long)pidx * p.Hkv + g) * D + piece * 8) * 2;
+    return is_pend ? off_pend : off_pool;
+  };
+  auto load_block = [&](BlockRegs& br, int b) {
+    long long off[8];
+    bool pnd[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int j = min(b * kWBlock + rbase + 4 * i, n_tok - 1);  // rows past the end repeat the last one
+      off[i] = src_of(j, pnd[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      br.k[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? kpend : kb) + off[i]);
+      br.v[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? vpend : vb) + off[i]);
+    }
+  };
+  BlockRegs br;
+  if (w < n_blocks) load_block(br, w);          // first: nothing else on the way to these loads
+  PASTA_CLK(1);
+
+  // ---- stacked Q rows -> LDS (loads issued behind the blocks')
+  {
+    const u32x4* qg = reinterpret_cast<const u32x4*>(p.q);
+    u32x4 qr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int idx = tid + i * kAttnThreads;
+      const int r = idx >> 4, pc16 = idx & 15;
+      qr[i] = u32x4{0u, 0u, 0u, 0u};
+      if (r < R) {
+        const int s = GATHER ? q_stream : (req_streams ? req_streams[r / G] : r / G);
+        qr[i] = qg[((long long)s * p.Hq + (g * G + r % G)) * 16 + pc16];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int idx = tid + i * kAttnThreads;
+      const int r = idx >> 4, pc16 = idx & 15;
+      lds.q[r * 16 + (pc16 ^ (r & 15))] = qr[i];
+    }
+  }
+
+  if (p.dbg_rows && g == 0 && !listed) {  // listed items reported their rows while expanding
+    const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
+    for (int j = tid; j < n_tok; j += kAttnThreads) {
+      const int phys = phys_of(j);
+      if constexpr (GATHER) {
+        p.dbg_rows[gather_pos + j] = phys;
+      } else {
+        for (int k = 0; k < n_req_streams; ++k)
+          p.dbg_rows[streams[req_streams ? req_streams[k] : k].gather_base + gather_pos + j] = phys;
+      }
+    }
+  }
+  __syncthreads();  // Q visible to every wave; the only barrier before the end of the item
+  PASTA_CLK(2);
+
+  f32x16 O[4];  // O^T M-tile mt: d = 32 mt + 8 (i / 4) + 4 hh + i % 4, row l32
+  float m_run = -INFINITY, l_run = 0.f;  // row l32; l_run covers this lane's 16 tokens of every block
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) O[mt][i] = 0.f;
+
+  u32x4* ktw = lds.tile[w].kt;
+  u32x4* vtw = lds.tile[w].vt;
+  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vtw);
+  const int bl = lane & 15, cblk = (lane >> 4) & 1;
+
+  auto compute_block = [&](int b) {
+    // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = rbase + 4 * i;
+      ktw[r * 16 + (piece ^ (r & 15))] = br.k[i];
+      vtw[r * 16 + (piece ^ (r & 15))] = br.v[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
+
+    // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
+    f32x16 S, S1;  // two accumulation chains (even / odd steps) halve the dependent-MFMA latency
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { S[i] = 0.f; S1[i] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < 8; kk += 2) {
+      const int pc0 = (2 * kk + hh) ^ (l32 & 15), pc1 = (2 * kk + 2 + hh) ^ (l32 & 15);
+      const u32x4 a0 = ktw[l32 * 16 + pc0], q0 = lds.q[l32 * 16 + pc0];
+      const u32x4 a1 = ktw[l32 * 16 + pc1], q1 = lds.q[l32 * 16 + pc1];
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a0),
+                                                  *reinterpret_cast<const bf16x8*>(&q0), S, 0, 0, 0);
+      S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a1),
+                                                   *reinterpret_cast<const bf16x8*>(&q1), S1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) S[i] += S1[i];
+    // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block
+    const int tok0 = b * kWBlock + 4 * hh;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float s = (tok0 + 8 * (i >> 2) + (i & 3)) < n_tok ? S[i] * p.scale_log2e : -INFINITY;
+      S[i] = s;
+      mx = fmaxf(mx, s);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float mn = fmaxf(m_run, mx);  // finite: a block holds at least one valid token
+    const float corr = fast_exp2(m_run - mn);
+    m_run = mn;
+    float ps = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      S[i] = fast_exp2(S[i] - mn);
+      ps += S[i];
+    }
+    l_run = l_run * corr + ps;
+    if (!__all(corr == 1.f)) {  // the running max moves rarely once a few blocks are in
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
+    }
+    // P^T as B operand: contraction step ks holds registers 8 ks .. 8 ks + 7
+    bf16x8 Pb[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 pk;
+      pk[0] = pack_bf16x2(S[8 * ks + 0], S[8 * ks + 1]);
+      pk[1] = pack_bf16x2(S[8 * ks + 2], S[8 * ks + 3]);
+      pk[2] = pack_bf16x2(S[8 * ks + 4], S[8 * ks + 5]);
+      pk[3] = pack_bf16x2(S[8 * ks + 6], S[8 * ks + 7]);
+      Pb[ks] = *reinterpret_cast<const bf16x8*>(&pk);
+    }
+    // ---- O^T += V^T P^T.  Slot (ks, hh, e) is token 16 ks + 8 (e / 4) + 4 hh + e % 4: per
+    // transposing read, 4 consecutive token rows x 16 columns per 16-lane block.
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        s16x4 part[2];
+#pragma unroll
+        for (int e4 = 0; e4 < 2; ++e4) {
+          const int trow = 16 * ks + 8 * e4 + 4 * hh + (bl >> 2);
+          const int col = 32 * mt + 16 * cblk + 4 * (bl & 3);
+          part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ (trow & 15))) * 8 + (col & 7));
+        }
+        u32x4 a4;
+        a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
+        a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
+        a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
+        a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
+        O[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a4), Pb[ks], O[mt], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the tile may be overwritten by the next block
+  };
+
+  // this wave's blocks w, w + 4, ...
+  for (int b = w; b < n_blocks; b += 4) compute_block(b);
+  PASTA_CLK(6);
+
+  // ---- combine the four waves.  Each wave parks its (unscaled) O^T in its OWN tile area as soon
+  // as it is done -- [32 rows][32 pieces of 4 floats], piece c of row r at c ^ r -- so only one
+  // barrier stands between the slowest wave and the output; the scales 2^(m_w - m) are applied
+  // while adding.
+  f32x4* otile = reinterpret_cast<f32x4*>(&lds.tile[w]);  // 1024 pieces = 16 KB
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int b4 = 0; b4 < 4; ++b4) {
+      const int c = 8 * mt + 2 * b4 + hh;  // floats 32 mt + 8 b4 + 4 hh .. + 3 of row l32
+      otile[l32 * 32 + (c ^ l32)] = f32x4{O[mt][4 * b4], O[mt][4 * b4 + 1], O[mt][4 * b4 + 2], O[mt][4 * b4 + 3]};
+    }
+  {
+    const float lw = l_run + __shfl_xor(l_run, 32, kWave);
+    if (hh == 0) { lds.mw[w][l32] = m_run; lds.lw[w][l32] = lw; }
+  }
+  __syncthreads();
+  float l_all = 0.f, m_all = -INFINITY;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int rr = pass * 8 + (tid >> 5), c = tid & 31;
+    if (rr < R) {
+      const float m0 = lds.mw[0][rr], m1 = lds.mw[1][rr], m2 = lds.mw[2][rr], m3 = lds.mw[3][rr];
+      const float ma = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));  // finite: wave 0 always has a block
+      const float s0 = fast_exp2(m0 - ma), s1 = fast_exp2(m1 - ma), s2 = fast_exp2(m2 - ma), s3 = fast_exp2(m3 - ma);
+      const f32x4* src = reinterpret_cast<const f32x4*>(&lds.tile[0]) + rr * 32 + (c ^ rr);  // + 1024 per wave
+      const f32x4 acc = src[0] * s0 + src[1024] * s1 + src[2048] * s2 + src[3072] * s3;
+      *reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + rr) * D + 4 * c) = acc;
+      if (c == 0) {  // one lane per row also writes (m, l)
+        l_all = lds.lw[0][rr] * s0 + lds.lw[1][rr] * s1 + lds.lw[2][rr] * s2 + lds.lw[3][rr] * s3;
+        m_all = ma;
+        p.part_ml[part_row0 + rr] = make_float2(m_all, l_all);
+      }
+    }
+  }
+  PASTA_CLK(7);
+}
+
+// One launch for all partials of a decode step with at most 32 stacked rows per request;
+// work-groups [0, n_priv_wgs) are private (gather) items, the rest shared-prefix items.
+template <bool PAGED>
+__global__ __launch_bounds__(kAttnThreads, 2) void k_attn_w(DecodeParams p) {
+  __shared__ AttnWLds lds;
+  const int32_t* meta = meta_of(p);
+  if (p.pend_n > 0) {
+    // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads
+    // those pool rows -- lists that name them are served from k_pend / v_pend -- so the copy
+    // needs no ordering against the rest of the launch.
+    const int pieces = p.Hkv * 16;  // 16-byte pieces per row
+    const int total = 2 * p.pend_n * pieces;
+    const int32_t* dst = pend_dst_of(p);
+    for (int t = blockIdx.x * kAttnThreads + threadIdx.x; t < total; t += gridDim.x * kAttnThreads) {
+      const bool is_v = t >= total / 2;
+      const int u = is_v ? t - total / 2 : t;
+      const int row = u / pieces, gh = (u % pieces) >> 4, pc16 = u & 15;
+      const u32x4 val = reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
+      char* base = reinterpret_cast<char*>(const_cast<void*>(is_v ? p.v : p.k));
+      *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, dst[row], gh) + pc16 * 8) * 2) = val;
+    }
+  }
+  const int n_priv_wgs = p.n_mfma_items * p.Hkv;
+  if ((int)blockIdx.x < n_priv_wgs) attn_item_w<PAGED, true>(p, lds, meta, blockIdx.x);
+  else attn_item_w<PAGED, false>(p, lds, meta, blockIdx.x - n_priv_wgs);
+}
+
+}  // namespace pasta

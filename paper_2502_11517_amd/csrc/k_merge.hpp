@@ -26,8 +26,10 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
   __shared__ float lsum[NGRP];
   const int tid = threadIdx.x;
   const int grp = tid / D, d = tid % D;
-  const int s = blockIdx.x / p.Hq, h = blockIdx.x % p.Hq;
-  const int g = h / G, gi = h % G;
+  // work-group index = (s * G + gi) * Hkv + g: index mod Hkv is the kv head, as in the attention
+  // launch, so that with 8 kv heads the partials are read on the XCD whose L2 holds them
+  const int g = blockIdx.x % p.Hkv, gi = (blockIdx.x / p.Hkv) % G, s = blockIdx.x / p.Hq;
+  const int h = g * G + gi;
   const int32_t* meta = meta_of(p);
   const DevStream* stp = reinterpret_cast<const DevStream*>(meta + p.off_streams) + s;
   int R, n_pre, part_base, local;
@@ -74,8 +76,15 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
       fold(ml, a, n_valid);
     }
   };
-  const int item_begin = stp->item_begin;          // requested here, needed after the prefix parts
-  const int n_priv = stp->item_end - item_begin;
+  int item_begin, n_priv;
+  if (p.single_req == 2) {  // the stream's item range rides in the kernel arguments
+    const int32_t* si = s_items_of(p);
+    item_begin = si[2 * s];
+    n_priv = si[2 * s + 1];
+  } else {
+    item_begin = stp->item_begin;  // requested here, needed after the prefix parts
+    n_priv = stp->item_end - item_begin;
+  }
   run(pre0, R, n_pre);
   run(p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv);
 

@@ -17,6 +17,7 @@
 #include "../../include/pasta_attn.h"
 #include "k_append.hpp"
 #include "k_attn.hpp"
+#include "k_attn_w.hpp"
 #include "k_merge.hpp"
 #include "k_private.hpp"
 
@@ -745,17 +746,29 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     p.Hkv = Hkv;
     p.scale_log2e = c.softmax_scale * kLog2e;
 #ifdef PASTA_PHASE_CLOCKS
-    p.clock_row0 = h->part_rows_cap - 8192;  // the last 64 KiB of the (m, l) array
+    p.clock_row0 = h->part_rows_cap - 8192 + (a->layer & 1) * 4096;  // the last 64 KiB of the (m, l) array, two halves
 #endif
     p.single_req = reqs.size() == 1 ? 1 : 0;
+    if (p.single_req && n <= 16) {  // item ranges of the streams as kernel-argument scalars
+      p.single_req = 2;
+      for (int i = 0; i < n; ++i) {
+        p.s_items[2 * i] = streams[i].item_begin;
+        p.s_items[2 * i + 1] = streams[i].item_end - streams[i].item_begin;
+      }
+    }
     p.req0 = reqs[0];
 
     if (a->prof_event_start && hipEventRecord((hipEvent_t)a->prof_event_start, st) != hipSuccess)
       return PASTA_E_DEVICE;
     if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
-      rc = launch_attn((int)max_rows, dim3(grid), st, p);
-      if (rc != PASTA_OK) return rc;
+      if (max_rows <= 32) {  // the wave-autonomous form
+        if (h->lay.paged) k_attn_w<true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        else k_attn_w<false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+      } else {
+        rc = launch_attn((int)max_rows, dim3(grid), st, p);
+        if (rc != PASTA_OK) return rc;
+      }
       if (take_pending) h->pending.active = false;
     } else if (!items.empty()) {
       const unsigned waves = (unsigned)items.size() * Hkv;

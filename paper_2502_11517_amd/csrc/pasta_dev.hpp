@@ -108,6 +108,8 @@ struct DecodeParams {
   const void* v_pend;
   int pend_n;           // rows of the deferred append (0: none)
   int32_t pend_dst[32]; // their physical rows
+  int32_t s_items[32];  // single_req with <= 16 streams: stream i's private items are
+                        //   [s_items[2i], s_items[2i] + s_items[2i+1]) -- spares the merge a table look-up
   int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
   DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way
                         //    to the first K/V load)
@@ -124,6 +126,13 @@ __device__ __forceinline__ const int32_t* meta_of(const DecodeParams& p) {
   typedef const char __attribute__((address_space(4))) * kernarg_ptr;
   kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, inline_meta));
+}
+
+__device__ __forceinline__ const int32_t* s_items_of(const DecodeParams& p) {
+  (void)p;
+  typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+  kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, s_items));
 }
 
 __device__ __forceinline__ const int32_t* pend_dst_of(const DecodeParams& p) {
