@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
     ap.add_argument("--eager-append", action="store_true",
                     help="run the KV-append as a launch of its own instead of letting it ride with the decode launch")
+    ap.add_argument("--workload", choices=["config3", "config2", "config4", "config5"], default="config3",
+                    help="config3 (default) is the headline line; the others time decode steps only (their "
+                         "state is a single step's) and exist to show how the kernels behave on the other shapes")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (3x) before the loop: the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -62,6 +65,8 @@ def main():
         raise SystemExit("libpasta_attn.so is not built: run `python __graft_entry__.py` first")
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
+    if args.workload != "config3":
+        return decode_only(args, getattr(W, args.workload)(), dev)
     L = args.layers
     tokens = -(-args.steps // L)  # token steps needed
     w = W.config3(steps=max(tokens, 2))
@@ -186,7 +191,7 @@ def main():
                                             "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
     # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (if present)
     traffic = None
-    prof = os.path.join(ROOT, "profiles", "k_attn_config3.txt")
+    prof = os.path.join(ROOT, "profiles", "k_attn_w_config3.txt")
     if os.path.exists(prof) and not args.no_mfma:
         for line in open(prof):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
@@ -211,13 +216,87 @@ def main():
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "k_attn (shared-prefix + private-segment partials, one launch)",
+                     "kernel": "k_attn_w (shared-prefix + private-segment partials, one launch)",
                      "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
         "whole_step": {"algorithmic_GBps": alg_bytes / (elapsed / args.steps) / 1e9},
         "cpu_baseline": cpu,
     }
     res.update(result_extra)
     print(json.dumps(res))
+    s.close()
+
+
+def decode_only(args, w, dev):
+    """Decode steps of a single-step configuration, cycling `--layers` pools that hold the same
+    rows (only the decode is timed: these configurations define no token loop)."""
+    import torch
+
+    from paper_2502_11517_amd import binding as B
+    from paper_2502_11517_amd.harness import Session, to_device
+
+    row_bytes = 2 * w.Hkv * w.D * (2 if w.dtype == "bf16" else 4)
+    pool_rows = (w.n_phys_pages * w.page_tokens) if w.page_tokens else w.max_requests * w.pool_tokens
+    L = max(1, min(args.layers, int(6e9 // (pool_rows * row_bytes))))
+    layout = B.HEAD_MAJOR if args.layout == "head" else B.TOKEN_MAJOR
+    s = Session(w, kv_layout=layout, n_layers=L)
+    hip = C.CDLL("libamdhip64.so.7")
+    ne = w.n_events(0)
+    for lo in range(0, ne, 65536):
+        hi = min(ne, lo + 65536)
+        k, v = w.kv_rows(lo, hi)
+        kd, vd = to_device(k, w.dtype, dev), to_device(v, w.dtype, dev)
+        for l in range(L):
+            s.h.append_kv(l, w.ev_request[lo:hi], w.ev_stream[lo:hi], kd, vd, parent_stream=w.ev_parent[lo:hi])
+        torch.cuda.synchronize()
+    q = to_device(w.q(0), w.dtype, dev)
+    out = torch.empty(L, w.n, w.Hq, w.D, dtype=q.dtype, device=dev)
+    flags = B.DECODE_NO_MFMA if args.no_mfma else 0
+    n_ev = args.steps // args.event_every + 1
+    evs = []
+    for _ in range(2 * n_ev):
+        e = C.c_void_p()
+        assert hip.hipEventCreate(C.byref(e)) == 0
+        evs.append(e)
+    calls = []
+    for i in range(args.steps):
+        j = i // args.event_every
+        pe = (evs[2 * j], evs[2 * j + 1]) if i % args.event_every == 0 else None
+        calls.append(s.h.prepare_decode(i % L, w.dec_request, w.dec_stream, q, out[i % L], flags=flags, prof_events=pe))
+    for i in range(args.warmup):
+        assert calls[i % len(calls)]() == 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for c in calls:
+        if c():
+            raise SystemExit("library error in timed loop")
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = C.c_float()
+    durs = []
+    for j in range(0, args.steps, args.event_every):
+        assert hip.hipEventElapsedTime(C.byref(ms), evs[2 * (j // args.event_every)], evs[2 * (j // args.event_every) + 1]) == 0
+        durs.append(ms.value * 1e-3)
+    kern_s = float(np.mean(durs))
+    # algorithmic bytes: per request the common prefix once, everything else once per stream
+    pl, offs, st, ct, sd = w.lists(0)
+    rows = 0
+    for r in np.unique(w.dec_request):
+        idx = np.nonzero(w.dec_request == r)[0]
+        pc = int(pl[idx].min())
+        rows += pc + sum(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum()) for i in idx)
+    alg_bytes = rows * row_bytes + w.n * w.Hq * w.D * (2 if w.dtype == "bf16" else 4)
+    achieved = alg_bytes / kern_s / 1e9
+    print(json.dumps({
+        "metric": "multi-stream decode-attention stream-tokens/s (decode step only, per layer)",
+        "value": w.n * args.steps / elapsed, "unit": "stream-tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload} ({w.name}): {w.n} streams, {rows} distinct visible rows, decode only",
+                   "n_layers_cycled": L, "kv_layout": args.layout},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "attention-partials launch", "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
+        "cpu_baseline": None}))
     s.close()
 
 

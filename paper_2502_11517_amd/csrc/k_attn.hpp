@@ -76,6 +76,28 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
+// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l's
+// datum lands at lds_base + 16 l, lds_base wave-uniform; counted by vmcnt like any load.
+__device__ __forceinline__ void load_to_lds16(const void* src, void* lds_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) alone (N < 64): vector-memory loads return in issue order, so this waits
+// for every load except the N issued last.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Work-group barrier that orders LDS traffic only: unlike __syncthreads() it does not drain the
+// vector-memory counter, so global loads issued before it stay in flight across it.  LDS filled
+// by load_to_lds16 needs the matching wait_vmcnt before this barrier.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 struct TileRegs { u32x4 k[4], v[4]; };  // one thread's share of a 64-token tile
 
 // Phase clocks for kernel tuning (compiled in only with -DPASTA_PHASE_CLOCKS): thread 0 of every

@@ -21,6 +21,8 @@
 // The four waves' (m, l, O) are combined once, at the end, through LDS, and leave as
 // coalesced 512-byte stores (they stay in this XCD's L2, where the merge of the same kv head looks for them).  Logits are kept in log2 units.
 #pragma once
+#include <type_traits>
+
 #include "k_attn.hpp"
 
 namespace pasta {
@@ -46,7 +48,8 @@ template <bool PAGED, bool GATHER>
 __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, w = tid >> 6;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform: scalar branches below
   const int l32 = lane & 31, hh = lane >> 5;
   const int G = p.Hq / p.Hkv;
   PASTA_CLK(0);
@@ -126,7 +129,9 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
       __syncthreads();
     }
   }
-  const int n_blocks = (n_tok + kWBlock - 1) / kWBlock;
+  // (work-group-uniform values, but loaded per lane: tell the compiler, so that the branches on
+  // them are scalar and its wait-count bookkeeping sees an exhaustive if / else)
+  const int n_blocks = __builtin_amdgcn_readfirstlane((n_tok + kWBlock - 1) / kWBlock);
 
   // ---- block loads: lane -> piece (lane & 15) of rows (lane >> 4) + 4 i, i < 8
   const char* kb = reinterpret_cast<const char*>(p.k);
@@ -143,7 +148,7 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
       return req * p.lay.pool_tokens + t;
     }
   };
-  auto src_of = [&](int j, bool& is_pend) -> long long {  // branch-free: a block's loads issue together
+  auto src_of = [&](int j, bool& is_pend) -> long long {  // byte offset of token j's row of head g; branch-free
     const int t = slot0 + j * stride;
     int phys = phys_of(j);
     int pidx = pend_src0 + (t - pend0);
@@ -152,17 +157,17 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
       const int code = lds.rows[j];  // j < kGatherMax; meaningful only for listed items
       if (listed) { is_pend = code < 0; pidx = -1 - code; phys = code; }
     }
-    const long long off_pool = (elem_off(p.lay, is_pend ? 0 : phys, g) + piece * 8) * 2;
-    const long long off_pend = (((long long)pidx * p.Hkv + g) * D + piece * 8) * 2;
+    const long long off_pool = elem_off(p.lay, is_pend ? 0 : phys, g) * 2;
+    const long long off_pend = ((long long)pidx * p.Hkv + g) * D * 2;
     return is_pend ? off_pend : off_pool;
   };
-  auto load_block = [&](BlockRegs& br, int b) {
+  auto load_block = [&](BlockRegs& br, int b) {  // block b -> registers, natural piece order
     long long off[8];
     bool pnd[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int j = min(b * kWBlock + rbase + 4 * i, n_tok - 1);  // rows past the end repeat the last one
-      off[i] = src_of(j, pnd[i]);
+      off[i] = src_of(j, pnd[i]) + piece * 16;
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -170,31 +175,52 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
       br.v[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? vpend : vb) + off[i]);
     }
   };
-  BlockRegs br;
-  if (w < n_blocks) load_block(br, w);          // first: nothing else on the way to these loads
-  PASTA_CLK(1);
-
-  // ---- stacked Q rows -> LDS (loads issued behind the blocks')
-  {
-    const u32x4* qg = reinterpret_cast<const u32x4*>(p.q);
-    u32x4 qr[2];
+  u32x4* ktw = lds.tile[w].kt;
+  u32x4* vtw = lds.tile[w].vt;
+  // Block b straight into this wave's LDS tile, no registers in between: one such load writes
+  // 64 consecutive 16-byte pieces (lane l at piece l of the destination), so instruction i fills
+  // rows 4 i .. 4 i + 3 and the swizzle moves to the global side -- the lane whose LDS place is
+  // position (lane & 15) of row r fetches piece (lane & 15) ^ (r & 15) of that row.
+  auto dma_block = [&](int b) {
+    long long off[8];
+    bool pnd[8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int idx = tid + i * kAttnThreads;
-      const int r = idx >> 4, pc16 = idx & 15;
-      qr[i] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < 8; ++i) {
+      const int r = rbase + 4 * i;
+      const int j = min(b * kWBlock + r, n_tok - 1);
+      off[i] = src_of(j, pnd[i]) + (piece ^ (r & 15)) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      load_to_lds16((pnd[i] ? kpend : kb) + off[i], ktw + 64 * i);
+      load_to_lds16((pnd[i] ? vpend : vb) + off[i], vtw + 64 * i);
+    }
+  };
+  // ---- everything this wave needs first is requested here, before anything is waited for:
+  // its share of the stacked Q rows (2 loads), its first block (16 loads into LDS), and its
+  // second block (16 loads into registers).  Loads return in issue order, so Q is waited for
+  // with the blocks still in flight.
+  {
+    const char* qg = reinterpret_cast<const char*>(p.q);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // wave w fills pieces [128 w + 64 i, + 64) of lds.q: rows 8 w + 4 i + rbase
+      const int r = 8 * w + 4 * i + rbase;
+      u32x4* dst = lds.q + 128 * w + 64 * i;
       if (r < R) {
         const int s = GATHER ? q_stream : (req_streams ? req_streams[r / G] : r / G);
-        qr[i] = qg[((long long)s * p.Hq + (g * G + r % G)) * 16 + pc16];
+        load_to_lds16(qg + (((long long)s * p.Hq + (g * G + r % G)) * 16 + (piece ^ (r & 15))) * 16, dst);
+      } else {
+        dst[lane] = u32x4{0u, 0u, 0u, 0u};  // rows past R are zero
       }
     }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int idx = tid + i * kAttnThreads;
-      const int r = idx >> 4, pc16 = idx & 15;
-      lds.q[r * 16 + (pc16 ^ (r & 15))] = qr[i];
-    }
   }
+  BlockRegs br;
+  const bool has1 = w < n_blocks, has2 = w + 4 < n_blocks;
+  if (has1) dma_block(w);
+  if (has2) load_block(br, w + 4);
+  PASTA_CLK(1);
+  // Q has landed once at most the block loads issued behind it are outstanding
+  if (has2) wait_vmcnt<32>(); else if (has1) wait_vmcnt<16>(); else wait_vmcnt<0>();
 
   if (p.dbg_rows && g == 0 && !listed) {  // listed items reported their rows while expanding
     const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
@@ -208,7 +234,8 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
       }
     }
   }
-  __syncthreads();  // Q visible to every wave; the only barrier before the end of the item
+  lds_barrier();  // Q visible to every wave; the only barrier before the end of the item, and it
+                  // does not wait for the block loads still in flight
   PASTA_CLK(2);
 
   f32x16 O[4];  // O^T M-tile mt: d = 32 mt + 8 (i / 4) + 4 hh + i % 4, row l32
@@ -218,23 +245,30 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
 #pragma unroll
     for (int i = 0; i < 16; ++i) O[mt][i] = 0.f;
 
-  u32x4* ktw = lds.tile[w].kt;
-  u32x4* vtw = lds.tile[w].vt;
   const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vtw);
   const int bl = lane & 15, cblk = (lane >> 4) & 1;
 
-  auto compute_block = [&](int b) {
-    // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
+  auto compute_block = [&](int b, auto first) {
+    if constexpr (first.value) {
+      // the first block was loaded straight into the tile: done once only the second block's
+      // 16 register loads (if any) are still outstanding
+      if (has2) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      PASTA_CLK(3);
+    } else {
+      // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = rbase + 4 * i;
-      ktw[r * 16 + (piece ^ (r & 15))] = br.k[i];
-      vtw[r * 16 + (piece ^ (r & 15))] = br.v[i];
+      for (int i = 0; i < 8; ++i) {
+        const int r = rbase + 4 * i;
+        ktw[r * 16 + (piece ^ (r & 15))] = br.k[i];
+        vtw[r * 16 + (piece ^ (r & 15))] = br.v[i];
+      }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
+    if constexpr (!first.value) {
+      if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
+    }
 
     // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
     f32x16 S, S1;  // two accumulation chains (even / odd steps) halve the dependent-MFMA latency
@@ -315,7 +349,11 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
   };
 
   // this wave's blocks w, w + 4, ...
-  for (int b = w; b < n_blocks; b += 4) compute_block(b);
+  if (has1) {
+    compute_block(w, std::true_type{});
+    PASTA_CLK(4);
+    for (int b = w + 4; b < n_blocks; b += 4) compute_block(b, std::false_type{});
+  }
   PASTA_CLK(6);
 
   // ---- combine the four waves.  Each wave parks its (unscaled) O^T in its OWN tile area as soon
@@ -328,7 +366,7 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
 #pragma unroll
     for (int b4 = 0; b4 < 4; ++b4) {
       const int c = 8 * mt + 2 * b4 + hh;  // floats 32 mt + 8 b4 + 4 hh .. + 3 of row l32
-      otile[l32 * 32 + (c ^ l32)] = f32x4{O[mt][4 * b4], O[mt][4 * b4 + 1], O[mt][4 * b4 + 2], O[mt][4 * b4 + 3]};
+      if (l32 < R) otile[l32 * 32 + (c ^ l32)] = f32x4{O[mt][4 * b4], O[mt][4 * b4 + 1], O[mt][4 * b4 + 2], O[mt][4 * b4 + 3]};
     }
   {
     const float lw = l_run + __shfl_xor(l_run, 32, kWave);
@@ -357,7 +395,7 @@ __device__ __forceinline__ void attn_item_w(const DecodeParams& p, AttnWLds& lds
 }
 
 // One launch for all partials of a decode step with at most 32 stacked rows per request;
-// work-groups [0, n_priv_wgs) are private (gather) items, the rest shared-prefix items.
+// the shared-prefix items' work-groups come first, the private (gather) items' after them.
 template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn_w(DecodeParams p) {
   __shared__ AttnWLds lds;
@@ -378,9 +416,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn_w(DecodeParams p) {
       *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, dst[row], gh) + pc16 * 8) * 2) = val;
     }
   }
-  const int n_priv_wgs = p.n_mfma_items * p.Hkv;
-  if ((int)blockIdx.x < n_priv_wgs) attn_item_w<PAGED, true>(p, lds, meta, blockIdx.x);
-  else attn_item_w<PAGED, false>(p, lds, meta, blockIdx.x - n_priv_wgs);
+  // shared-prefix items first: they are the longer ones (up to two blocks per wave against one)
+  const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
+  if ((int)blockIdx.x < n_prefix_wgs) attn_item_w<PAGED, false>(p, lds, meta, blockIdx.x);
+  else attn_item_w<PAGED, true>(p, lds, meta, blockIdx.x - n_prefix_wgs);
 }
 
 }  // namespace pasta
