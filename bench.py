@@ -191,7 +191,7 @@ def main():
                                             "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
     # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (if present)
     traffic = None
-    prof = os.path.join(ROOT, "profiles", "k_attn_w_config3.txt")
+    prof = os.path.join(ROOT, "profiles", "k_attn_config3.txt")
     if os.path.exists(prof) and not args.no_mfma:
         for line in open(prof):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
@@ -216,7 +216,7 @@ def main():
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "k_attn_w (shared-prefix + private-segment partials, one launch)",
+                     "kernel": "k_attn (shared-prefix + private-segment partials, one launch)",
                      "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
         "whole_step": {"algorithmic_GBps": alg_bytes / (elapsed / args.steps) / 1e9},
         "cpu_baseline": cpu,

@@ -1,132 +1,80 @@
 // K2 + K3 on the matrix cores, one launch.
 //
-// K2, shared prefix.  Every stream forked from the same thread sees the same prefix rows
-// of the pool (arxiv 2502.11517, Section 3, "Efficiency": a forked thread attends to the
-// spawning thread's tokens that existed before the fork; the appendix on the naive
-// interpreter names the cost of duplicating that prefix per thread).  Here the prefix K/V
-// rows of one kv head are read from HBM ONCE per step and used for all R = n_streams * G
-// query rows stacked together, so  S = Q_stack K^T  and  O = P V  are small dense
-// contractions.  Work item = (request, kv head, split-K chunk of the common prefix).
+// K2, shared prefix.  Every stream forked from the same thread sees the same prefix rows of the
+// pool (arxiv 2502.11517, Section 3, "Efficiency": a forked thread attends to the spawning
+// thread's tokens that existed before the fork; the appendix on the naive interpreter names
+// the cost of duplicating that prefix per thread).  Here the prefix K/V rows of one kv head
+// are read from HBM ONCE per step and used for all R = n_streams * G query rows stacked
+// together, so  S = Q_stack K^T  and  O = P V  are small dense contractions.  Work item =
+// (request, kv head, split-K chunk of the common prefix, group of up to 32 stacked rows).
 //
-// K3, private segments.  A stream's own rows are interleaved with the other streams' rows
-// in the pool (Section 3, "Efficiency"; Figure 2c).  Work item = (stream, kv head, chunk of
-// the stream's private list).  A chunk that lies inside one (start, count, stride) range
-// is addressed arithmetically; otherwise its ranges are expanded to physical rows in LDS.
-// Rows are gathered with the same 128-bit loads (16 lanes = one 256-byte row of one kv
-// head).  Only the G query rows of that stream are live.
+// K3, private segments.  A stream's own rows are interleaved with the other streams' rows in
+// the pool (Section 3, "Efficiency"; Figure 2c).  Work item = (stream, kv head, chunk of the
+// stream's private list).  A chunk that lies inside one (start, count, stride) range is
+// addressed arithmetically; otherwise its ranges are expanded to physical rows in LDS.  Only
+// the G query rows of that stream are live.
 //
-// Both kinds run the same tile loop in a work-group of four wavefronts, 64 tokens per
-// tile.  The loop is built around bytes in flight, because that is what bounds a decode
-// step: every thread keeps TWO tiles of loads (16 x 16 B) outstanding in registers while
-// the work-group computes on a third that sits in LDS.
-//   * registers -> LDS with a 16-byte XOR swizzle;
-//   * wave w computes S^T for tokens 16w..16w+15 against all rows with
-//     v_mfma_f32_16x16x32_bf16 (A = K rows, B = Q rows, both from LDS), fp32 accumulate;
-//   * row maxima: across the four 16-lane groups of a wave by lane shuffles, across the
-//     waves through LDS, so the work-group shares one running max per row;
-//   * P = 2^(S - m) is rounded to bf16 and written to LDS in B-operand order; wave w then
-//     accumulates O^T for head-dim slice 32w..32w+31 over the tile's 64 tokens with
-//     v_mfma_f32_32x32x16_bf16, A = V^T fetched with the transposing LDS read.
-// A work item ends with one partial (m, l, acc[D]) per live row for the merge kernel.
-// Logits are kept in log2 units.
+// A decode step is a chain of latencies more than a stream of bytes: what bounds it is how
+// many bytes are in flight and how long a block takes from "data arrived" to "accumulated".
+// So every WAVEFRONT of the four in a work-group is its own pipeline, and there is no
+// work-group barrier in the loop:
+//   * a wave owns the 32-token blocks w, w+4, ... of the item.  Its first block is loaded
+//     straight into its LDS tile (global_load_lds, 16 B per lane), its second block into
+//     registers, both requested before anything is waited for; later blocks follow through the
+//     registers, one block ahead of the computation;
+//   * the wave's LDS tile holds K and V of one block with a 16-byte XOR swizzle;
+//     S^T[32 tok x 32 rows] = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows, B = Q rows);
+//   * online softmax in registers: a lane holds 16 tokens of one row, its partner lane
+//     (lane ^ 32) the other 16 -- one lane exchange per block for the row max;
+//   * P = 2^(S - m) goes to bf16 IN REGISTERS: the S^T accumulator layout is already the
+//     B-operand layout of the next MFMA for a suitable token order inside the contraction
+//     (slot (ks, half, e) <-> token 16 ks + 8 (e / 4) + 4 half + e % 4), and V^T is fetched
+//     from LDS with the transposing read in exactly that order;
+//   * O^T[128 x 32 rows] += V^T P^T, four 32-row M-tiles per wave.
+// The four waves' (m, l, O) are combined once, at the end, through LDS, and leave as coalesced
+// 512-byte stores: one partial (m, l, acc[D]) per live row for the merge kernel (they stay in
+// this XCD's L2, where the merge of the same kv head looks for them).  Logits are kept in
+// log2 units.
 #pragma once
-#include "pasta_dev.hpp"
+#include <type_traits>
+
+#include "mfma_util.hpp"
 
 namespace pasta {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // a plain 16-byte register quad
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+constexpr int kBlock = 32;  // tokens per wave block
 
-constexpr int kTile = 64;            // tokens per LDS tile
-constexpr int kAttnThreads = 256;    // four wavefronts
-constexpr int kAttnMaxRows = 128;    // stacked query rows one work-group can carry (RT <= 4)
-constexpr int kGatherMax = 256;      // most tokens (and ranges) of one private work item
-
-inline bool attn_kernel_supports(int D, int G) { return D == 128 && G >= 1; }
-
-template <int RT>
-struct AttnLds {
-  u32x4 kt[kTile * 16];     // K tile [row][16 pieces], piece p of row r at p ^ (r & 15); once
-                            // S is done it holds P^T [rt][4 steps][2 halves][32 rows]: 8 tokens
-                            // (16 B) each, RT * 4 KB
-  u32x4 vt[kTile * 16];     // V tile, same swizzle
-  u32x4 q[RT * 32 * 16];    // stacked Q rows, same swizzle (rows >= R are zero)
-  float tmax[4][RT * 32];   // per-wave row maxima of the current tile
-  float lsum[4][RT * 32];   // per-wave row sums at the end of the item
-  int rows[kGatherMax];          // listed gather items: physical row of every token
-  DevRange ranges[kGatherMax];   // listed gather items: the ranges the item overlaps
+struct AttnTile {             // one wave's 16 KB: K and V block, later its O^T on the way out
+  u32x4 kt[kBlock * 16];      // K block [row][16 pieces], piece p of row r at p ^ (r & 15)
+  u32x4 vt[kBlock * 16];      // V block, same swizzle
 };
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  f32x2 f = {a, b};
-  bf16x2 h = __builtin_convertvector(f, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
-  return *reinterpret_cast<uint32_t*>(&h);
-}
+struct AttnLds {
+  AttnTile tile[4];           // first member: wave w's area starts at byte w * 16 KB
+  u32x4 q[32 * 16];            // stacked Q rows, same swizzle (rows >= R are zero)
+  float mw[4][32], lw[4][32];  // per-wave row max / row sum at the end of the item
+  int rows[kGatherMax];        // listed gather items: row code of every token
+  DevRange ranges[kGatherMax]; // listed gather items: the ranges the item overlaps
+};
 
-// Transposing LDS read: within each 16-lane block, lane i receives element (i % 4) of the
-// 8-byte datum addressed by block lane 4 e + i / 4, for e = 0..3.  With block lane j
-// pointing at row (j / 4), columns 4 (j % 4).., lane i ends up with column i of 4 rows.
-__device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
-}
+struct BlockRegs { u32x4 k[8], v[8]; };  // one lane's share of a 32-token block
 
-// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l's
-// datum lands at lds_base + 16 l, lds_base wave-uniform; counted by vmcnt like any load.
-__device__ __forceinline__ void load_to_lds16(const void* src, void* lds_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
-}
-
-// s_waitcnt vmcnt(N) alone (N < 64): vector-memory loads return in issue order, so this waits
-// for every load except the N issued last.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
-// Work-group barrier that orders LDS traffic only: unlike __syncthreads() it does not drain the
-// vector-memory counter, so global loads issued before it stay in flight across it.  LDS filled
-// by load_to_lds16 needs the matching wait_vmcnt before this barrier.
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-struct TileRegs { u32x4 k[4], v[4]; };  // one thread's share of a 64-token tile
-
-// Phase clocks for kernel tuning (compiled in only with -DPASTA_PHASE_CLOCKS): thread 0 of every
-// work-group stores the 100 MHz wall clock at a few points into the tail of the partials buffer.
-#ifdef PASTA_PHASE_CLOCKS
-#define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < 512) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
-    __builtin_bit_cast(float2, (unsigned long long)__builtin_amdgcn_s_memrealtime()); } while (0)
-#else
-#define PASTA_CLK(n) do {} while (0)
-#endif
-
-template <int RT, bool PAGED, bool GATHER>
-__device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& lds, const int32_t* meta, int wi) {
+template <bool PAGED, bool GATHER>
+__device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
-  constexpr int NT = 2 * RT;  // 16-row tiles of S^T
   const int tid = threadIdx.x;
-  const int lane = tid & 63, w = tid >> 6;
-  const int c16 = lane & 15, q4 = lane >> 4;   // S^T layout: row nt*16 + c16, tokens 16 w + 4 q4 + i
-  const int l32 = lane & 31, hh = lane >> 5;   // O^T layout: row rt*32 + l32, half hh
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform: scalar branches below
+  const int l32 = lane & 31, hh = lane >> 5;
   const int G = p.Hq / p.Hkv;
   PASTA_CLK(0);
 
-  // ---- decode the work item.  Token j of the item is logical slot slot0 + j * stride of
-  // request `req`, except for "listed" gather items, whose rows come from LDS.
+  // ---- decode the work item (as in attn_item)
   int req, g, R, n_tok, slot0, stride, gather_pos, pend0, pend_src0;
+  int row0 = 0;  // first stacked row of this item's row group (shared-prefix items)
   long long part_row0;
-  const int32_t* req_streams = nullptr;  // prefix, several requests: stacked row r is stream req_streams[r / G]
-  int q_stream = 0;                      // gather: the one stream
-  int n_req_streams = 0;
+  const int32_t* req_streams = nullptr;
+  int q_stream = 0, n_req_streams = 0;
   bool listed = false;
   if constexpr (!GATHER) {
     DevReq rq;
@@ -140,24 +88,30 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
       int qi = 0;
       for (; qi < p.n_reqs - 1; ++qi) {
         const int b = reqs[qi].wg_begin;
-        if (wi >= b && wi < b + reqs[qi].n_chunks * p.Hkv) break;
+        if (wi >= b && wi < b + reqs[qi].n_chunks * p.Hkv * ((reqs[qi].n_streams * G + 31) >> 5)) break;
       }
       rq = reqs[qi];
       req_streams = meta + p.off_req_streams + rq.stream0;
     }
     // kv head = work-group index mod Hkv: with 8 kv heads every work-group of head g (private
     // items included, their index is item * Hkv + g) lands on XCD g, whose L2 then holds all of
-    // that head's partials for the merge
+    // that head's partials for the merge.  A request with more than 32 stacked rows is served
+    // in row groups of 32: the groups of one (chunk, kv head) are neighbours in launch order on
+    // the same XCD, so the chunk comes from HBM once and from that XCD's L2 for the others.
+    const int R_all = rq.n_streams * G;
+    const int n_rg = (R_all + 31) >> 5;
     const int wl = wi - rq.wg_begin;
-    const int c = wl / p.Hkv;
+    const int t = wl / p.Hkv;
+    const int c = t / n_rg;
+    row0 = (t % n_rg) * 32;
     g = wl % p.Hkv;
     req = rq.req;
-    R = rq.n_streams * G;
+    R = min(32, R_all - row0);
     n_req_streams = rq.n_streams;
     slot0 = c * rq.chunk_tokens;
     stride = 1;
     n_tok = min(rq.chunk_tokens, rq.pc - slot0);
-    part_row0 = rq.part_base + (long long)(g * rq.n_chunks + c) * R;
+    part_row0 = rq.part_base + (long long)(g * rq.n_chunks + c) * R_all + row0;
     gather_pos = slot0;
     pend0 = rq.pend0;
     pend_src0 = rq.pend_src0;
@@ -176,7 +130,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
     pend0 = it.pend0;
     pend_src0 = it.pend_src0;
     listed = it.n_ranges > 1;
-    if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> physical row
+    if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> row code
       const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
       const int nr = it.n_ranges;
       for (int r = tid; r < nr; r += kAttnThreads) lds.ranges[r] = ranges[it.range_first + r];
@@ -191,21 +145,22 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
         const DevRange rg = lds.ranges[lo];
         const int slot = rg.start + (tok - rg.cum) * rg.stride;
         const int phys = phys_row(p.lay, p.page_table, req, slot);
-        // rows of a deferred append are kept as -(1 + row in k_pend)
-        lds.rows[j] = slot >= pend0 ? -1 - (pend_src0 + (slot - pend0)) : phys;
+        lds.rows[j] = slot >= pend0 ? -1 - (pend_src0 + (slot - pend0)) : phys;  // deferred rows: -(1 + row)
         if (p.dbg_rows && g == 0) p.dbg_rows[gather_pos + j] = phys;
       }
       __syncthreads();
     }
   }
-  const int n_tiles = (n_tok + kTile - 1) / kTile;
+  // (work-group-uniform values, but loaded per lane: tell the compiler, so that the branches on
+  // them are scalar and its wait-count bookkeeping sees an exhaustive if / else)
+  const int n_blocks = __builtin_amdgcn_readfirstlane((n_tok + kBlock - 1) / kBlock);
 
-  // ---- tile loads: thread -> piece (tid & 15) of rows (tid >> 4) + 16 i, i < 4
+  // ---- block loads: lane -> piece (lane & 15) of rows (lane >> 4) + 4 i, i < 8
   const char* kb = reinterpret_cast<const char*>(p.k);
   const char* vb = reinterpret_cast<const char*>(p.v);
-  const int piece = tid & 15, rbase = tid >> 4;  // rbase 0..15
   const char* kpend = reinterpret_cast<const char*>(p.k_pend);
   const char* vpend = reinterpret_cast<const char*>(p.v_pend);
+  const int piece = lane & 15, rbase = lane >> 4;  // rbase 0..3
   auto phys_of = [&](int j) -> int {  // physical pool row of token j (not for listed items)
     const int t = slot0 + j * stride;
     if constexpr (PAGED) {
@@ -215,9 +170,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
       return req * p.lay.pool_tokens + t;
     }
   };
-  // Source of token j's row: the pool, or the rows of a deferred append.  Branch-free so that
-  // a tile's loads issue together.  Returns the byte offset; is_pend picks the base.
-  auto src_of = [&](int j, bool& is_pend) -> long long {
+  auto src_of = [&](int j, bool& is_pend) -> long long {  // byte offset of token j's row of head g; branch-free
     const int t = slot0 + j * stride;
     int phys = phys_of(j);
     int pidx = pend_src0 + (t - pend0);
@@ -226,52 +179,73 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
       const int code = lds.rows[j];  // j < kGatherMax; meaningful only for listed items
       if (listed) { is_pend = code < 0; pidx = -1 - code; phys = code; }
     }
-    const long long off_pool = (elem_off(p.lay, is_pend ? 0 : phys, g) + piece * 8) * 2;
-    const long long off_pend = (((long long)pidx * p.Hkv + g) * D + piece * 8) * 2;
+    const long long off_pool = elem_off(p.lay, is_pend ? 0 : phys, g) * 2;
+    const long long off_pend = ((long long)pidx * p.Hkv + g) * D * 2;
     return is_pend ? off_pend : off_pool;
   };
-  auto load_tile = [&](TileRegs& tr, int tile) {
-    long long off[4];
-    bool pnd[4];
+  auto load_block = [&](BlockRegs& br, int b) {  // block b -> registers, natural piece order
+    long long off[8];
+    bool pnd[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = min(tile * kTile + rbase + 16 * i, n_tok - 1);  // rows past the end repeat the last one
-      off[i] = src_of(j, pnd[i]);
+    for (int i = 0; i < 8; ++i) {
+      const int j = min(b * kBlock + rbase + 4 * i, n_tok - 1);  // rows past the end repeat the last one
+      off[i] = src_of(j, pnd[i]) + piece * 16;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      tr.k[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? kpend : kb) + off[i]);
-      tr.v[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? vpend : vb) + off[i]);
+    for (int i = 0; i < 8; ++i) {
+      br.k[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? kpend : kb) + off[i]);
+      br.v[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? vpend : vb) + off[i]);
     }
   };
-  TileRegs ta, tb;
-  load_tile(ta, 0);  // first: nothing else on the way to these loads
-  if (n_tiles > 1) load_tile(tb, 1);
-  PASTA_CLK(1);
-
-  // ---- stacked Q rows -> LDS (loads issued behind the tiles', stored before them)
-  {
-    const u32x4* qg = reinterpret_cast<const u32x4*>(p.q);
-    u32x4 qr[RT * 2];
+  u32x4* ktw = lds.tile[w].kt;
+  u32x4* vtw = lds.tile[w].vt;
+  // Block b straight into this wave's LDS tile, no registers in between: one such load writes
+  // 64 consecutive 16-byte pieces (lane l at piece l of the destination), so instruction i fills
+  // rows 4 i .. 4 i + 3 and the swizzle moves to the global side -- the lane whose LDS place is
+  // position (lane & 15) of row r fetches piece (lane & 15) ^ (r & 15) of that row.
+  auto dma_block = [&](int b) {
+    long long off[8];
+    bool pnd[8];
 #pragma unroll
-    for (int i = 0; i < RT * 2; ++i) {
-      const int idx = tid + i * kAttnThreads;
-      const int r = idx >> 4, pc16 = idx & 15;
-      qr[i] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < 8; ++i) {
+      const int r = rbase + 4 * i;
+      const int j = min(b * kBlock + r, n_tok - 1);
+      off[i] = src_of(j, pnd[i]) + (piece ^ (r & 15)) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      load_to_lds16((pnd[i] ? kpend : kb) + off[i], ktw + 64 * i);
+      load_to_lds16((pnd[i] ? vpend : vb) + off[i], vtw + 64 * i);
+    }
+  };
+  // ---- everything this wave needs first is requested here, before anything is waited for:
+  // its share of the stacked Q rows (2 loads), its first block (16 loads into LDS), and its
+  // second block (16 loads into registers).  Loads return in issue order, so Q is waited for
+  // with the blocks still in flight.
+  {
+    const char* qg = reinterpret_cast<const char*>(p.q);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // wave w fills pieces [128 w + 64 i, + 64) of lds.q: rows 8 w + 4 i + rbase
+      const int r = 8 * w + 4 * i + rbase;
+      u32x4* dst = lds.q + 128 * w + 64 * i;
       if (r < R) {
-        const int s = GATHER ? q_stream : (req_streams ? req_streams[r / G] : r / G);
-        qr[i] = qg[((long long)s * p.Hq + (g * G + r % G)) * 16 + pc16];
+        const int ra = row0 + r;  // row of the request's stack
+        const int s = GATHER ? q_stream : (req_streams ? req_streams[ra / G] : ra / G);
+        load_to_lds16(qg + (((long long)s * p.Hq + (g * G + ra % G)) * 16 + (piece ^ (r & 15))) * 16, dst);
+      } else {
+        dst[lane] = u32x4{0u, 0u, 0u, 0u};  // rows past R are zero
       }
     }
-#pragma unroll
-    for (int i = 0; i < RT * 2; ++i) {
-      const int idx = tid + i * kAttnThreads;
-      const int r = idx >> 4, pc16 = idx & 15;
-      lds.q[r * 16 + (pc16 ^ (r & 15))] = qr[i];
-    }
   }
+  BlockRegs br;
+  const bool has1 = w < n_blocks, has2 = w + 4 < n_blocks;
+  if (has1) dma_block(w);
+  if (has2) load_block(br, w + 4);
+  PASTA_CLK(1);
+  // Q has landed once at most the block loads issued behind it are outstanding
+  if (has2) wait_vmcnt<32>(); else if (has1) wait_vmcnt<16>(); else wait_vmcnt<0>();
 
-  if (p.dbg_rows && g == 0 && !listed) {  // listed items reported their rows while expanding
+  if (p.dbg_rows && g == 0 && row0 == 0 && !listed) {  // listed items reported their rows while expanding
     const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
     for (int j = tid; j < n_tok; j += kAttnThreads) {
       const int phys = phys_of(j);
@@ -283,193 +257,171 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds<RT>& ld
       }
     }
   }
+  lds_barrier();  // Q visible to every wave; the only barrier before the end of the item, and it
+                  // does not wait for the block loads still in flight
+  PASTA_CLK(2);
 
-  f32x16 O[RT];                 // O^T: d = 32 w + 8 (i / 4) + 4 hh + i % 4, row rt*32 + l32
-  float m_run[NT], l_run[NT];   // per 16-row tile: row nt*16 + c16 (l_run: this lane's tokens only)
+  f32x16 O[4];  // O^T M-tile mt: d = 32 mt + 8 (i / 4) + 4 hh + i % 4, row l32
+  float m_run = -INFINITY, l_run = 0.f;  // row l32; l_run covers this lane's 16 tokens of every block
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+  for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) O[rt][i] = 0.f;
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) { m_run[nt] = -INFINITY; l_run[nt] = 0.f; }
+    for (int i = 0; i < 16; ++i) O[mt][i] = 0.f;
 
-  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(lds.vt);
-  u32x4* pt = lds.kt;  // the K tile is dead once every wave has its S^T (barrier below)
-  uint16_t* pt16 = reinterpret_cast<uint16_t*>(pt);
+  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vtw);
+  const int bl = lane & 15, cblk = (lane >> 4) & 1;
 
-  auto compute_tile = [&](int t0) {
-    // ---- S^T = K Q^T for this wave's 16 tokens: A = K[16 tok x 32 d], B = Q^T[32 d x 16 rows]
-    f32x4 S[NT];
+  auto compute_block = [&](int b, auto first) {
+    if constexpr (first.value) {
+      // the first block was loaded straight into the tile: done once only the second block's
+      // 16 register loads (if any) are still outstanding
+      if (has2) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      PASTA_CLK(3);
+    } else {
+      // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) S[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int krow = 16 * w + c16;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int pc = (4 * kk + q4) ^ c16;  // (krow & 15) == c16, and Q row (nt*16 + c16) & 15 == c16
-      const u32x4 ar = lds.kt[krow * 16 + pc];
-      const bf16x8 A = *reinterpret_cast<const bf16x8*>(&ar);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const u32x4 br = lds.q[(nt * 16 + c16) * 16 + pc];
-        S[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, *reinterpret_cast<const bf16x8*>(&br), S[nt], 0, 0, 0);
+      for (int i = 0; i < 8; ++i) {
+        const int r = rbase + 4 * i;
+        ktw[r * 16 + (piece ^ (r & 15))] = br.k[i];
+        vtw[r * 16 + (piece ^ (r & 15))] = br.v[i];
       }
     }
-    // scale to log2 units, mask the ragged end, wave-level row max
-    const int tok_lane0 = t0 + 16 * w + 4 * q4;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float s = (tok_lane0 + i) < n_tok ? S[nt][i] * p.scale_log2e : -INFINITY;
-        S[nt][i] = s;
-        mx = fmaxf(mx, s);
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      if (q4 == 0) lds.tmax[w][nt * 16 + c16] = mx;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if constexpr (!first.value) {
+      if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
     }
-    __syncthreads();  // tmax visible; every wave is done with the K tile
 
-    // ---- P = 2^(S - m) -> LDS in B-operand order; running sums; rescale O
-    // contraction slot (ks, hh', e) of P V is token 16 ks + 8 hh' + e; this lane's 4 tokens
-    // are ks = w, hh' = q4 / 2, e = 4 (q4 % 2) + i
-    float corr[NT];
+    // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
+    f32x16 S, S1;  // two accumulation chains (even / odd steps) halve the dependent-MFMA latency
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int r = nt * 16 + c16;
-      const float mt = fmaxf(fmaxf(lds.tmax[0][r], lds.tmax[1][r]), fmaxf(lds.tmax[2][r], lds.tmax[3][r]));
-      const float mn = fmaxf(m_run[nt], mt);  // finite: every tile holds a valid token
-      corr[nt] = fast_exp2(m_run[nt] - mn);
-      m_run[nt] = mn;
-      float e[4];
+    for (int i = 0; i < 16; ++i) { S[i] = 0.f; S1[i] = 0.f; }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) e[i] = fast_exp2(S[nt][i] - mn);
-      l_run[nt] = l_run[nt] * corr[nt] + (e[0] + e[1]) + (e[2] + e[3]);
-      u32x2 pk;
-      pk[0] = pack_bf16x2(e[0], e[1]);
-      pk[1] = pack_bf16x2(e[2], e[3]);
-      const int rt = nt >> 1, row32 = (nt & 1) * 16 + c16;
-      *reinterpret_cast<u32x2*>(pt16 + ((((rt * 4 + w) * 2 + (q4 >> 1)) * 32 + row32) * 8 + 4 * (q4 & 1))) = pk;
+    for (int kk = 0; kk < 8; kk += 2) {
+      const int pc0 = (2 * kk + hh) ^ (l32 & 15), pc1 = (2 * kk + 2 + hh) ^ (l32 & 15);
+      const u32x4 a0 = ktw[l32 * 16 + pc0], q0 = lds.q[l32 * 16 + pc0];
+      const u32x4 a1 = ktw[l32 * 16 + pc1], q1 = lds.q[l32 * 16 + pc1];
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a0),
+                                                  *reinterpret_cast<const bf16x8*>(&q0), S, 0, 0, 0);
+      S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a1),
+                                                   *reinterpret_cast<const bf16x8*>(&q1), S1, 0, 0, 0);
     }
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      // this lane's O^T row is in 16-row tile 2 rt + ((lane >> 4) & 1); picked with a bit mask so
-      // that the compiler keeps corr[] in registers instead of indexing it in scratch memory
-      const uint32_t msk = 0u - (uint32_t)((lane >> 4) & 1);
-      const float cr = __uint_as_float((__float_as_uint(corr[2 * rt + 1]) & msk) | (__float_as_uint(corr[2 * rt]) & ~msk));
+    for (int i = 0; i < 16; ++i) S[i] += S1[i];
+    // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block
+    const int tok0 = b * kBlock + 4 * hh;
+    float mx = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) O[rt][i] *= cr;
+    for (int i = 0; i < 16; ++i) {
+      const float s = (tok0 + 8 * (i >> 2) + (i & 3)) < n_tok ? S[i] * p.scale_log2e : -INFINITY;
+      S[i] = s;
+      mx = fmaxf(mx, s);
     }
-    __syncthreads();  // P visible
-
-    // ---- O^T[d = 32 w + dd][r] += V^T P^T over the tile's 64 tokens.
-    // Lane (dd, hh) needs V[16 ks + 8 hh + e][32 w + dd], e < 8: two transposing reads, each
-    // over 4 consecutive token rows x 16 columns per 16-lane block.
-    const int bl = lane & 15;             // lane inside its 16-lane block
-    const int cblk = (lane >> 4) & 1;     // which 16 columns of the 32-wide M-tile
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float mn = fmaxf(m_run, mx);  // finite: a block holds at least one valid token
+    const float corr = fast_exp2(m_run - mn);
+    m_run = mn;
+    float ps = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      s16x4 part[2];
+    for (int i = 0; i < 16; ++i) {
+      S[i] = fast_exp2(S[i] - mn);
+      ps += S[i];
+    }
+    l_run = l_run * corr + ps;
+    if (!__all(corr == 1.f)) {  // the running max moves rarely once a few blocks are in
 #pragma unroll
-      for (int e4 = 0; e4 < 2; ++e4) {
-        const int trow = 16 * ks + 8 * hh + 4 * e4 + (bl >> 2);
-        const int col = 32 * w + 16 * cblk + 4 * (bl & 3);
-        part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ (trow & 15))) * 8 + (col & 7));
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
+    }
+    // P^T as B operand: contraction step ks holds registers 8 ks .. 8 ks + 7
+    bf16x8 Pb[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 pk;
+      pk[0] = pack_bf16x2(S[8 * ks + 0], S[8 * ks + 1]);
+      pk[1] = pack_bf16x2(S[8 * ks + 2], S[8 * ks + 3]);
+      pk[2] = pack_bf16x2(S[8 * ks + 4], S[8 * ks + 5]);
+      pk[3] = pack_bf16x2(S[8 * ks + 6], S[8 * ks + 7]);
+      Pb[ks] = *reinterpret_cast<const bf16x8*>(&pk);
+    }
+    // ---- O^T += V^T P^T.  Slot (ks, hh, e) is token 16 ks + 8 (e / 4) + 4 hh + e % 4: per
+    // transposing read, 4 consecutive token rows x 16 columns per 16-lane block.
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        s16x4 part[2];
+#pragma unroll
+        for (int e4 = 0; e4 < 2; ++e4) {
+          const int trow = 16 * ks + 8 * e4 + 4 * hh + (bl >> 2);
+          const int col = 32 * mt + 16 * cblk + 4 * (bl & 3);
+          part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ (trow & 15))) * 8 + (col & 7));
+        }
+        u32x4 a4;
+        a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
+        a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
+        a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
+        a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
+        O[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a4), Pb[ks], O[mt], 0, 0, 0);
       }
-      u32x4 a4;
-      a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
-      a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
-      a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
-      a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
-      const bf16x8 A = *reinterpret_cast<const bf16x8*>(&a4);
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const u32x4 br = pt[((rt * 4 + ks) * 2 + hh) * 32 + l32];
-        O[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, *reinterpret_cast<const bf16x8*>(&br), O[rt], 0, 0, 0);
-      }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the tile may be overwritten by the next block
   };
 
-  auto store_tile = [&](const TileRegs& tr) {  // rows rbase + 16 i all have (row & 15) == rbase
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      lds.kt[(rbase + 16 * i) * 16 + (piece ^ rbase)] = tr.k[i];
-      lds.vt[(rbase + 16 * i) * 16 + (piece ^ rbase)] = tr.v[i];
-    }
-  };
-
-  // two tiles of loads stay in flight while a third is computed on
-  for (int t = 0; t < n_tiles; t += 2) {
-    store_tile(ta);
-    __syncthreads();
-    if (t == 0) PASTA_CLK(2);
-    if (t + 2 < n_tiles) load_tile(ta, t + 2);
-    compute_tile(t * kTile);
-    __syncthreads();  // tile buffers free
-    if (t == 0) PASTA_CLK(3);
-    if (t + 1 < n_tiles) {
-      store_tile(tb);
-      __syncthreads();
-      if (t == 0) PASTA_CLK(4);
-      if (t + 3 < n_tiles) load_tile(tb, t + 3);
-      compute_tile((t + 1) * kTile);
-      __syncthreads();
-      if (t == 0) PASTA_CLK(5);
-    }
+  // this wave's blocks w, w + 4, ...
+  if (has1) {
+    compute_block(w, std::true_type{});
+    PASTA_CLK(4);
+    for (int b = w + 4; b < n_blocks; b += 4) compute_block(b, std::false_type{});
   }
   PASTA_CLK(6);
 
-  // ---- partial out: l summed over the wave's 16-lane groups and over the waves
+  // ---- combine the four waves.  Each wave parks its (unscaled) O^T in its OWN tile area as soon
+  // as it is done -- [32 rows][32 pieces of 4 floats], piece c of row r at c ^ r -- so only one
+  // barrier stands between the slowest wave and the output; the scales 2^(m_w - m) are applied
+  // while adding.
+  f32x4* otile = reinterpret_cast<f32x4*>(&lds.tile[w]);  // 1024 pieces = 16 KB
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    float lw = l_run[nt];
-    lw += __shfl_xor(lw, 16, kWave);
-    lw += __shfl_xor(lw, 32, kWave);
-    if (q4 == 0) lds.lsum[w][nt * 16 + c16] = lw;
-  }
-  // O^T goes through LDS (over the dead K/V tiles: 32 rows x 128 floats = 16 KB per row tile)
-  // so that every partial row leaves as one coalesced 512-byte line.  The stores are
-  // non-temporal: partials are read once, by the merge kernel, from another XCD, so there is
-  // no point in leaving them dirty in this XCD's L2 for the end-of-kernel write-back.
-  float* ot = reinterpret_cast<float*>(lds.kt);  // [32 rows][128 + 4 pad]
-  constexpr int OTS = 132;
+  for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    __syncthreads();  // rt == 0: lsum visible and tiles dead; rt > 0: previous row tile stored
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-      *reinterpret_cast<f32x4*>(ot + l32 * OTS + 32 * w + 8 * b + 4 * hh) =
-          f32x4{O[rt][4 * b], O[rt][4 * b + 1], O[rt][4 * b + 2], O[rt][4 * b + 3]};
-    __syncthreads();
-    // 256 threads = 8 rows x 32 lanes x 16 B per pass, 4 passes for the 32 rows
-#pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-      const int rr = pass * 8 + (tid >> 5), r = rt * 32 + rr;
-      if (r < R) {
-        const f32x4 val = *reinterpret_cast<const f32x4*>(ot + rr * OTS + 4 * (tid & 31));
-        __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + r) * D + 4 * (tid & 31)));
-      }
+    for (int b4 = 0; b4 < 4; ++b4) {
+      const int c = 8 * mt + 2 * b4 + hh;  // floats 32 mt + 8 b4 + 4 hh .. + 3 of row l32
+      if (l32 < R) otile[l32 * 32 + (c ^ l32)] = f32x4{O[mt][4 * b4], O[mt][4 * b4 + 1], O[mt][4 * b4 + 2], O[mt][4 * b4 + 3]};
     }
+  {
+    const float lw = l_run + __shfl_xor(l_run, 32, kWave);
+    if (hh == 0) { lds.mw[w][l32] = m_run; lds.lw[w][l32] = lw; }
   }
-  if (w == 0 && q4 == 0) {
+  __syncthreads();
+  float l_all = 0.f, m_all = -INFINITY;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int r = nt * 16 + c16;
-      if (r < R)
-        p.part_ml[part_row0 + r] =
-            make_float2(m_run[nt], lds.lsum[0][r] + lds.lsum[1][r] + lds.lsum[2][r] + lds.lsum[3][r]);
+  for (int pass = 0; pass < 4; ++pass) {
+    const int rr = pass * 8 + (tid >> 5), c = tid & 31;
+    if (rr < R) {
+      const float m0 = lds.mw[0][rr], m1 = lds.mw[1][rr], m2 = lds.mw[2][rr], m3 = lds.mw[3][rr];
+      const float ma = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));  // finite: wave 0 always has a block
+      const float s0 = fast_exp2(m0 - ma), s1 = fast_exp2(m1 - ma), s2 = fast_exp2(m2 - ma), s3 = fast_exp2(m3 - ma);
+      const f32x4* src = reinterpret_cast<const f32x4*>(&lds.tile[0]) + rr * 32 + (c ^ rr);  // + 1024 per wave
+      const f32x4 acc = src[0] * s0 + src[1024] * s1 + src[2048] * s2 + src[3072] * s3;
+      *reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + rr) * D + 4 * c) = acc;
+      if (c == 0) {  // one lane per row also writes (m, l)
+        l_all = lds.lw[0][rr] * s0 + lds.lw[1][rr] * s1 + lds.lw[2][rr] * s2 + lds.lw[3][rr] * s3;
+        m_all = ma;
+        p.part_ml[part_row0 + rr] = make_float2(m_all, l_all);
+      }
     }
   }
   PASTA_CLK(7);
 }
 
-// One launch for all partials of a decode step: work-groups [0, n_priv_wgs) are private
-// (gather) items -- they have the longer dependency chain, so they start first -- and the
-// rest are shared-prefix items.
-template <int RT, bool PAGED>
-__global__ __launch_bounds__(kAttnThreads, (RT == 1 ? 3 : (RT == 2 ? 2 : 1))) void k_attn(DecodeParams p) {
-  __shared__ AttnLds<RT> lds;
+// One launch for all partials of a decode step with at most 32 stacked rows per request;
+// the shared-prefix items' work-groups come first, the private (gather) items' after them.
+template <bool PAGED>
+__global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
+  __shared__ AttnLds lds;
   const int32_t* meta = meta_of(p);
   if (p.pend_n > 0) {
     // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads
@@ -487,24 +439,10 @@ __global__ __launch_bounds__(kAttnThreads, (RT == 1 ? 3 : (RT == 2 ? 2 : 1))) vo
       *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, dst[row], gh) + pc16 * 8) * 2) = val;
     }
   }
-  const int n_priv_wgs = p.n_mfma_items * p.Hkv;
-  if ((int)blockIdx.x < n_priv_wgs)
-    attn_item<1, PAGED, true>(p, reinterpret_cast<AttnLds<1>&>(lds), meta, blockIdx.x);
-  else
-    attn_item<RT, PAGED, false>(p, lds, meta, blockIdx.x - n_priv_wgs);
-}
-
-inline int launch_attn(int max_rows, dim3 grid, hipStream_t st, const DecodeParams& p) {
-  if (max_rows > kAttnMaxRows) return PASTA_E_INVAL;
-  const bool paged = p.lay.paged != 0;
-  if (max_rows <= 32) {
-    return PASTA_E_INVAL;  // served by k_attn_w
-  } else if (max_rows <= 64) {
-    if (paged) k_attn<2, true><<<grid, kAttnThreads, 0, st>>>(p); else k_attn<2, false><<<grid, kAttnThreads, 0, st>>>(p);
-  } else {
-    if (paged) k_attn<4, true><<<grid, kAttnThreads, 0, st>>>(p); else k_attn<4, false><<<grid, kAttnThreads, 0, st>>>(p);
-  }
-  return PASTA_OK;
+  // shared-prefix items first: they are the longer ones (up to two blocks per wave against one)
+  const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
+  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false>(p, lds, meta, blockIdx.x);
+  else attn_item<PAGED, true>(p, lds, meta, blockIdx.x - n_prefix_wgs);
 }
 
 }  // namespace pasta

@@ -3,22 +3,28 @@
 // identity used is  sum_t e^{z_t} v_t = sum_i e^{m_i} acc_i  over the parts i, so
 //   m = max_i m_i,  l = sum_i l_i 2^{m_i - m},  out = sum_i acc_i 2^{m_i - m} / l
 // (m in log2 units).  Parts with l_i = 0 (nothing visible in them) contribute nothing.
-// One work-group of 1024 threads per (stream, query head): the threads form 1024/D groups,
-// group k takes parts k, k + 1024/D, ... with one head-dim element per thread (a part's
+// One work-group of NT threads per (stream, query head): the threads form NT/D groups,
+// group k takes parts k, k + NT/D, ... with one head-dim element per thread (a part's
 // row is read as one coalesced 4D-byte line).  The kernel is a chain of memory round
 // trips, so everything that can be requested early is: the shared-prefix parts first
 // (their rows follow from kernel-argument scalars when the call holds one request), the
 // stream's record meanwhile, its private parts next.  The maximum is taken over what each
 // thread already holds plus an LDS exchange; the groups are added through LDS.
+// NT = 1024 for steps with few output rows (they are a chain of latencies, and wide work-groups
+// shorten it); with many rows the launch is bound by the rate at which wavefronts can be
+// started, and NT = 256 starts a quarter as many.
 #pragma once
 #include "pasta_dev.hpp"
 
 namespace pasta {
 
-constexpr int kMergeThreads = 1024;
+constexpr int kMergeThreads = 1024;      // few rows
+constexpr int kMergeThreadsSmall = 256;  // many rows
+constexpr int kMergeManyRows = 512;      // from this many (stream, query head) rows on: the small form
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kMergeThreads) void k_merge(DecodeParams p) {
+template <typename T, int D, int G, int NT>
+__global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
+  constexpr int kMergeThreads = NT;
   constexpr int NGRP = kMergeThreads / D;
   constexpr int UNR = 8;  // parts per thread and batch
   __shared__ float red[kMergeThreads / kWave];

@@ -17,7 +17,6 @@
 #include "../../include/pasta_attn.h"
 #include "k_append.hpp"
 #include "k_attn.hpp"
-#include "k_attn_w.hpp"
 #include "k_merge.hpp"
 #include "k_private.hpp"
 
@@ -206,11 +205,21 @@ int launch_private_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
 }
 template <typename T, int D>
 int launch_merge_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
+  if (grid.x >= (unsigned)kMergeManyRows) {
+    switch (G) {
+      case 1: k_merge<T, D, 1, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
+      case 2: k_merge<T, D, 2, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
+      case 4: k_merge<T, D, 4, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
+      case 8: k_merge<T, D, 8, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
+      default: return PASTA_E_INVAL;
+    }
+    return PASTA_OK;
+  }
   switch (G) {
-    case 1: k_merge<T, D, 1><<<grid, kMergeThreads, 0, st>>>(p); break;
-    case 2: k_merge<T, D, 2><<<grid, kMergeThreads, 0, st>>>(p); break;
-    case 4: k_merge<T, D, 4><<<grid, kMergeThreads, 0, st>>>(p); break;
-    case 8: k_merge<T, D, 8><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 1: k_merge<T, D, 1, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 2: k_merge<T, D, 2, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 4: k_merge<T, D, 4, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 8: k_merge<T, D, 8, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
     default: return PASTA_E_INVAL;
   }
   return PASTA_OK;
@@ -572,11 +581,11 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
 
     // ---- shared-prefix plan: only what the matrix-core kernel takes; the rest is private
     const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G);
-    int64_t pc_total = 0, max_rows = 1;
+    int64_t pc_total = 0, pc_weighted = 0;  // the second counts a prefix once per row group of 32
     for (auto& q : reqs) {
-      if (!mfma || q.pc < kTile || q.n_streams * G > kAttnMaxRows) q.pc = 0;
+      if (!mfma || q.pc < kTile) q.pc = 0;
       pc_total += q.pc;
-      if (q.pc) max_rows = std::max<int64_t>(max_rows, (int64_t)q.n_streams * G);
+      pc_weighted += (int64_t)q.pc * ((q.n_streams * G + 31) / 32);
     }
     // Chunking.  Every chunk costs one partial row per stacked query row (written here, read
     // by the merge), so chunks should be long; but the step wants at least one shared-prefix
@@ -585,7 +594,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     // items stay at 128 tokens: they are few and their rows are scattered.
     int64_t priv_chunk = kPrivChunk, chunk_tokens = kTile;
     if (mfma) {
-      chunk_tokens = std::max<int64_t>(kTile, pc_total * Hkv / kNumCUs / kTile * kTile);
+      chunk_tokens = std::max<int64_t>(kTile, pc_weighted * Hkv / kNumCUs / kTile * kTile);
       priv_chunk = 128;
       if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
       if (h->tune_priv_chunk >= kTile) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / kTile * kTile, kGatherMax);
@@ -654,7 +663,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
           q.chunk_tokens = (int32_t)chunk_tokens;
           q.wg_begin = (int32_t)n_prefix_wgs;
           q.part_base = (int32_t)prefix_rows;
-          n_prefix_wgs += (int64_t)q.n_chunks * Hkv;
+          n_prefix_wgs += (int64_t)q.n_chunks * Hkv * ((q.n_streams * G + 31) / 32);
           prefix_rows += (int64_t)q.n_chunks * Hkv * q.n_streams * G;
         }
         if (prefix_rows + priv_rows <= h->part_rows_cap) break;
@@ -762,13 +771,8 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       return PASTA_E_DEVICE;
     if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
-      if (max_rows <= 32) {  // the wave-autonomous form
-        if (h->lay.paged) k_attn_w<true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-        else k_attn_w<false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-      } else {
-        rc = launch_attn((int)max_rows, dim3(grid), st, p);
-        if (rc != PASTA_OK) return rc;
-      }
+      if (h->lay.paged) k_attn<true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+      else k_attn<false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
       if (take_pending) h->pending.active = false;
     } else if (!items.empty()) {
       const unsigned waves = (unsigned)items.size() * Hkv;

@@ -166,10 +166,12 @@ def test_head_shapes(dtype, Hq, Hkv, D):
 
 
 @pytest.mark.parametrize("prefix,lengths", [(128, [1]), (127, [5, 5]), (129, [200, 1]), (1000, [1, 1, 1]),
-                                            (4096 + 17, [130] * 9), (2, [300, 300]), (256, [64] * 33)])
+                                            (4096 + 17, [130] * 9), (2, [300, 300]), (256, [64] * 33),
+                                            (512, [20] * 40)])
 def test_ragged_tiles_and_stream_counts(prefix, lengths):
-    """Prefix lengths around the tile size, many streams (more stacked rows than one row tile),
-    more streams than the prefix kernel stacks (falls back to the private walk)."""
+    """Prefix lengths around the tile size; more stacked rows than one 32-row group (9 streams x 4:
+    a full group and a ragged one; 33 streams: five groups); 40 streams x 16 heads = 640 output
+    rows, which takes the narrow form of the merge."""
     w = W.single_request("ragged", "bf16", 16, 4, 128, 1.0, 33, prefix, lengths, "round_robin", k_std=128 ** -0.5)
     s = _session(w)
     op = OraclePool(w).append_events(w.n_prefill)
