@@ -122,7 +122,7 @@ def main():
 
     # ---- warm-up: decode only (no state change), cycling the layers
     warm = [s.h.prepare_decode(l % L, w.dec_request, w.dec_stream, q_steps[0], out[l % L], flags=flags)
-            for l in range(min(args.warmup, L))]
+            for l in range(max(1, min(args.warmup, L)))]
     for i in range(args.warmup):
         assert warm[i % len(warm)]() == 0
     torch.cuda.synchronize()
@@ -174,7 +174,7 @@ def main():
         lists = w.lists(last)
         q = w.q(last)
         reps, t_cpu = 0, 0.0
-        while reps < 3 or (t_cpu < 10.0 and reps < 64):
+        while reps < 3 or (t_cpu < 10.0 and reps < 512):
             c0 = time.perf_counter()
             ref, _ = oracle.attention(g, kp, vp, w.dec_request, *lists, q, w.scale)
             t_cpu += time.perf_counter() - c0
