@@ -8,6 +8,7 @@ from .pasta_oracle import (  # noqa: F401
     append,
     attention,
     attention_dense,
+    attention_q64,
     build,
     elem_offset,
     gather_map,
@@ -15,6 +16,9 @@ from .pasta_oracle import (  # noqa: F401
     num_threads,
     partial,
     phys_row,
+    rope,
+    round_pool,
     rows_per_layer,
     visible_dense,
+    widen_pool,
 )

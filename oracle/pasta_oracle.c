@@ -55,6 +55,7 @@ int oracle_num_threads(void) {
 
 /* ---------- element widening (exact) ---------- */
 static double widen(const void *base, int dtype, int64_t idx) {
+  if (dtype == 2) return ((const double *)base)[idx]; /* fp64: rotated queries only */
   if (dtype == 0) return (double)((const float *)base)[idx];
   uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16; /* bf16 = top half of fp32 */
   float f;
@@ -152,10 +153,10 @@ int64_t oracle_gather_map(const oracle_geom *g, int32_t req, int32_t prefix_len,
  * rows: copy the rows to contiguous fp64 buffers, logits, max-subtracted
  * softmax, weighted sum.  Also usable as the "partial" (m, l, acc) of a
  * subset when normalise == 0. ---------- */
-static int attend_rows(const oracle_geom *g, const void *k_pool, const void *v_pool, int64_t n,
-                       const int64_t *rows, const void *q, int64_t q_off, int32_t kv_head,
-                       double scale, int normalise, double *out /* [D] */, double *m_out,
-                       double *l_out) {
+static int attend_rows_q(const oracle_geom *g, const void *k_pool, const void *v_pool, int64_t n,
+                         const int64_t *rows, const void *q, int q_dtype, int64_t q_off, int32_t kv_head,
+                         double scale, int normalise, double *out /* [D] */, double *m_out,
+                         double *l_out) {
   const int64_t D = g->head_dim;
   double *Kc = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)D);
   double *Vc = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)D);
@@ -171,7 +172,7 @@ static int attend_rows(const oracle_geom *g, const void *k_pool, const void *v_p
   double m = -INFINITY;
   for (int64_t t = 0; t < n; ++t) {
     double s = 0.0;
-    for (int64_t d = 0; d < D; ++d) s += widen(q, g->dtype, q_off + d) * Kc[t * D + d];
+    for (int64_t d = 0; d < D; ++d) s += widen(q, q_dtype, q_off + d) * Kc[t * D + d];
     z[t] = scale * s;
     if (z[t] > m) m = z[t];
   }
@@ -190,14 +191,21 @@ static int attend_rows(const oracle_geom *g, const void *k_pool, const void *v_p
   return 0;
 }
 
+static int attend_rows(const oracle_geom *g, const void *k_pool, const void *v_pool, int64_t n,
+                       const int64_t *rows, const void *q, int64_t q_off, int32_t kv_head,
+                       double scale, int normalise, double *out, double *m_out, double *l_out) {
+  return attend_rows_q(g, k_pool, v_pool, n, rows, q, g->dtype, q_off, kv_head, scale, normalise, out,
+                       m_out, l_out);
+}
+
 /* ---------- A2+A3+A4 as one definition: for each stream gather its visible
  * rows and run textbook attention per query head.
  * q: [n][Hq][D] pool dtype.  out: [n][Hq][D] fp64.  lse: [n][Hq] fp64 or NULL. */
-int oracle_attention(const oracle_geom *g, const void *k_pool, const void *v_pool, int32_t n_streams,
-                     const int32_t *request_id, const int32_t *prefix_len,
-                     const int32_t *range_offsets, const int32_t *range_start,
-                     const int32_t *range_count, const int32_t *range_stride, const void *q,
-                     double scale, double *out, double *lse) {
+static int attention_core(const oracle_geom *g, const void *k_pool, const void *v_pool, int32_t n_streams,
+                          const int32_t *request_id, const int32_t *prefix_len,
+                          const int32_t *range_offsets, const int32_t *range_start,
+                          const int32_t *range_count, const int32_t *range_stride, const void *q,
+                          int q_dtype, double scale, double *out, double *lse) {
   const int64_t D = g->head_dim, Hq = g->n_q_heads;
   const int32_t G = g->n_q_heads / g->n_kv_heads;
   int64_t **maps = (int64_t **)calloc((size_t)n_streams, sizeof(int64_t *));
@@ -220,8 +228,8 @@ int oracle_attention(const oracle_geom *g, const void *k_pool, const void *v_poo
     for (int64_t w = 0; w < total; ++w) {
       int32_t s = (int32_t)(w / Hq), h = (int32_t)(w % Hq);
       double m, l;
-      int r = attend_rows(g, k_pool, v_pool, cnt[s], maps[s], q, ((int64_t)s * Hq + h) * D, h / G,
-                          scale, 1, out + ((int64_t)s * Hq + h) * D, &m, &l);
+      int r = attend_rows_q(g, k_pool, v_pool, cnt[s], maps[s], q, q_dtype, ((int64_t)s * Hq + h) * D,
+                            h / G, scale, 1, out + ((int64_t)s * Hq + h) * D, &m, &l);
       if (r != 0) {
 #pragma omp atomic write
         rc = r;
@@ -232,6 +240,74 @@ int oracle_attention(const oracle_geom *g, const void *k_pool, const void *v_poo
   for (int32_t s = 0; s < n_streams; ++s) free(maps[s]);
   free(maps); free(cnt);
   return rc;
+}
+
+int oracle_attention(const oracle_geom *g, const void *k_pool, const void *v_pool, int32_t n_streams,
+                     const int32_t *request_id, const int32_t *prefix_len,
+                     const int32_t *range_offsets, const int32_t *range_start,
+                     const int32_t *range_count, const int32_t *range_stride, const void *q,
+                     double scale, double *out, double *lse) {
+  return attention_core(g, k_pool, v_pool, n_streams, request_id, prefix_len, range_offsets, range_start,
+                        range_count, range_stride, q, g->dtype, scale, out, lse);
+}
+
+/* The same with queries given in fp64 (queries rotated by oracle_rope are not
+ * rounded back to the pool dtype: the rotation is part of the definition, the
+ * rounding of a rotated query would be an implementation's choice). */
+int oracle_attention_q64(const oracle_geom *g, const void *k_pool, const void *v_pool, int32_t n_streams,
+                         const int32_t *request_id, const int32_t *prefix_len,
+                         const int32_t *range_offsets, const int32_t *range_start,
+                         const int32_t *range_count, const int32_t *range_stride, const double *q,
+                         double scale, double *out, double *lse) {
+  return attention_core(g, k_pool, v_pool, n_streams, request_id, prefix_len, range_offsets, range_start,
+                        range_count, range_stride, q, 2, scale, out, lse);
+}
+
+/* ---------- rotary position embedding with given (estimated) position ids.
+ * The paper assigns position ids to tokens after a promise from the predicted
+ * length of the asynchronous block (Section 4, "Training a PASTA-SFT model";
+ * appendix "Positional Embedding") and leaves the embedding to the base model.
+ * Rotary embedding (RoFormer) in the half-split pairing that Gemma / Llama
+ * implementations use: the head dim is D/2 planes (x[f], x[f + D/2]); plane f is
+ * turned by the angle pos * theta^(-2 f / D).
+ * x, out: [n_rows][n_heads][D] fp64; pos: [n_rows]. ---------- */
+void oracle_rope(const double *x, int64_t n_rows, int32_t n_heads, int32_t D, const int32_t *pos,
+                 double theta, double *out) {
+  const int32_t half = D / 2;
+  for (int64_t r = 0; r < n_rows; ++r)
+    for (int32_t h = 0; h < n_heads; ++h) {
+      const double *xi = x + (r * n_heads + h) * (int64_t)D;
+      double *oi = out + (r * n_heads + h) * (int64_t)D;
+      for (int32_t f = 0; f < half; ++f) {
+        double angle = (double)pos[r] * pow(theta, -2.0 * (double)f / (double)D);
+        double c = cos(angle), sn = sin(angle);
+        oi[f] = xi[f] * c - xi[f + half] * sn;
+        oi[f + half] = xi[f + half] * c + xi[f] * sn;
+      }
+    }
+}
+
+/* ---------- fp64 -> pool dtype, one rounding to nearest even (what "the pool
+ * holds rotated keys in bf16 / fp32" means).  out: float[n] or uint16[n]. */
+void oracle_round_pool(const double *x, int64_t n, int32_t dtype, void *out) {
+  for (int64_t i = 0; i < n; ++i) {
+    if (dtype == 0) { ((float *)out)[i] = (float)x[i]; continue; }
+    double v = x[i];
+    float f;
+    if (v == 0.0 || !isfinite(v)) {
+      f = (float)v;
+    } else {
+      int e;
+      (void)frexp(v, &e);          /* |v| = m 2^e, m in [0.5, 1) */
+      int ulp_exp = (e - 1) - 7;   /* bf16 keeps 8 significant bits */
+      if (ulp_exp < -133) ulp_exp = -133; /* subnormal range of bf16 */
+      double q = nearbyint(ldexp(v, -ulp_exp)); /* ties to even in the default rounding mode */
+      f = (float)ldexp(q, ulp_exp);             /* exact: at most 9 significant bits */
+    }
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    ((uint16_t *)out)[i] = (uint16_t)(bits >> 16);
+  }
 }
 
 /* ---------- partial over an arbitrary subset of physical rows (for testing

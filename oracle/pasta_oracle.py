@@ -54,6 +54,12 @@ def _load():
         L.oracle_gather_map.argtypes = [P, C.c_int32, C.c_int32, C.c_int32, P, P, P, P]
         L.oracle_attention.restype = C.c_int
         L.oracle_attention.argtypes = [P, P, P, C.c_int32, P, P, P, P, P, P, P, C.c_double, P, P]
+        L.oracle_attention_q64.restype = C.c_int
+        L.oracle_attention_q64.argtypes = [P, P, P, C.c_int32, P, P, P, P, P, P, P, C.c_double, P, P]
+        L.oracle_rope.restype = None
+        L.oracle_rope.argtypes = [P, C.c_int64, C.c_int32, C.c_int32, P, C.c_double, P]
+        L.oracle_round_pool.restype = None
+        L.oracle_round_pool.argtypes = [P, C.c_int64, C.c_int32, P]
         L.oracle_partial.restype = C.c_int
         L.oracle_partial.argtypes = [P, P, P, C.c_int64, P, P, C.c_int32, C.c_double, P, P, P]
         L.oracle_merge.restype = C.c_int
@@ -162,6 +168,50 @@ def attention(g: Geom, k_pool, v_pool, request_id, prefix_len, range_offsets, ra
     if rc != 0:
         raise ValueError(f"oracle_attention failed: {rc}")
     return out, lse
+
+
+def attention_q64(g: Geom, k_pool, v_pool, request_id, prefix_len, range_offsets, range_start, range_count,
+                  range_stride, q64, scale):
+    """attention() with the queries given in float64 (rotated queries)."""
+    request_id, prefix_len, range_offsets = _i32(request_id), _i32(prefix_len), _i32(range_offsets)
+    rs, rc_, rst = _i32(range_start), _i32(range_count), _i32(range_stride)
+    n = request_id.shape[0]
+    q = np.ascontiguousarray(q64, dtype=np.float64)
+    assert q.size == n * g.Hq * g.D
+    out = np.empty((n, g.Hq, g.D), dtype=np.float64)
+    lse = np.empty((n, g.Hq), dtype=np.float64)
+    rc = _load().oracle_attention_q64(g.ref, _p(k_pool), _p(v_pool), n, _p(request_id), _p(prefix_len),
+                                      _p(range_offsets), _p(rs), _p(rc_), _p(rst), _p(q), float(scale),
+                                      _p(out), _p(lse))
+    if rc != 0:
+        raise ValueError(f"oracle_attention_q64 failed: {rc}")
+    return out, lse
+
+
+def rope(x, positions, theta):
+    """x: [n_rows][n_heads][D] (any float dtype, taken as float64); returns the rotated rows, float64."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    pos = _i32(positions)
+    assert x.ndim == 3 and pos.shape[0] == x.shape[0] and x.shape[2] % 2 == 0
+    out = np.empty_like(x)
+    _load().oracle_rope(_p(x), x.shape[0], x.shape[1], x.shape[2], _p(pos), float(theta), _p(out))
+    return out
+
+
+def round_pool(dtype, x):
+    """float64 -> pool dtype with one rounding to nearest even: float32, or uint16 bf16 bit patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    code = {"f32": 0, "bf16": 1}[dtype]
+    out = np.empty(x.shape, dtype=np.float32 if code == 0 else np.uint16)
+    _load().oracle_round_pool(_p(x), x.size, code, _p(out))
+    return out
+
+
+def widen_pool(dtype, x):
+    """pool dtype (float32, or uint16 bf16 bit patterns) -> float64, exact."""
+    if dtype == "f32":
+        return np.asarray(x, dtype=np.float32).astype(np.float64)
+    return (np.asarray(x, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
 def partial(g: Geom, k_pool, v_pool, phys_rows, q_row, kv_head, scale):

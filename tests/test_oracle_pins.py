@@ -3,6 +3,7 @@ forms, the paper's worked visibility example, brute force, invariances.  CPU onl
 from __future__ import annotations
 
 import json
+import math
 import os
 
 import numpy as np
@@ -442,3 +443,101 @@ def test_configs_have_the_stated_shapes():
         pages = w4.page_table[r, :-(-int(tails[r]) // 16)].tolist()
         assert not (used & set(pages))
         used |= set(pages)
+
+
+# ------------------------------------------------------------------ rotary embedding and rounding
+def _rand_rows(seed, n=5, H=3, D=16):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((n, H, D)), rng.integers(0, 5000, size=n).astype(np.int32)
+
+
+@pytest.mark.parametrize("D,theta", [(2, 10000.0), (16, 10000.0), (128, 10000.0), (64, 500000.0)])
+def test_rope_equals_complex_multiplication(D, theta):
+    """Plane f = (x[f], x[f + D/2]) read as a complex number is multiplied by
+    exp(i pos theta^(-2f/D)) -- numpy's complex arithmetic as the independent statement."""
+    x, pos = _rand_rows(3, D=D)
+    got = oracle.rope(x, pos, theta)
+    f = np.arange(D // 2)
+    z = (x[..., : D // 2] + 1j * x[..., D // 2:]) * np.exp(1j * pos[:, None, None] * theta ** (-2.0 * f / D))
+    assert np.allclose(got[..., : D // 2], z.real, rtol=0, atol=1e-12)
+    assert np.allclose(got[..., D // 2:], z.imag, rtol=0, atol=1e-12)
+
+
+def test_rope_two_dims_is_a_plane_rotation_by_pos_radians():
+    x = np.array([[[1.0, 0.0]], [[0.0, 1.0]], [[2.0, -3.0]]])
+    pos = np.array([1, 2, 7], np.int32)
+    got = oracle.rope(x, pos, 10000.0)
+    for i, p in enumerate(pos):
+        c, s = math.cos(p), math.sin(p)
+        a, b = x[i, 0]
+        assert np.allclose(got[i, 0], [a * c - b * s, b * c + a * s], atol=1e-15)
+
+
+def test_rope_invariants():
+    x, pos = _rand_rows(5, n=6, H=2, D=32)
+    y, _ = _rand_rows(6, n=6, H=2, D=32)
+    th = 10000.0
+    zero = np.zeros_like(pos)
+    assert np.array_equal(oracle.rope(x, zero, th), x)  # position 0: identity
+    rx = oracle.rope(x, pos, th)
+    for f in range(16):  # every plane keeps its length
+        assert np.allclose(rx[..., f] ** 2 + rx[..., f + 16] ** 2, x[..., f] ** 2 + x[..., f + 16] ** 2, rtol=1e-12)
+    # composition: turning by a then by b = turning by a + b
+    a = np.array([3, 10, 0, 77, 1000, 5], np.int32)
+    assert np.allclose(oracle.rope(oracle.rope(x, a, th), pos, th), oracle.rope(x, a + pos, th), atol=1e-9)
+    # relative position: <R(p) q, R(p') k> depends on p - p' only
+    shift = np.full_like(pos, 123)
+    d0 = (oracle.rope(x, pos, th) * oracle.rope(y, a, th)).sum(-1)
+    d1 = (oracle.rope(x, pos + shift, th) * oracle.rope(y, a + shift, th)).sum(-1)
+    assert np.allclose(d0, d1, atol=1e-9)
+    # frequencies: at position 1 the unit vector of plane f turns by theta^(-2f/D) radians
+    D = 32
+    e = np.zeros((D // 2, 1, D))
+    e[np.arange(D // 2), 0, np.arange(D // 2)] = 1.0
+    r = oracle.rope(e, np.ones(D // 2, np.int32), th)
+    ang = np.arctan2(r[np.arange(D // 2), 0, np.arange(D // 2) + D // 2], r[np.arange(D // 2), 0, np.arange(D // 2)])
+    assert np.allclose(ang, np.exp(-2.0 * np.arange(D // 2) / D * math.log(th)), atol=1e-12)
+
+
+def test_round_pool_is_round_to_nearest_even_once():
+    # against torch's float32 -> bfloat16 conversion on float32-representable inputs
+    rng = np.random.default_rng(11)
+    x = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-6, 6, 4000),
+                        [0.0, -0.0, 1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 255.5, 2.0 ** -130,
+                         3.3895313892515355e38]]).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.round_pool("bf16", x.astype(np.float64))
+    assert np.array_equal(got, want)
+    # ties: 1 + 2^-8 lies halfway between 1 and 1 + 2^-7 -> even (1.0); 1 + 3 * 2^-8 -> 1 + 2^-6
+    assert oracle.widen_pool("bf16", oracle.round_pool("bf16", np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8]))).tolist() == [1.0, 1 + 2.0 ** -6]
+    # one rounding, not two: just above the tie in fp64, where a detour through fp32 would land on the tie
+    y = np.array([1 + 2.0 ** -8 + 2.0 ** -40])
+    assert oracle.widen_pool("bf16", oracle.round_pool("bf16", y))[0] == 1 + 2.0 ** -7
+    assert np.array_equal(oracle.round_pool("f32", np.array([0.1, 1e-50, 3.0])), np.array([0.1, 1e-50, 3.0], np.float32))
+    # widen is exact
+    assert np.array_equal(oracle.widen_pool("bf16", want).astype(np.float32), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+
+
+def test_attention_with_rotated_queries_and_keys_sees_relative_positions_only():
+    """One stream, causal list: rotating q and every k by their positions, then shifting ALL
+    positions by a constant, leaves the output unchanged; and attention_q64 on unrotated
+    float64 queries equals attention() on the same queries in the pool dtype."""
+    rng = np.random.default_rng(5)
+    Hq, Hkv, D, N = 4, 2, 16, 40
+    g = oracle.Geom("f32", Hq, Hkv, D, pool_tokens=64)
+    k = rng.standard_normal((N, Hkv, D))
+    v = rng.standard_normal((N, Hkv, D)).astype(np.float32)
+    q = rng.standard_normal((1, Hq, D)).astype(np.float32)
+    outs = []
+    for shift in (0, 1000):
+        pos = np.arange(N, dtype=np.int32) + shift
+        kp, vp, tail = g.new_pool(), g.new_pool(), np.zeros(1, np.int64)
+        kr = oracle.round_pool("f32", oracle.rope(k, pos, 10000.0))
+        oracle.append(g, kp, vp, np.zeros(N, np.int32), kr, v, tail)
+        qr = oracle.rope(q, np.array([N - 1 + shift], np.int32), 10000.0)
+        o, _ = oracle.attention_q64(g, kp, vp, [0], [N], [0, 0], [], [], [], qr, 0.25)
+        outs.append(o)
+    assert np.allclose(outs[0], outs[1], atol=2e-5)  # fp32 pool rounding of the rotated keys
+    o32, l32 = oracle.attention(g, kp, vp, [0], [N], [0, 0], [], [], [], q, 0.25)
+    o64, l64 = oracle.attention_q64(g, kp, vp, [0], [N], [0, 0], [], [], [], q.astype(np.float64), 0.25)
+    assert np.array_equal(o32, o64) and np.array_equal(l32, l64)
