@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
     ap.add_argument("--eager-append", action="store_true",
                     help="run the KV-append as a launch of its own instead of letting it ride with the decode launch")
+    ap.add_argument("--rope", action="store_true",
+                    help="rotary embedding by position ids inside the path: K rotated by the append (a launch of its "
+                         "own, not deferred), Q rotated in the attention kernel")
     ap.add_argument("--workload", choices=["config3", "config2", "config4", "config5"], default="config3",
                     help="config3 (default) is the headline line; the others time decode steps only (their "
                          "state is a single step's) and exist to show how the kernels behave on the other shapes")
@@ -71,8 +74,10 @@ def main():
     tokens = -(-args.steps // L)  # token steps needed
     w = W.config3(steps=max(tokens, 2))
     layout = B.HEAD_MAJOR if args.layout == "head" else B.TOKEN_MAJOR
-    s = Session(w, kv_layout=layout, n_layers=L)
+    theta = 10000.0
+    s = Session(w, kv_layout=layout, n_layers=L, rope_theta=theta if args.rope else 0.0)
     hip = C.CDLL("libamdhip64.so.7")  # already loaded by torch: same runtime
+    ev_pos = w.event_positions() if args.rope else None
 
     # ---- prefill every layer (layer l holds the generator's rows rolled by l along D)
     n0 = w.n_prefill
@@ -80,7 +85,8 @@ def main():
     kd, vd = to_device(k0, w.dtype, dev), to_device(v0, w.dtype, dev)
     for l in range(L):
         s.h.append_kv(l, w.ev_request[:n0], w.ev_stream[:n0], torch.roll(kd, l, dims=2).contiguous(),
-                      torch.roll(vd, l, dims=2).contiguous(), parent_stream=w.ev_parent[:n0])
+                      torch.roll(vd, l, dims=2).contiguous(), parent_stream=w.ev_parent[:n0],
+                      position=ev_pos[:n0] if args.rope else None, flags=B.APPEND_ROPE if args.rope else 0)
     torch.cuda.synchronize()
 
     # ---- inputs of the timed loop, all resident on the device
@@ -91,7 +97,8 @@ def main():
     v_steps = [[torch.roll(vs[t], l, dims=2).contiguous() for l in range(L)] for t in range(tokens)]
     q_steps = [to_device(w.q(t), w.dtype, dev) for t in range(tokens)]
     out = torch.empty(L, w.n, w.Hq, w.D, dtype=torch.bfloat16, device=dev)
-    flags = B.DECODE_NO_MFMA if args.no_mfma else 0
+    flags = (B.DECODE_NO_MFMA if args.no_mfma else 0) | (B.DECODE_ROPE_Q if args.rope else 0)
+    q_pos = [w.q_positions(t) if args.rope else None for t in range(tokens)]
 
     # HIP events around the attention-partials kernels of sampled steps
     n_ev = args.steps // args.event_every + 1
@@ -107,10 +114,11 @@ def main():
     for i in range(args.steps):
         t, l = divmod(i, L)
         pe = (evs[2 * (i // args.event_every)], evs[2 * (i // args.event_every) + 1]) if i % args.event_every == 0 else None
-        calls.append((s.h.prepare_append(l, req_step, ev_step, k_steps[t][l], v_steps[t][l],
-                                         flags=0 if args.eager_append else B.APPEND_DEFER),
+        app_flags = (0 if args.eager_append else B.APPEND_DEFER) | (B.APPEND_ROPE if args.rope else 0)
+        calls.append((s.h.prepare_append(l, req_step, ev_step, k_steps[t][l], v_steps[t][l], flags=app_flags,
+                                         position=ev_pos[n0 + t * w.n:n0 + (t + 1) * w.n] if args.rope else None),
                       s.h.prepare_decode(l, w.dec_request, w.dec_stream, q_steps[t], out[l], flags=flags,
-                                         prof_events=pe)))
+                                         prof_events=pe, position=q_pos[t])))
 
     if args.calibrate:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -121,7 +129,8 @@ def main():
         del src, dst
 
     # ---- warm-up: decode only (no state change), cycling the layers
-    warm = [s.h.prepare_decode(l % L, w.dec_request, w.dec_stream, q_steps[0], out[l % L], flags=flags)
+    warm = [s.h.prepare_decode(l % L, w.dec_request, w.dec_stream, q_steps[0], out[l % L], flags=flags,
+                               position=q_pos[0])
             for l in range(max(1, min(args.warmup, L)))]
     for i in range(args.warmup):
         assert warm[i % len(warm)]() == 0
@@ -170,13 +179,19 @@ def main():
         g = oracle.Geom(w.dtype, w.Hq, w.Hkv, w.D, head_major=(layout == B.HEAD_MAJOR), pool_tokens=w.pool_tokens)
         kp, vp, tail = g.new_pool(), g.new_pool(), np.zeros(1, np.int64)
         ka, va = w.kv_rows(0, ne)
+        if args.rope:  # the oracle's pool holds keys rotated in fp64 and rounded once
+            ka = oracle.round_pool(w.dtype, oracle.rope(oracle.widen_pool(w.dtype, ka), ev_pos[:ne], theta))
         assert oracle.append(g, kp, vp, w.ev_request[:ne], ka, va, tail)[0] == 0
         lists = w.lists(last)
         q = w.q(last)
         reps, t_cpu = 0, 0.0
         while reps < 3 or (t_cpu < 10.0 and reps < 512):
             c0 = time.perf_counter()
-            ref, _ = oracle.attention(g, kp, vp, w.dec_request, *lists, q, w.scale)
+            if args.rope:
+                q64 = oracle.rope(oracle.widen_pool(w.dtype, q), q_pos[last], theta)
+                ref, _ = oracle.attention_q64(g, kp, vp, w.dec_request, *lists, q64, w.scale)
+            else:
+                ref, _ = oracle.attention(g, kp, vp, w.dec_request, *lists, q, w.scale)
             t_cpu += time.perf_counter() - c0
             reps += 1
         cpu = {"value": w.n * reps / t_cpu, "unit": "stream-tokens/s", "cores": oracle.num_threads(),
@@ -184,7 +199,8 @@ def main():
                "sample": f"{reps} decode steps (8 streams x 32 heads, {ne} pool rows) of one layer, fp64, "
                          f"{t_cpu:.1f} s; append not included (a 32 KiB copy)"}
         chk = torch.empty(w.n, w.Hq, w.D, dtype=torch.bfloat16, device=dev)
-        s.h.decode_step(0, w.dec_request, w.dec_stream, q_steps[last], chk, lists=lists, flags=flags)
+        s.h.decode_step(0, w.dec_request, w.dec_stream, q_steps[last], chk, lists=lists, flags=flags,
+                        position=q_pos[last])
         torch.cuda.synchronize()
         got = W.bf16_bits_to_f32(to_host_bits(chk, w.dtype)).astype(np.float64)
         result_extra["parity_vs_oracle"] = {"max_abs": float(np.max(np.abs(got - ref))),
@@ -212,7 +228,8 @@ def main():
         "config": {"workload": "config 3: bf16 32q/8kv heads D=128, prefix 8192, 8 streams L~U[64,512] "
                                "right-aligned round-robin, append+decode per step",
                    "n_layers_cycled": L, "kv_layout": args.layout, "visibility": "maintained lists",
-                   "append": "eager (own launch)" if args.eager_append else "deferred (rides with the decode launch)",
+                   "append": "eager (own launch)" if (args.eager_append or args.rope) else "deferred (rides with the decode launch)",
+                   "rope": "K rotated at append, Q in the attention kernel, theta 1e4" if args.rope else "off (Q, K arrive rotated)",
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

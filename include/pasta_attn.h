@@ -87,6 +87,9 @@ typedef struct {
   int32_t max_ranges;     /* most range descriptors one decode_step may carry
                              (sum over its streams) */
   float softmax_scale;    /* applied to q.k; explicit, never implied */
+  float rope_theta;       /* base of the rotary position embedding, e.g. 10000; 0 = the
+                             library never rotates (PASTA_APPEND_ROPE / PASTA_DECODE_ROPE_Q
+                             are then E_INVAL).  See "Rotary embedding" below. */
   int64_t pool_tokens;    /* contiguous mode: slots per request per layer (the
                              paper's fixed maximum sequence length) */
   void *k_pool;           /* DEVICE, borrowed for the handle's lifetime:
@@ -99,6 +102,21 @@ typedef struct {
   uint64_t workspace_bytes; /* in: bytes provided; query mode writes bytes needed */
   void *hip_stream;       /* hipStream_t of the caller; all work is enqueued here */
 } pasta_attn_config;
+
+/* Rotary embedding (optional).  Tokens decoded after a promise get ESTIMATED
+ * position ids, because the length of the asynchronous block before them is
+ * only predicted (Section 4, "Training a PASTA-SFT model": the model predicts each
+ * block's length in the promise tag's tokens attribute; appendix "Positional
+ * Embedding": lengths in multiples of ten).  Where the rotation is applied is not
+ * stated; here the caller passes the ids and the library can apply the base
+ * model's rotary embedding while it touches the data anyway: to K in append_kv
+ * (PASTA_APPEND_ROPE) and to Q in decode_step (PASTA_DECODE_ROPE_Q).  Convention:
+ * half-split pairs over the whole head dim -- with f = i mod D/2 and
+ * angle = position * rope_theta^(-2 f / D),
+ *   out[i]       = x[i] cos(angle) - x[i + D/2] sin(angle)        (i <  D/2)
+ *   out[i + D/2] = x[i + D/2] cos(angle) + x[i] sin(angle)
+ * computed in fp32 (angle reduced in fp64) and rounded once to the pool dtype.
+ * V is never rotated.                                                        */
 
 /* Creates a handle.  With out == NULL ("query mode") only validates cfg and
  * writes the required size into cfg->workspace_bytes; pointers in cfg may be
@@ -124,7 +142,7 @@ enum {
   PASTA_APPEND_RESERVE_ONLY = 1u, /* assign slots and advance the bookkeeping, copy nothing:
                                     the caller's own kernel writes the rows (out_slot says
                                     where); k_new / v_new may be NULL */
-  PASTA_APPEND_DEFER = 2u        /* bookkeeping now, copy later: the rows are copied into the
+  PASTA_APPEND_DEFER = 2u,       /* bookkeeping now, copy later: the rows are copied into the
                                     pool by the attention launch of the next decode_step on
                                     the same layer (which reads them from k_new / v_new
                                     wherever its lists name them), or by a small launch of
@@ -132,6 +150,10 @@ enum {
                                     take them along.  k_new / v_new must stay valid and
                                     unchanged until that work has run.  Saves one launch
                                     per append + decode step; ignored for more than 32 rows. */
+  PASTA_APPEND_ROPE = 4u         /* rotate every K row by position[i] on its way into the
+                                    pool (needs position != NULL and rope_theta > 0; not
+                                    with RESERVE_ONLY).  Combined with DEFER the copy is not
+                                    deferred: it runs as a launch of its own now. */
 };
 
 typedef struct {
@@ -147,10 +169,10 @@ typedef struct {
                                    rule).  -1 otherwise; a row with -1 whose stream
                                    is unknown opens a root stream (empty visible
                                    set). */
-  const int32_t *position;      /* HOST [n_rows] or NULL: position ids (the paper's
-                                   length-predicted ids, Section 4.1); carried for
-                                   the caller, not used by the arithmetic: Q and K
-                                   arrive already rotated */
+  const int32_t *position;      /* HOST [n_rows] or NULL: position ids >= 0 (the paper's
+                                   length-predicted ids).  Used only with
+                                   PASTA_APPEND_ROPE; otherwise K arrives already
+                                   rotated and the ids are ignored */
   const void *k_new;            /* DEVICE [n_rows][Hkv][D], pool dtype */
   const void *v_new;            /* DEVICE [n_rows][Hkv][D] */
   int32_t *out_slot;            /* HOST [n_rows] or NULL: logical slot given to row i */
@@ -181,8 +203,10 @@ int32_t pasta_attn_append_kv(pasta_attn *h, const pasta_append_args *a);
  * Output row i belongs to stream i of the call.                              */
 enum {
   PASTA_DECODE_PLAN_ONLY = 1u, /* validate + plan + fill HOST debug outputs, enqueue nothing */
-  PASTA_DECODE_NO_MFMA = 2u    /* route the shared prefix through the private-segment
+  PASTA_DECODE_NO_MFMA = 2u,   /* route the shared prefix through the private-segment
                                   kernel too (the path F32 always takes) */
+  PASTA_DECODE_ROPE_Q = 4u     /* rotate query row i by position[i] before use (q itself is
+                                  not modified; needs position != NULL, rope_theta > 0) */
 };
 
 typedef struct {
@@ -192,7 +216,8 @@ typedef struct {
   int32_t n_streams;            /* n >= 1 */
   const int32_t *request_id;    /* HOST [n] */
   const int32_t *stream_id;     /* HOST [n]; (request, stream) pairs distinct */
-  const int32_t *position;      /* HOST [n] or NULL; carried, unused */
+  const int32_t *position;      /* HOST [n] or NULL: position id >= 0 of each query token;
+                                   used only with PASTA_DECODE_ROPE_Q */
   const int32_t *prefix_len;    /* HOST [n]   (explicit mode) */
   const int32_t *range_offsets; /* HOST [n+1] (explicit mode) or NULL */
   const int32_t *range_start;   /* HOST [range_offsets[n]] */

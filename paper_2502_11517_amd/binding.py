@@ -19,8 +19,8 @@ _lib = None
 OK, E_INVAL, E_CAPACITY, E_NOMEM, E_DEVICE, E_STATE = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
-DECODE_PLAN_ONLY, DECODE_NO_MFMA = 1, 2
-APPEND_RESERVE_ONLY, APPEND_DEFER = 1, 2
+DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q = 1, 2, 4
+APPEND_RESERVE_ONLY, APPEND_DEFER, APPEND_ROPE = 1, 2, 4
 _ERR = {E_INVAL: "E_INVAL", E_CAPACITY: "E_CAPACITY", E_NOMEM: "E_NOMEM", E_DEVICE: "E_DEVICE",
         E_STATE: "E_STATE"}
 
@@ -56,7 +56,8 @@ class Config(C.Structure):
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("n_layers", C.c_int32),
         ("max_requests", C.c_int32), ("page_tokens", C.c_int32), ("kv_layout", C.c_int32),
         ("n_phys_pages", C.c_int32), ("pages_per_request", C.c_int32), ("max_streams", C.c_int32),
-        ("max_ranges", C.c_int32), ("softmax_scale", C.c_float), ("pool_tokens", C.c_int64),
+        ("max_ranges", C.c_int32), ("softmax_scale", C.c_float), ("rope_theta", C.c_float),
+        ("pool_tokens", C.c_int64),
         ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("hip_stream", C.c_void_p),
     ]
@@ -118,7 +119,7 @@ def _dp(t):
 
 def make_config(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale, *, n_layers=1, max_requests=1,
                 page_tokens=0, kv_layout=TOKEN_MAJOR, n_phys_pages=0, pages_per_request=0,
-                max_streams=2, max_ranges=1024, pool_tokens=0) -> Config:
+                max_streams=2, max_ranges=1024, pool_tokens=0, rope_theta=0.0) -> Config:
     c = Config()
     c.struct_size = C.sizeof(Config)
     c.dtype = {"f32": F32, "bf16": BF16}.get(dtype, dtype)
@@ -126,6 +127,7 @@ def make_config(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale, *, n_laye
     c.n_layers, c.max_requests, c.page_tokens, c.kv_layout = n_layers, max_requests, page_tokens, kv_layout
     c.n_phys_pages, c.pages_per_request = n_phys_pages, pages_per_request
     c.max_streams, c.max_ranges, c.softmax_scale, c.pool_tokens = max_streams, max_ranges, softmax_scale, pool_tokens
+    c.rope_theta = rope_theta
     return c
 
 
@@ -189,20 +191,21 @@ class PastaAttn:
             raise PastaError(rc, "pasta_attn_decode_step")
 
     # ---- prepared calls: marshal once, call many times (tight serving loops) ----
-    def prepare_append(self, layer, request_id, stream_id, k_new, v_new, parent_stream=None, flags=0):
+    def prepare_append(self, layer, request_id, stream_id, k_new, v_new, parent_stream=None, flags=0,
+                       position=None):
         """Returns f() -> status that issues this exact append; arrays are kept alive by f."""
-        rid, sid, par = _i32(request_id), _i32(stream_id), _i32(parent_stream)
+        rid, sid, par, pos = _i32(request_id), _i32(stream_id), _i32(parent_stream), _i32(position)
         a = AppendArgs(C.sizeof(AppendArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), _hp(par),
-                       None, _dp(k_new), _dp(v_new), None)
+                       _hp(pos), _dp(k_new), _dp(v_new), None)
         fn, h, ref = self._lib.pasta_attn_append_kv, self._h, C.byref(a)
 
-        def call(_keep=(rid, sid, par, a, k_new, v_new)):
+        def call(_keep=(rid, sid, par, pos, a, k_new, v_new)):
             return fn(h, ref)
         return call
 
     def prepare_decode(self, layer, request_id, stream_id, q, out, *, lists=None, out_lse=None, flags=0,
-                       prof_events=None):
-        rid, sid = _i32(request_id), _i32(stream_id)
+                       prof_events=None, position=None):
+        rid, sid, pos = _i32(request_id), _i32(stream_id), _i32(position)
         if lists is not None:
             pl, offs, st, ct, sd = (_i32(x) for x in lists)
             if st.size == 0:
@@ -210,12 +213,12 @@ class PastaAttn:
         else:
             pl = offs = st = ct = sd = None
         ev0, ev1 = prof_events if prof_events is not None else (None, None)
-        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), None, _hp(pl),
+        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), _hp(pos), _hp(pl),
                        _hp(offs), _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), None, None, None,
                        ev0, ev1)
         fn, h, ref = self._lib.pasta_attn_decode_step, self._h, C.byref(a)
 
-        def call(_keep=(rid, sid, pl, offs, st, ct, sd, a, q, out, out_lse)):
+        def call(_keep=(rid, sid, pos, pl, offs, st, ct, sd, a, q, out, out_lse)):
             return fn(h, ref)
         return call
 

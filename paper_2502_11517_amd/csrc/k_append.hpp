@@ -2,8 +2,9 @@
 // every active thread's new K/V row goes to the next free slot of the shared pool, so rows
 // of concurrently decoding threads end up in neighbouring slots.  A pure copy: each lane
 // moves one 16-byte piece of one (row, kv head) from k_new/v_new to its pool position.
+// With the rotary option the K pieces are turned by the row's position id on the way (V never).
 #pragma once
-#include "pasta_dev.hpp"
+#include "k_rope.hpp"
 
 namespace pasta {
 
@@ -20,6 +21,10 @@ struct AppendParams {
   int n_rows, Hkv;
   int pieces_per_head;  // D * elem_bytes / 16
   int elem_shift;       // log2(elem_bytes)
+  // rotary embedding of K (rope_tab == nullptr: plain copy)
+  const double* rope_tab;             // theta^(-2f/D) / (2 pi), f < D/2 (device)
+  const int32_t* pos_rows;            // position id per appended row (device), or null:
+  int32_t inline_pos[kAppendInline];  // then the ids are here
 };
 
 __global__ __launch_bounds__(256) void k_append(AppendParams p) {
@@ -34,7 +39,14 @@ __global__ __launch_bounds__(256) void k_append(AppendParams p) {
   const int row = (int)(rh / p.Hkv);
   const int phys = p.dst_rows ? p.dst_rows[row] : p.inline_rows[row];
   const long long off_bytes = (elem_off(p.lay, phys, g) << p.elem_shift) + (long long)piece * 16;
-  const uint4 val = (is_v ? p.v_new : p.k_new)[t];
+  uint4 val;
+  if (p.rope_tab && !is_v) {
+    const int pos = p.pos_rows ? p.pos_rows[row] : p.inline_pos[row];
+    val = rope_row_piece(p.k_new + rh * p.pieces_per_head, piece, p.pieces_per_head, p.elem_shift == 2, pos,
+                         p.rope_tab);
+  } else {
+    val = (is_v ? p.v_new : p.k_new)[t];
+  }
   *reinterpret_cast<uint4*>(reinterpret_cast<char*>(is_v ? p.v : p.k) + off_bytes) = val;
 }
 

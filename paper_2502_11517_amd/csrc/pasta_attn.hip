@@ -53,6 +53,7 @@ struct pasta_attn {
   std::vector<StreamState> streams;      // [max_requests * max_streams]
   // workspace carve-up (byte offsets)
   size_t off_page_table = 0, off_meta = 0, meta_bytes = 0, off_ml = 0, off_acc = 0;
+  size_t off_rope = 0, off_qrot = 0;  // rotary table (fp64, D/2 entries) and rotated-Q buffer (rope_theta > 0)
   int64_t part_rows_cap = 0;
   // a deferred append (PASTA_APPEND_DEFER): its copy is done by the next decode_step's launch
   struct Pending {
@@ -60,6 +61,8 @@ struct pasta_attn {
     int layer = 0, n_rows = 0;
     const void *k_new = nullptr, *v_new = nullptr;
     int32_t dst_rows[kAppendInline]{};
+    bool rope = false;                 // PASTA_APPEND_ROPE: K still to be rotated by pos
+    int32_t pos[kAppendInline]{};
     std::vector<int32_t> req_pend0, req_src0;  // per request: first deferred slot, its row in k_new
   } pending;
   int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // PASTA_PREFIX_CHUNK / PASTA_PRIV_CHUNK (tokens; 0 = heuristic)
@@ -94,6 +97,8 @@ int validate_cfg(const pasta_attn_config* c) {
   if (c->n_layers < 1 || c->max_requests < 1 || c->max_streams < 1 || c->max_ranges < 1) return PASTA_E_INVAL;
   if (c->kv_layout != PASTA_LAYOUT_TOKEN_MAJOR && c->kv_layout != PASTA_LAYOUT_HEAD_MAJOR) return PASTA_E_INVAL;
   if (!(c->softmax_scale > 0.f) || !std::isfinite(c->softmax_scale)) return PASTA_E_INVAL;
+  if (!(c->rope_theta >= 0.f) || !std::isfinite(c->rope_theta) || (c->rope_theta > 0.f && c->rope_theta < 1.f))
+    return PASTA_E_INVAL;
   if (c->page_tokens == 0) {
     if (c->pool_tokens < 1) return PASTA_E_INVAL;
     if ((int64_t)c->max_requests * c->pool_tokens >= ((int64_t)1 << 31)) return PASTA_E_INVAL;
@@ -130,6 +135,12 @@ void carve(pasta_attn* h) {
   off += align_up((size_t)h->part_rows_cap * sizeof(float2), 256);
   h->off_acc = off;
   off += align_up((size_t)h->part_rows_cap * c.head_dim * sizeof(float), 256);
+  if (c.rope_theta > 0.f) {
+    h->off_rope = off;
+    off += align_up((size_t)kRopeTabEntries * sizeof(double), 256);
+    h->off_qrot = off;
+    off += align_up((size_t)c.max_requests * c.max_streams * c.n_q_heads * c.head_dim * h->elem, 256);
+  }
   h->cfg.workspace_bytes = off;
 }
 
@@ -145,6 +156,19 @@ int ensure_device(pasta_attn* h) {
   if (h->cfg.page_tokens) {
     if (hipMemcpy((char*)h->cfg.workspace + h->off_page_table, h->page_table.data(),
                   h->page_table.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
+      return PASTA_E_DEVICE;
+  }
+  if (h->cfg.rope_theta > 0.f) {  // theta^(-2f/D) / (2 pi) in fp64: angles are taken in revolutions
+    const int D = h->cfg.head_dim;
+    const double two_pi = 6.283185307179586476925286766559, th = (double)h->cfg.rope_theta;
+    std::vector<double> tab(kRopeTabEntries, 0.0);
+    for (int f = 0; f < D / 2; ++f) tab[f] = std::pow(th, -2.0 * f / D) / two_pi;
+    for (int k = 0; k < 8; ++k) {  // f = 8 a + b (the attention kernel, D = 128)
+      tab[kRopeTabFactorA + k] = std::pow(th, -16.0 * k / D) / two_pi;
+      tab[kRopeTabFactorB + k] = std::pow(th, -2.0 * k / D);
+    }
+    if (hipMemcpy((char*)h->cfg.workspace + h->off_rope, tab.data(), tab.size() * sizeof(double),
+                  hipMemcpyHostToDevice) != hipSuccess)
       return PASTA_E_DEVICE;
   }
   h->device_ready = true;
@@ -240,7 +264,7 @@ int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodePar
 }
 
 int launch_append(pasta_attn* h, int layer, int n_rows, const void* k_new, const void* v_new,
-                  const int32_t* dst_rows) {
+                  const int32_t* dst_rows, const int32_t* positions = nullptr) {  // positions: rotate K
   const pasta_attn_config& c = h->cfg;
   hipStream_t st = (hipStream_t)c.hip_stream;
   AppendParams p{};
@@ -251,12 +275,15 @@ int launch_append(pasta_attn* h, int layer, int n_rows, const void* k_new, const
   p.pieces_per_head = c.head_dim * h->elem / 16;
   p.elem_shift = h->elem == 4 ? 2 : 1;
   const size_t row_bytes = (size_t)c.n_kv_heads * c.head_dim * h->elem;
+  p.rope_tab = positions ? (const double*)((const char*)c.workspace + h->off_rope) : nullptr;
+  p.pos_rows = nullptr;
   if (n_rows <= kAppendInline) {
     p.k_new = (const uint4*)k_new;
     p.v_new = (const uint4*)v_new;
     p.n_rows = n_rows;
     p.dst_rows = nullptr;
     std::memcpy(p.inline_rows, dst_rows, (size_t)n_rows * 4);
+    if (positions) std::memcpy(p.inline_pos, positions, (size_t)n_rows * 4);
     const long long total = 2ll * n_rows * c.n_kv_heads * p.pieces_per_head;
     k_append<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? PASTA_OK : PASTA_E_DEVICE;
@@ -269,6 +296,11 @@ int launch_append(pasta_attn* h, int layer, int n_rows, const void* k_new, const
     int rc = upload_meta(h, dst_rows + lo, n * 4, &dev);
     if (rc != PASTA_OK) return rc;
     p.dst_rows = dev;
+    if (positions) {
+      rc = upload_meta(h, positions + lo, n * 4, &dev);
+      if (rc != PASTA_OK) return rc;
+      p.pos_rows = dev;
+    }
     p.n_rows = (int)n;
     p.k_new = (const uint4*)((const char*)k_new + lo * row_bytes);
     p.v_new = (const uint4*)((const char*)v_new + lo * row_bytes);
@@ -284,7 +316,7 @@ int flush_pending(pasta_attn* h) {
   if (!h->pending.active) return PASTA_OK;
   h->pending.active = false;
   return launch_append(h, h->pending.layer, h->pending.n_rows, h->pending.k_new, h->pending.v_new,
-                       h->pending.dst_rows);
+                       h->pending.dst_rows, h->pending.rope ? h->pending.pos : nullptr);
 }
 
 }  // namespace
@@ -388,6 +420,12 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
   if (!a->request_id || !a->stream_id) return PASTA_E_INVAL;
   if (!reserve_only && (!a->k_new || !a->v_new)) return PASTA_E_INVAL;
   if (!reserve_only && (((uintptr_t)a->k_new & 15) || ((uintptr_t)a->v_new & 15))) return PASTA_E_INVAL;
+  const bool rope = a->flags & PASTA_APPEND_ROPE;
+  if (rope) {
+    if (reserve_only || !a->position || !(c.rope_theta > 0.f)) return PASTA_E_INVAL;
+    for (int i = 0; i < a->n_rows; ++i)
+      if (a->position[i] < 0) return PASTA_E_INVAL;
+  }
   const bool commit = a->layer == 0;  // layer 0 assigns the slots; other layers replay them
 
   // ---- dry run on copies of the touched state
@@ -448,7 +486,9 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
     if (rc != PASTA_OK) return rc;
     rc = flush_pending(h);  // at most one deferred append is outstanding
     if (rc != PASTA_OK) return rc;
-    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline;
+    // (a deferred rotating append can only ride with the matrix-core kernel: bf16, D = 128)
+    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline &&
+                 (!rope || (c.dtype == PASTA_BF16 && c.head_dim == 128));
     std::vector<int32_t> p0, s0;
     if (defer) {  // rows of one request must be consecutive in the call: slot t <-> row src0 + (t - pend0)
       p0.assign(c.max_requests, INT32_MAX);
@@ -469,10 +509,12 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
       pd.k_new = a->k_new;
       pd.v_new = a->v_new;
       std::memcpy(pd.dst_rows, dst_rows.data(), (size_t)a->n_rows * 4);
+      pd.rope = rope;
+      if (rope) std::memcpy(pd.pos, a->position, (size_t)a->n_rows * 4);
       pd.req_pend0.swap(p0);
       pd.req_src0.swap(s0);
     } else {
-      rc = launch_append(h, a->layer, a->n_rows, a->k_new, a->v_new, dst_rows.data());
+      rc = launch_append(h, a->layer, a->n_rows, a->k_new, a->v_new, dst_rows.data(), rope ? a->position : nullptr);
       if (rc != PASTA_OK) return rc;
     }
   }
@@ -511,6 +553,12 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
   const bool plan_only = a->flags & PASTA_DECODE_PLAN_ONLY;
   if (!plan_only && (!a->q || !a->out)) return PASTA_E_INVAL;
   if (!plan_only && (((uintptr_t)a->q & 15) || ((uintptr_t)a->out & 3))) return PASTA_E_INVAL;
+  const bool rope_q = a->flags & PASTA_DECODE_ROPE_Q;
+  if (rope_q) {
+    if (!a->position || !(c.rope_theta > 0.f)) return PASTA_E_INVAL;
+    for (int i = 0; i < n; ++i)
+      if (a->position[i] < 0) return PASTA_E_INVAL;
+  }
   const bool explicit_mode = a->range_offsets != nullptr;
   if (explicit_mode && !a->prefix_len) return PASTA_E_INVAL;
   const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
@@ -611,6 +659,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       ds.req = q.req;
       ds.req_idx = stream_req_idx[i];
       ds.local = stream_local[i];
+      ds.pos = rope_q ? a->position[i] : 0;
       ds.pc = q.pc;
       ds.range_begin = (int32_t)ranges.size();
       int32_t cum = 0;
@@ -722,6 +771,11 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       p.v_pend = pd.v_new;
       p.pend_n = pd.n_rows;
       std::memcpy(p.pend_dst, pd.dst_rows, sizeof(p.pend_dst));
+      if (pd.rope) {
+        p.pend_rope = 1;
+        std::memcpy(p.pend_pos, pd.pos, sizeof(p.pend_pos));
+        p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
+      }
       // the blob was built before these fields were known: patch the two tables in place
       std::memcpy(blob.data() + p.off_reqs, reqs.data(), reqs.size() * sizeof(DevReq));
       std::memcpy(blob.data() + p.off_items, items.data(), items.size() * sizeof(DevItem));
@@ -771,10 +825,24 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       return PASTA_E_DEVICE;
     if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
-      if (h->lay.paged) k_attn<true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-      else k_attn<false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+      if (rope_q) {  // Q is rotated on its way into the kernel's LDS
+        p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
+        if (h->lay.paged) k_attn<true, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        else k_attn<false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+      } else {
+        if (h->lay.paged) k_attn<true, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        else k_attn<false, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+      }
       if (take_pending) h->pending.active = false;
     } else if (!items.empty()) {
+      if (rope_q) {  // the vector-ALU walker reads Q from a rotated copy
+        p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
+        uint4* q_rot = (uint4*)((char*)c.workspace + h->off_qrot);
+        const int pph = D * h->elem / 16;
+        const long long total = (long long)n * c.n_q_heads * pph;
+        k_rope_q<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p, q_rot, pph, h->elem == 4);
+        p.q = q_rot;
+      }
       const unsigned waves = (unsigned)items.size() * Hkv;
       rc = launch_private(h, dim3((waves + 3) / 4), st, p);
       if (rc != PASTA_OK) return rc;

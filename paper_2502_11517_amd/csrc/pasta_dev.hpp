@@ -51,7 +51,8 @@ struct DevStream {      // one per decoding stream, call order
   int32_t item_begin;   // private work items [item_begin, item_end)
   int32_t item_end;
   int32_t gather_base;  // first entry of this stream in dbg_gather_rows
-  int32_t pad[3];
+  int32_t pos;          // position id of the stream's query token (rotary embedding of Q)
+  int32_t pad[2];
 };
 struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it
   int32_t start, count, stride, cum;
@@ -108,14 +109,20 @@ struct DecodeParams {
   const void* v_pend;
   int pend_n;           // rows of the deferred append (0: none)
   int32_t pend_dst[32]; // their physical rows
+  int32_t pend_pos[32]; // their position ids, when pend_rope
+  int pend_rope;        // 1: the deferred K rows are still unrotated (PASTA_APPEND_ROPE): whoever reads or
+                        //    copies them turns them by pend_pos
   int32_t s_items[32];  // single_req with <= 16 streams: stream i's private items are
                         //   [s_items[2i], s_items[2i] + s_items[2i+1]) -- spares the merge a table look-up
+  const double* rope_tab;  // theta^(-2f/D) / (2 pi), f < D/2 (device), when Q is rotated in the kernel
   int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
   DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way
                         //    to the first K/V load)
   int32_t inline_meta[kInlineMetaWords];  // the blob itself when meta == nullptr (small plans:
                                           // no host-to-device copy on the step's critical path)
 };
+
+static_assert(sizeof(DecodeParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 // The metadata blob: device memory, or the copy inside the kernel arguments.  The inline copy
 // is addressed through the kernarg segment pointer (DecodeParams is always the first kernel
@@ -126,6 +133,17 @@ __device__ __forceinline__ const int32_t* meta_of(const DecodeParams& p) {
   typedef const char __attribute__((address_space(4))) * kernarg_ptr;
   kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, inline_meta));
+}
+
+// One 32-bit word of the blob, loaded through a pointer of known address space (global or
+// kernel-argument memory, chosen by a uniform branch).  meta_of()'s merged pointer makes FLAT
+// loads, whose completion is not ordered with other loads: fine before anything else is in
+// flight, costly (a wait for everything) once the K/V loads are.
+__device__ __forceinline__ int32_t meta_word(const DecodeParams& p, int word) {
+  if (p.meta) return p.meta[word];
+  typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+  kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  return *(const int32_t __attribute__((address_space(4)))*)(ka + __builtin_offsetof(DecodeParams, inline_meta) + 4 * word);
 }
 
 __device__ __forceinline__ const int32_t* s_items_of(const DecodeParams& p) {
@@ -140,6 +158,13 @@ __device__ __forceinline__ const int32_t* pend_dst_of(const DecodeParams& p) {
   typedef const char __attribute__((address_space(4))) * kernarg_ptr;
   kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, pend_dst));
+}
+
+__device__ __forceinline__ const int32_t* pend_pos_of(const DecodeParams& p) {
+  (void)p;
+  typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+  kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, pend_pos));
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

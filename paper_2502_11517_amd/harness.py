@@ -31,7 +31,7 @@ class Session:
     """A handle plus the device buffers it borrows, shaped after a Workload."""
 
     def __init__(self, w: Workload, *, kv_layout=B.TOKEN_MAJOR, n_layers=1, device="cuda:0",
-                 max_ranges=None, max_streams=None):
+                 max_ranges=None, max_streams=None, rope_theta=0.0):
         self.w, self.device, self.n_layers, self.kv_layout = w, torch.device(device), n_layers, kv_layout
         torch.cuda.set_device(self.device)
         if max_ranges is None:
@@ -41,7 +41,7 @@ class Session:
                                  kv_layout=kv_layout, n_phys_pages=w.n_phys_pages,
                                  pages_per_request=w.pages_per_request,
                                  max_streams=max_streams or w.max_streams, max_ranges=max_ranges,
-                                 pool_tokens=w.pool_tokens)
+                                 pool_tokens=w.pool_tokens, rope_theta=rope_theta)
         ws_bytes = B.query_workspace_bytes(self.cfg)
         rows = (w.n_phys_pages * w.page_tokens) if w.page_tokens else w.max_requests * w.pool_tokens
         self.rows_per_layer = rows
@@ -56,8 +56,10 @@ class Session:
                              stream=self.stream.cuda_stream, page_table=w.page_table)
         self.n_done = 0
 
-    def append_events(self, hi: int, layer: int = 0, chunk: int = 8192, lo: int | None = None, flags: int = 0):
-        """Appends events [n_done, hi) of the workload's history (K/V rows from the generator)."""
+    def append_events(self, hi: int, layer: int = 0, chunk: int = 8192, lo: int | None = None, flags: int = 0,
+                      positions=None):
+        """Appends events [n_done, hi) of the workload's history (K/V rows from the generator);
+        positions: position id per event of the history (for flags with APPEND_ROPE)."""
         w = self.w
         pos = self.n_done if lo is None else lo
         while pos < hi:
@@ -66,14 +68,15 @@ class Session:
             kd, vd = to_device(k, w.dtype, self.device), to_device(v, w.dtype, self.device)
             self._keep_rows = (kd, vd)  # a deferred append reads them later
             self.h.append_kv(layer, w.ev_request[pos:b], w.ev_stream[pos:b], kd, vd,
-                             parent_stream=w.ev_parent[pos:b], flags=flags)
+                             parent_stream=w.ev_parent[pos:b], flags=flags,
+                             position=None if positions is None else positions[pos:b])
             pos = b
         if layer == 0 and lo is None:
             self.n_done = hi
         return self
 
     def decode(self, step: int = 0, *, layer: int = 0, explicit: bool = True, q=None, flags=0,
-               want_lse=True, want_gather=False):
+               want_lse=True, want_gather=False, position=None):
         w = self.w
         q = w.q(step) if q is None else q
         qd = to_device(q, w.dtype, self.device)
@@ -85,10 +88,11 @@ class Session:
             goffs = np.zeros(w.n + 1, np.int64)
             plan = np.zeros(8, np.int64)
             self.h.decode_step(layer, w.dec_request, w.dec_stream, qd, out, lists=lists,
-                               flags=flags | B.DECODE_PLAN_ONLY, dbg_gather_offsets=goffs, dbg_plan=plan)
+                               flags=flags | B.DECODE_PLAN_ONLY, dbg_gather_offsets=goffs, dbg_plan=plan,
+                               position=position)
             grows = torch.full((int(goffs[-1]),), -1, dtype=torch.int32, device=self.device)
         self.h.decode_step(layer, w.dec_request, w.dec_stream, qd, out, lists=lists, out_lse=lse, flags=flags,
-                           dbg_gather_offsets=goffs, dbg_gather_rows=grows)
+                           dbg_gather_offsets=goffs, dbg_gather_rows=grows, position=position)
         return out, lse, (goffs, grows)
 
     def pool_bits(self, layer: int = 0):

@@ -134,6 +134,37 @@ class Workload:
         x = rng.standard_normal((self.n, self.Hq, self.D), dtype=np.float32) * np.float32(self.q_std)
         return self._encode(x)
 
+    def event_positions(self, n_events: int | None = None) -> np.ndarray:
+        """A position id for every event, as inputs for the rotary option: a stream counts up from
+        where it starts; a fork starts at its parent's next id, and the parent then jumps ahead by
+        a seeded multiple of ten (the stand-in for a predicted block length)."""
+        n_events = len(self.ev_request) if n_events is None else n_events
+        rng = np.random.default_rng([self.seed, 3])
+        nxt: dict = {}
+        pos = np.empty(n_events, np.int32)
+        for e in range(n_events):
+            key = (int(self.ev_request[e]), int(self.ev_stream[e]))
+            if key not in nxt:
+                par = (key[0], int(self.ev_parent[e]))
+                if par in nxt:
+                    nxt[key] = nxt[par]
+                    nxt[par] += 10 * int(rng.integers(1, 30))
+                else:
+                    nxt[key] = 0
+            pos[e] = nxt[key]
+            nxt[key] += 1
+        return pos
+
+    def q_positions(self, step: int = 0) -> np.ndarray:
+        """Position id of each decoding stream's newest token at decode step `step`."""
+        ne = self.n_events(step)
+        pos = self.event_positions(ne)
+        out = np.zeros(self.n, np.int32)
+        for i in range(self.n):
+            m = np.nonzero((self.ev_request[:ne] == self.dec_request[i]) & (self.ev_stream[:ne] == self.dec_stream[i]))[0]
+            out[i] = pos[m[-1]] if m.size else 0
+        return out
+
     def event_slots(self, n_events: int | None = None) -> np.ndarray:
         """Logical slot of every event: its rank among the events of its request."""
         n_events = len(self.ev_request) if n_events is None else n_events

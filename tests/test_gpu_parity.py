@@ -426,3 +426,157 @@ def test_deferred_append_falls_back_when_it_cannot_ride():
     _check_step(w, s, op)
     _check_pool(w, s, op)
     s.close()
+
+
+# ------------------------------------------------------------------------- rotary embedding
+THETA = 10000.0
+
+
+def _check_rope_pool(w, s, op, n_events):
+    """Pool K rows after a rotating append: the oracle rotates in fp64 and rounds once; the
+    kernel rotates in fp32 (angle reduced in fp64) and rounds once.  Where the fp32 result sits
+    next to a rounding boundary the two may land on neighbouring values: at most 1 unit in the
+    last place apart (bf16), and only on a small fraction of the elements.  V rows: bit-exact."""
+    torch.cuda.synchronize()
+    k, v = s.pool_bits(0)
+    slots = w.event_slots(n_events)
+    rows = np.array([oracle.phys_row(op.g, int(w.ev_request[e]), int(slots[e])) for e in range(n_events)])
+    sample = rows[:: max(1, n_events // 600)]
+    n_bad = n_all = 0
+    for h in range(w.Hkv):
+        offs = np.array([oracle.elem_offset(op.g, int(p), h) for p in sample])
+        idx = (offs[:, None] + np.arange(w.D)[None, :]).ravel()
+        assert np.array_equal(v[idx], op.v[idx])
+        a, b = k[idx], op.k[idx]
+        av, bv = oracle.widen_pool(w.dtype, a), oracle.widen_pool(w.dtype, b)
+        # one unit in the last place of the oracle's value, plus the fp32 error of a plane whose two
+        # products cancel (absolute ~1e-7 of the plane's length, many ulps of a result near zero)
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(bv), 1e-30))) - (7 if w.dtype == "bf16" else 23))
+        assert np.all(np.abs(av - bv) <= ulp + 1e-6 * np.max(np.abs(bv))), "rotated K off by more than one ulp"
+        n_bad += int((av != bv).sum())
+        n_all += idx.size
+    assert w.dtype == "f32" or n_bad <= 0.01 * n_all, f"{n_bad} of {n_all} rotated K elements differ"
+    return n_bad, n_all
+
+
+def _check_rope_step(w, s, op, step, positions, flags=0, explicit=True):
+    qpos = w.q_positions(step)
+    out, lse, _ = s.decode(step, explicit=explicit, flags=flags | B.DECODE_ROPE_Q, position=qpos)
+    got = _out64(w, out)
+    q64 = oracle.rope(oracle.widen_pool(w.dtype, w.q(step)), qpos, THETA)
+    ref, ref_lse = oracle.attention_q64(op.g, op.k, op.v, w.dec_request, *w.lists(step), q64, w.scale)
+    res = check_close(got, ref, w.dtype, f"{w.name} rope step {step}")
+    assert np.max(np.abs(lse.cpu().numpy() - ref_lse)) <= (2e-2 if w.dtype == "bf16" else 1e-4)
+    return res
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_rope_at_append_and_on_queries_config3_loop(layout):
+    """K rotated by K1 on its way into the pool, Q rotated inside the attention kernel, position
+    ids with jumps (a fork starts at its parent's next id, the parent skips ahead)."""
+    w = W.config3(steps=6)
+    pos = w.event_positions()
+    s = _session(w, kv_layout=layout, rope_theta=THETA)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR))
+    s.append_events(w.n_prefill, flags=B.APPEND_ROPE, positions=pos)
+    op.append_events(w.n_prefill, positions=pos, theta=THETA)
+    for step in range(w.steps):
+        hi = w.n_events(step)
+        # every other step defers the copy: the rows are then turned inside the attention launch
+        s.append_events(hi, chunk=w.n, flags=B.APPEND_ROPE | (B.APPEND_DEFER if step % 2 else 0), positions=pos)
+        op.append_events(hi, positions=pos, theta=THETA)
+        res = _check_rope_step(w, s, op, step, pos, explicit=(step % 2 == 0))
+    print("rope cfg3 errors:", res, "pool mismatches:", _check_rope_pool(w, s, op, w.n_events(w.steps - 1)))
+    s.close()
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,flags", [("f32", 4, 1, 64, 0), ("f32", 8, 2, 128, 0),
+                                                   ("bf16", 8, 2, 64, 0), ("bf16", 16, 4, 128, B.DECODE_NO_MFMA),
+                                                   ("bf16", 64, 8, 128, 0)])
+def test_rope_on_the_other_paths(dtype, Hq, Hkv, D, flags):
+    """fp32 pools, D = 64 and the vector-ALU walker take Q from a rotated copy (k_rope_q); G = 8 on
+    the matrix-core path; random interleave, so many short ranges."""
+    w = W.single_request("rope", dtype, Hq, Hkv, D, D ** -0.5, 77, 300, [40, 3, 129, 77], "random")
+    pos = w.event_positions()
+    s = _session(w, rope_theta=THETA)
+    op = OraclePool(w)
+    s.append_events(w.n_prefill, flags=B.APPEND_ROPE, positions=pos)
+    op.append_events(w.n_prefill, positions=pos, theta=THETA)
+    _check_rope_pool(w, s, op, w.n_prefill)
+    _check_rope_step(w, s, op, 0, pos, flags=flags)
+    s.close()
+
+
+def test_rope_large_positions_and_another_theta():
+    """Position ids in the tens of thousands (angle = tens of thousands of radians at plane 0):
+    the reduction of the angle has to be done in fp64 for the rotated keys to stay within one
+    bf16 ulp of the oracle's."""
+    w = W.single_request("rope_far", "bf16", 8, 2, 128, 128 ** -0.5, 78, 200, [30, 30], "round_robin")
+    pos = w.event_positions() + 39000
+    s = _session(w, rope_theta=500000.0)
+    op = OraclePool(w)
+    s.append_events(w.n_prefill, flags=B.APPEND_ROPE, positions=pos)
+    op.append_events(w.n_prefill, positions=pos, theta=500000.0)
+    _check_rope_pool(w, s, op, w.n_prefill)
+    qpos = w.q_positions(0) + 39000
+    out, lse, _ = s.decode(0, flags=B.DECODE_ROPE_Q, position=qpos)
+    q64 = oracle.rope(oracle.widen_pool(w.dtype, w.q(0)), qpos, 500000.0)
+    ref, _ = oracle.attention_q64(op.g, op.k, op.v, w.dec_request, *w.lists(0), q64, w.scale)
+    check_close(_out64(w, out), ref, w.dtype, "rope far")
+    s.close()
+
+
+def test_rope_deferred_rows_are_turned_where_they_are_read_and_where_they_are_copied():
+    """PASTA_APPEND_DEFER | PASTA_APPEND_ROPE: the attention launch reads the step's unrotated rows
+    from k_new, turns them in its LDS tile, and turns them again on their way into the pool; a
+    deferred rotating append that cannot ride (a second append arrives first) is flushed by K1.
+    (a) no fork: the deferred row is the last row of the prefix; (b) explicit lists naming rows
+    that other streams appended in the deferred call, paged pool; (c) flush."""
+    from paper_2502_11517_amd.harness import to_device
+    w = W.single_request("nofork", "bf16", 8, 2, 128, 1.0, 5, 700, [1], "random", k_std=128 ** -0.5)
+    w.ev_stream[:] = 0
+    w.ev_parent[:] = -1
+    w.dec_stream[:] = 0
+    w.anc_slots = [[]]
+    pos = (np.arange(w.n_prefill) * 3 + 11).astype(np.int32)
+    s = _session(w, rope_theta=THETA)
+    op = OraclePool(w).append_events(w.n_prefill, positions=pos, theta=THETA)
+    s.append_events(w.n_prefill - 1, flags=B.APPEND_ROPE, positions=pos)
+    s.append_events(w.n_prefill, flags=B.APPEND_ROPE | B.APPEND_DEFER, positions=pos)
+    _check_rope_step(w, s, op, 0, pos)
+    _check_rope_pool(w, s, op, w.n_prefill)
+    s.close()
+    # (b)
+    w = W.single_request("cross", "bf16", 8, 2, 128, 1.0, 6, 300, [40, 50, 60], "random", k_std=128 ** -0.5)
+    n0 = w.n_prefill
+    w.page_tokens, w.pages_per_request = 16, -(-w.pool_tokens // 16)
+    w.n_phys_pages = w.pages_per_request + 5
+    w.page_table = np.random.default_rng(3).permutation(w.n_phys_pages)[:w.pages_per_request].astype(np.int32).reshape(1, -1)
+    pos = w.event_positions()
+    s = _session(w, rope_theta=THETA)
+    op = OraclePool(w).append_events(n0, positions=pos, theta=THETA)
+    s.append_events(n0 - 3, flags=B.APPEND_ROPE, positions=pos)
+    s.append_events(n0, flags=B.APPEND_ROPE | B.APPEND_DEFER, positions=pos)  # the last three rows are deferred
+    q = w.q(0)
+    qd = to_device(q, w.dtype, s.device)
+    out = torch.empty_like(qd)
+    lists = ([300, 300, 0], [0, 1, 2, 4], [n0 - 3, n0 - 5, 10, n0 - 2], [3, 5, 20, 2], [1, 1, 7, 1])
+    qpos = np.array([900, 17, 3], np.int32)
+    s.h.decode_step(0, w.dec_request, w.dec_stream, qd, out, lists=lists, flags=B.DECODE_ROPE_Q, position=qpos)
+    q64 = oracle.rope(oracle.widen_pool(w.dtype, q), qpos, THETA)
+    ref, _ = oracle.attention_q64(op.g, op.k, op.v, w.dec_request, *lists, q64, w.scale)
+    check_close(_out64(w, out), ref, w.dtype, "lists over deferred rotated rows")
+    _check_rope_pool(w, s, op, n0)
+    s.close()
+    # (c)
+    w = W.config3(steps=2, prefix=200, n_streams=3)
+    pos = w.event_positions()
+    s = _session(w, rope_theta=THETA)
+    op = OraclePool(w)
+    s.append_events(w.n_prefill, flags=B.APPEND_ROPE, positions=pos)
+    s.append_events(w.n_events(0), chunk=w.n, flags=B.APPEND_ROPE | B.APPEND_DEFER, positions=pos)
+    s.append_events(w.n_events(1), chunk=w.n, flags=B.APPEND_ROPE | B.APPEND_DEFER, positions=pos)  # flushes the first
+    op.append_events(w.n_events(1), positions=pos, theta=THETA)
+    _check_rope_step(w, s, op, 1, pos)
+    _check_rope_pool(w, s, op, w.n_events(1))
+    s.close()

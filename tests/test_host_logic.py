@@ -235,3 +235,35 @@ def test_destroy_and_stale_handle():
     lib = B.load_library()
     assert lib.pasta_attn_destroy(None) == B.OK
     h.destroy()
+
+
+def test_rope_flags_need_theta_and_positions():
+    """PASTA_APPEND_ROPE / PASTA_DECODE_ROPE_Q are E_INVAL without rope_theta, without position
+    ids, with a negative id, or together with RESERVE_ONLY; the workspace grows by the table and
+    the rotated-Q buffer when rope_theta is set."""
+    plain = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=4, pool_tokens=256)
+    roped = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=4, pool_tokens=256, rope_theta=10000.0)
+    assert B.query_workspace_bytes(roped) >= B.query_workspace_bytes(plain) + 64 * 8 + 4 * 8 * 128 * 2
+    bad = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=4, pool_tokens=256, rope_theta=-1.0)
+    with pytest.raises(B.PastaError) as e:
+        B.query_workspace_bytes(bad)
+    assert e.value.code == B.E_INVAL
+    for cfg, theta_ok in ((plain, False), (roped, True)):
+        h = B.PastaAttn(cfg, FAKE, FAKE, FAKE, B.query_workspace_bytes(cfg))
+        rid, sid = np.zeros(3, np.int32), np.zeros(3, np.int32)
+        # RESERVE_ONLY | ROPE is refused in any case
+        with pytest.raises(B.PastaError) as e:
+            h.append_kv(0, rid, sid, None, None, position=[0, 1, 2], flags=B.APPEND_RESERVE_ONLY | B.APPEND_ROPE)
+        assert e.value.code == B.E_INVAL
+        for position in (None, [0, 1, -2]) + (() if theta_ok else ([0, 1, 2],)):
+            with pytest.raises(B.PastaError) as e:
+                h.append_kv(0, rid, sid, FAKE, FAKE, position=position, flags=B.APPEND_ROPE)
+            assert e.value.code == B.E_INVAL
+        h.append_kv(0, rid, sid, None, None, flags=B.APPEND_RESERVE_ONLY)
+        for position in (None, [-1]) + (() if theta_ok else ([2],)):
+            with pytest.raises(B.PastaError) as e:
+                h.decode_step(0, [0], [0], FAKE, FAKE, position=position, flags=B.DECODE_ROPE_Q | B.DECODE_PLAN_ONLY)
+            assert e.value.code == B.E_INVAL
+        if theta_ok:
+            h.decode_step(0, [0], [0], FAKE, FAKE, position=[2], flags=B.DECODE_ROPE_Q | B.DECODE_PLAN_ONLY)
+        h.destroy()

@@ -25,10 +25,15 @@ class OraclePool:
         self.tail = np.zeros(w.max_requests, np.int64)
         self.n_done = 0
 
-    def append_events(self, hi: int, chunk: int = 8192):
+    def append_events(self, hi: int, chunk: int = 8192, positions=None, theta: float = 0.0):
+        """positions / theta: rotate the K rows by their position ids before they enter the pool
+        (fp64 rotation, one rounding to the pool dtype)."""
         while self.n_done < hi:
             b = min(hi, self.n_done + chunk)
             k, v = self.w.kv_rows(self.n_done, b)
+            if positions is not None:
+                k = oracle.round_pool(self.w.dtype, oracle.rope(oracle.widen_pool(self.w.dtype, k),
+                                                                positions[self.n_done:b], theta))
             rc, slots = oracle.append(self.g, self.k, self.v, self.w.ev_request[self.n_done:b], k, v,
                                       self.tail)
             assert rc == 0
