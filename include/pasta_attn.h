@@ -245,6 +245,43 @@ typedef struct {
  * is asynchronous on cfg.hip_stream; the call returns without synchronising. */
 int32_t pasta_attn_decode_step(pasta_attn *h, const pasta_decode_args *a);
 
+/* Synchronisation (Section 3, Efficiency: a thread that has decoded its sync
+ * token waits for its forks; when they are complete the sync token enters the
+ * pool and the thread resumes "conditioning on both forks' generations";
+ * Figure 2b: the joined threads' last tokens get edges into the sync token).
+ * From this call on, stream `stream_id` of `request_id` also sees everything
+ * that the streams join_stream[0 .. n_join) see at this moment (their own rows,
+ * what they inherited, what they joined earlier).  Host bookkeeping of the
+ * maintained lists only: no KV row moves, nothing is enqueued; the caller then
+ * appends the sync token's row to `stream_id` as any other row.
+ * PASTA_SYNC_RETIRE closes the joined streams afterwards: their ids may be
+ * opened again by a later append, their rows stay where they are.  With
+ * stream_id == -1 and PASTA_SYNC_RETIRE the listed streams are only closed.
+ * Errors: E_INVAL (ids out of range, stream_id among join_stream, duplicates,
+ * stream_id == -1 without RETIRE), E_STATE (a stream is not open), E_CAPACITY
+ * (max_ranges exceeded), E_NOMEM.  A failing call changes no state.          */
+enum { PASTA_SYNC_RETIRE = 1u };
+
+typedef struct {
+  uint32_t struct_size;
+  uint32_t flags;               /* PASTA_SYNC_* */
+  int32_t request_id;
+  int32_t stream_id;            /* the stream that waited, or -1 (retire only) */
+  int32_t n_join;               /* >= 1 */
+  const int32_t *join_stream;   /* HOST [n_join], distinct, open streams */
+} pasta_sync_args;
+
+int32_t pasta_attn_sync(pasta_attn *h, const pasta_sync_args *a);
+
+/* Reads the maintained visibility list of one open stream (HOST outputs): what
+ * decode_step would use for it in maintained mode.  *prefix_len and *n_ranges
+ * are always written; at most `cap` descriptors go to start / count / stride
+ * (which may be NULL when cap == 0).
+ * Errors: E_INVAL, E_STATE (stream not open).                                */
+int32_t pasta_attn_stream_list(pasta_attn *h, int32_t request_id, int32_t stream_id, int32_t *prefix_len,
+                               int32_t *n_ranges, int32_t cap, int32_t *start, int32_t *count,
+                               int32_t *stride);
+
 /* Frees host state only; does not synchronise (the caller synchronises before
  * freeing pool / workspace).  NULL is a no-op.                               */
 int32_t pasta_attn_destroy(pasta_attn *h);

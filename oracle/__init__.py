@@ -20,5 +20,6 @@ from .pasta_oracle import (  # noqa: F401
     round_pool,
     rows_per_layer,
     visible_dense,
+    visible_events,
     widen_pool,
 )

@@ -368,6 +368,71 @@ int oracle_visible_dense(int64_t n_slots, const int32_t *slot_stream, int32_t n_
   return 0;
 }
 
+/* ---------- A0 with synchronisation, as the paper draws it (Figure 2b): "each
+ * directed edge connects a token to the very next token that may attend to it;
+ * a token can attend to any ancestor token reachable by following these edges
+ * backward".  Edges into pool slot t, from the history alone:
+ *   - the previous token of t's own thread;
+ *   - if t is the first token of a forked thread: the spawning thread's latest
+ *     token at that moment (ev_parent[t] >= 0 on that slot);
+ *   - if t is a token with which its thread synchronises (the sync token that
+ *     enters the pool once the awaited forks are complete): the latest token of
+ *     every joined thread (join_streams[join_offsets[t] .. join_offsets[t+1])).
+ * A thread id may be used again after its thread has ended: the slot that
+ * carries ev_parent >= 0 (or the very first use) starts a NEW thread.
+ * ev_new[t] = 1 marks such first tokens.  mask_out[u] = 1 iff slot u is q_slot
+ * or reachable backwards from q_slot.  One request. ---------- */
+int oracle_visible_events(int64_t n_slots, const int32_t *ev_stream, const int32_t *ev_parent,
+                          const uint8_t *ev_new, const int32_t *join_offsets,
+                          const int32_t *join_streams, int32_t n_stream_ids, int64_t q_slot,
+                          uint8_t *mask_out) {
+  if (q_slot < 0 || q_slot >= n_slots) return -1;
+  int64_t *last_of = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_stream_ids > 0 ? n_stream_ids : 1));
+  int64_t *pred_off = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_slots + 1));
+  int64_t n_join_total = join_offsets ? join_offsets[n_slots] : 0;
+  int64_t *pred = (int64_t *)malloc(sizeof(int64_t) * (size_t)(2 * n_slots + n_join_total + 1));
+  int64_t *stack = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_slots + 1));
+  if (!last_of || !pred_off || !pred || !stack) { free(last_of); free(pred_off); free(pred); free(stack); return -3; }
+  for (int32_t s = 0; s < n_stream_ids; ++s) last_of[s] = -1;
+  int64_t np = 0;
+  int rc = 0;
+  for (int64_t t = 0; t < n_slots && rc == 0; ++t) {
+    int32_t s = ev_stream[t];
+    pred_off[t] = np;
+    if (s < 0 || s >= n_stream_ids) { rc = -1; break; }
+    if (ev_new[t]) {
+      if (ev_parent[t] >= 0) {
+        if (ev_parent[t] >= n_stream_ids || last_of[ev_parent[t]] < 0) { rc = -1; break; }
+        pred[np++] = last_of[ev_parent[t]];
+      }
+    } else {
+      if (last_of[s] < 0) { rc = -1; break; }
+      pred[np++] = last_of[s];
+    }
+    if (join_offsets)
+      for (int32_t k = join_offsets[t]; k < join_offsets[t + 1]; ++k) {
+        int32_t j = join_streams[k];
+        if (j < 0 || j >= n_stream_ids || last_of[j] < 0) { rc = -1; break; }
+        pred[np++] = last_of[j];
+      }
+    last_of[s] = t;
+  }
+  if (rc == 0) {
+    pred_off[n_slots] = np;
+    memset(mask_out, 0, (size_t)n_slots);
+    int64_t top = 0;
+    stack[top++] = q_slot;
+    mask_out[q_slot] = 1;
+    while (top > 0) {
+      int64_t t = stack[--top];
+      for (int64_t k = pred_off[t]; k < pred_off[t + 1]; ++k)
+        if (!mask_out[pred[k]]) { mask_out[pred[k]] = 1; stack[top++] = pred[k]; }
+    }
+  }
+  free(last_of); free(pred_off); free(pred); free(stack);
+  return rc;
+}
+
 /* ---------- brute force: attention of one stream over ALL slots [0, n_slots)
  * of its request with masked logits set to -inf (the paper's dense-mask form).
  * q_row: [Hq][D]; out: [Hq][D] fp64; lse: [Hq] or NULL. ---------- */

@@ -60,6 +60,8 @@ def _load():
         L.oracle_rope.argtypes = [P, C.c_int64, C.c_int32, C.c_int32, P, C.c_double, P]
         L.oracle_round_pool.restype = None
         L.oracle_round_pool.argtypes = [P, C.c_int64, C.c_int32, P]
+        L.oracle_visible_events.restype = C.c_int
+        L.oracle_visible_events.argtypes = [C.c_int64, P, P, P, P, P, C.c_int32, C.c_int64, P]
         L.oracle_partial.restype = C.c_int
         L.oracle_partial.argtypes = [P, P, P, C.c_int64, P, P, C.c_int32, C.c_double, P, P, P]
         L.oracle_merge.restype = C.c_int
@@ -252,6 +254,27 @@ def visible_dense(slot_stream, stream_parent, stream_spawn_tail, query_stream):
                                       _p(stream_parent), _p(spawn), query_stream, _p(mask))
     if rc != 0:
         raise ValueError("bad fork tree")
+    return mask
+
+
+def visible_events(ev_stream, ev_parent, ev_new, joins, q_slot):
+    """Figure 2b's reachability with synchronisation: joins[t] = thread ids whose latest tokens
+    get an edge into slot t (a sync token); ev_new[t] = 1 on a thread's first token.
+    Returns a 0/1 mask over the slots (q_slot itself included)."""
+    ev_stream, ev_parent = _i32(ev_stream), _i32(ev_parent)
+    ev_new = np.ascontiguousarray(ev_new, dtype=np.uint8)
+    n = ev_stream.shape[0]
+    offs = np.zeros(n + 1, np.int32)
+    flat = []
+    for t in range(n):
+        flat += list(joins[t]) if joins is not None and t in joins else []
+        offs[t + 1] = len(flat)
+    flat = _i32(flat if flat else [0])
+    mask = np.zeros(n, np.uint8)
+    rc = _load().oracle_visible_events(n, _p(ev_stream), _p(ev_parent), _p(ev_new), _p(offs), _p(flat),
+                                       int(ev_stream.max()) + 1, int(q_slot), _p(mask))
+    if rc != 0:
+        raise ValueError(f"oracle_visible_events failed: {rc}")
     return mask
 
 

@@ -21,6 +21,7 @@ F32, BF16 = 0, 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
 DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q = 1, 2, 4
 APPEND_RESERVE_ONLY, APPEND_DEFER, APPEND_ROPE = 1, 2, 4
+SYNC_RETIRE = 1
 _ERR = {E_INVAL: "E_INVAL", E_CAPACITY: "E_CAPACITY", E_NOMEM: "E_NOMEM", E_DEVICE: "E_DEVICE",
         E_STATE: "E_STATE"}
 
@@ -71,6 +72,13 @@ class AppendArgs(C.Structure):
     ]
 
 
+class SyncArgs(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("request_id", C.c_int32), ("stream_id", C.c_int32),
+        ("n_join", C.c_int32), ("join_stream", C.c_void_p),
+    ]
+
+
 class DecodeArgs(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("layer", C.c_int32), ("n_streams", C.c_int32),
@@ -99,6 +107,11 @@ def load_library():
         L.pasta_attn_append_kv.argtypes = [C.c_void_p, C.POINTER(AppendArgs)]
         L.pasta_attn_decode_step.restype = C.c_int32
         L.pasta_attn_decode_step.argtypes = [C.c_void_p, C.POINTER(DecodeArgs)]
+        L.pasta_attn_sync.restype = C.c_int32
+        L.pasta_attn_sync.argtypes = [C.c_void_p, C.POINTER(SyncArgs)]
+        L.pasta_attn_stream_list.restype = C.c_int32
+        L.pasta_attn_stream_list.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
         L.pasta_attn_destroy.restype = C.c_int32
         L.pasta_attn_destroy.argtypes = [C.c_void_p]
         _lib = L
@@ -221,6 +234,29 @@ class PastaAttn:
         def call(_keep=(rid, sid, pos, pl, offs, st, ct, sd, a, q, out, out_lse)):
             return fn(h, ref)
         return call
+
+    def sync(self, request_id, stream_id, join_streams, retire=False):
+        """stream_id (or -1: retire only) from now on also sees what join_streams see."""
+        js = _i32(join_streams)
+        a = SyncArgs(C.sizeof(SyncArgs), SYNC_RETIRE if retire else 0, request_id, stream_id, int(js.shape[0]), _hp(js))
+        rc = self._lib.pasta_attn_sync(self._h, C.byref(a))
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_sync")
+
+    def stream_list(self, request_id, stream_id):
+        """(prefix_len, start[], count[], stride[]) of the maintained list of an open stream."""
+        pl, nr = C.c_int32(), C.c_int32()
+        rc = self._lib.pasta_attn_stream_list(self._h, request_id, stream_id, C.addressof(pl), C.addressof(nr), 0,
+                                              None, None, None)
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_stream_list")
+        n = max(nr.value, 1)
+        st, ct, sd = np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.int32)
+        rc = self._lib.pasta_attn_stream_list(self._h, request_id, stream_id, C.addressof(pl), C.addressof(nr), n,
+                                              _hp(st), _hp(ct), _hp(sd))
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_stream_list")
+        return pl.value, st[:nr.value], ct[:nr.value], sd[:nr.value]
 
     def destroy(self):
         if self._h is not None:

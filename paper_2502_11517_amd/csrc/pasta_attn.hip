@@ -529,6 +529,93 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
   return PASTA_OK;
 }
 
+// =============================================================================== sync
+// Union of visible sets, rebuilt slot by slot in ascending order so that the result is in the
+// same canonical form as a list grown by appends (contiguous head in prefix_len, then strided
+// descriptors).  Host work proportional to the number of visible slots; a sync is rare.
+extern "C" int32_t pasta_attn_sync(pasta_attn* h, const pasta_sync_args* a) {
+  if (!h || h->magic != kMagic) return PASTA_E_STATE;
+  if (!a || a->struct_size != sizeof(pasta_sync_args)) return PASTA_E_INVAL;
+  const pasta_attn_config& c = h->cfg;
+  const bool retire = a->flags & PASTA_SYNC_RETIRE;
+  if (a->request_id < 0 || a->request_id >= c.max_requests) return PASTA_E_INVAL;
+  if (a->n_join < 1 || !a->join_stream) return PASTA_E_INVAL;
+  if (a->stream_id < -1 || a->stream_id >= c.max_streams || (a->stream_id == -1 && !retire)) return PASTA_E_INVAL;
+  for (int i = 0; i < a->n_join; ++i) {
+    const int j = a->join_stream[i];
+    if (j < 0 || j >= c.max_streams || j == a->stream_id) return PASTA_E_INVAL;
+    for (int k = 0; k < i; ++k)
+      if (a->join_stream[k] == j) return PASTA_E_INVAL;
+    if (!sstate(h, a->request_id, j).open) return PASTA_E_STATE;
+  }
+  try {
+    if (a->stream_id >= 0) {
+      StreamState& dst = sstate(h, a->request_id, a->stream_id);
+      if (!dst.open) return PASTA_E_STATE;
+      // k-way merge of the lists' slots (each list ascending), duplicates dropped
+      struct Cursor { const StreamState* s; int64_t next; size_t ri; int32_t k; };  // next < prefix_len: in the head
+      std::vector<Cursor> cur;
+      cur.push_back({&dst, 0, 0, 0});
+      for (int i = 0; i < a->n_join; ++i) cur.push_back({&sstate(h, a->request_id, a->join_stream[i]), 0, 0, 0});
+      auto peek = [](const Cursor& q) -> int64_t {
+        if (q.next < q.s->prefix_len) return q.next;
+        if (q.ri < q.s->ranges.size()) return (int64_t)q.s->ranges[q.ri].start + (int64_t)q.k * q.s->ranges[q.ri].stride;
+        return INT64_MAX;
+      };
+      auto advance = [](Cursor& q) {
+        if (q.next < q.s->prefix_len) { q.next++; return; }
+        if (++q.k >= q.s->ranges[q.ri].count) { q.k = 0; q.ri++; }
+      };
+      // the common head [0, min prefix_len) needs no merging
+      int64_t head = INT64_MAX;
+      for (auto& q : cur) head = std::min<int64_t>(head, q.s->prefix_len);
+      StreamState merged;
+      merged.open = true;
+      merged.prefix_len = (int32_t)head;
+      for (auto& q : cur) q.next = head;
+      for (;;) {
+        int64_t lo = INT64_MAX;
+        for (auto& q : cur) lo = std::min(lo, peek(q));
+        if (lo == INT64_MAX) break;
+        add_slot(merged, (int32_t)lo);
+        for (auto& q : cur)
+          if (peek(q) == lo) advance(q);
+        if ((int64_t)merged.ranges.size() > c.max_ranges) return PASTA_E_CAPACITY;
+      }
+      dst = std::move(merged);
+    }
+    if (retire)
+      for (int i = 0; i < a->n_join; ++i) {
+        StreamState& js = sstate(h, a->request_id, a->join_stream[i]);
+        js.open = false;
+        js.prefix_len = 0;
+        js.ranges.clear();
+      }
+  } catch (const std::bad_alloc&) {
+    return PASTA_E_NOMEM;
+  }
+  return PASTA_OK;
+}
+
+extern "C" int32_t pasta_attn_stream_list(pasta_attn* h, int32_t request_id, int32_t stream_id, int32_t* prefix_len,
+                                          int32_t* n_ranges, int32_t cap, int32_t* start, int32_t* count,
+                                          int32_t* stride) {
+  if (!h || h->magic != kMagic) return PASTA_E_STATE;
+  const pasta_attn_config& c = h->cfg;
+  if (request_id < 0 || request_id >= c.max_requests || stream_id < 0 || stream_id >= c.max_streams) return PASTA_E_INVAL;
+  if (!prefix_len || !n_ranges || cap < 0 || (cap > 0 && (!start || !count || !stride))) return PASTA_E_INVAL;
+  const StreamState& s = sstate(h, request_id, stream_id);
+  if (!s.open) return PASTA_E_STATE;
+  *prefix_len = s.prefix_len;
+  *n_ranges = (int32_t)s.ranges.size();
+  for (int32_t k = 0; k < cap && k < (int32_t)s.ranges.size(); ++k) {
+    start[k] = s.ranges[k].start;
+    count[k] = s.ranges[k].count;
+    stride[k] = s.ranges[k].stride;
+  }
+  return PASTA_OK;
+}
+
 // =============================================================================== decode
 namespace {
 

@@ -397,3 +397,46 @@ def random_fork_history(seed: int, n_slots: int = 48, max_streams: int = 6, p_fo
             if len(ev_s) < n_slots:
                 ev_s.append(s), ev_p.append(-1)
     return np.asarray(ev_s, np.int32), np.asarray(ev_p, np.int32)
+
+
+def random_fork_sync_history(seed: int, n_slots: int = 80, max_ids: int = 5, p_fork: float = 0.2,
+                             p_sync: float = 0.12):
+    """A random history for one request with forks, synchronisations and reuse of thread ids:
+    every live thread appends one token per lock-step round; now and then a live thread spawns a
+    child (nested forks included); now and then a thread whose children have no live children of
+    their own waits for them: the children end, the thread's next token is its sync token, and
+    the children's ids become free for later forks.
+    Returns a list of events in pool order, each a dict
+      {"stream": id, "parent": id or -1, "new": first token of a thread, "join": [ids joined by this token]}."""
+    rng = np.random.default_rng(seed)
+    live, children, free_ids = [ROOT], {ROOT: []}, list(range(1, max_ids))
+    events = [dict(stream=ROOT, parent=-1, new=True, join=[])]
+    pending_join: dict = {}
+    while len(events) < n_slots:
+        r = rng.random()
+        if free_ids and r < p_fork:
+            par = int(rng.choice(live))
+            cid = free_ids.pop(0)
+            events.append(dict(stream=cid, parent=par, new=True, join=[]))
+            live.append(cid)
+            children[par].append(cid)
+            children[cid] = []
+            continue
+        if r > 1.0 - p_sync:
+            cands = [x for x in live if children[x] and x not in pending_join
+                     and all(not children[c] and c not in pending_join for c in children[x])]
+            if cands:
+                x = int(rng.choice(cands))
+                pending_join[x] = list(children[x])
+                for c in children[x]:
+                    live.remove(c)
+                children[x] = []
+        for sid in list(live):  # one lock-step round
+            if len(events) >= n_slots:
+                break
+            j = pending_join.pop(sid, [])
+            events.append(dict(stream=sid, parent=-1, new=False, join=j))
+            for c in j:  # the joined ids are free again once the sync token is in the pool
+                del children[c]
+                free_ids.append(c)
+    return events

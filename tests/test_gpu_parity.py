@@ -580,3 +580,54 @@ def test_rope_deferred_rows_are_turned_where_they_are_read_and_where_they_are_co
     _check_rope_step(w, s, op, 1, pos)
     _check_rope_pool(w, s, op, w.n_events(1))
     s.close()
+
+
+# ------------------------------------------------------------------------- synchronisation
+@pytest.mark.parametrize("seed", range(3))
+def test_maintained_lists_through_syncs_equal_reachability_and_dense_mask_attention(seed):
+    """Forks, nested forks, synchronisations (pasta_attn_sync) and reuse of stream ids: at a few
+    moments of the history every live stream decodes in maintained mode; its gather map must be
+    exactly the set reachable from its newest token in Figure 2b's graph, and its output the
+    brute-force attention over the whole pool with that set as mask.  No KV row is moved."""
+    events = W.random_fork_sync_history(700 + seed, n_slots=420, max_ids=6, p_fork=0.08, p_sync=0.15)
+    n = len(events)
+    ev_s = np.array([e["stream"] for e in events], np.int32)
+    ev_p = np.array([e["parent"] for e in events], np.int32)
+    ev_n = np.array([1 if e["new"] else 0 for e in events], np.uint8)
+    joins = {t: e["join"] for t, e in enumerate(events) if e["join"]}
+    assert len(joins) >= 2
+    w = W.Workload(name="syncs", dtype="bf16", Hq=8, Hkv=2, D=128, scale=1.0, seed=950 + seed, max_requests=1,
+                   pool_tokens=512, max_streams=6, k_std=128 ** -0.5)
+    w.ev_request = np.zeros(n, np.int32)
+    w.ev_stream, w.ev_parent, w.n_prefill = ev_s, np.where(ev_n == 1, ev_p, -1).astype(np.int32), n
+    s = _session(w, max_ranges=4096)
+    op = OraclePool(w).append_events(n)
+    from paper_2502_11517_amd.harness import to_device
+    checks = sorted(set([min(joins) + 1, max(joins) + 1, n // 2, n]))
+    done = 0
+    for stop in checks:
+        for t in range(done, stop):       # replay the history: a sync call before a sync token's row
+            if events[t]["join"]:
+                s.h.sync(0, int(ev_s[t]), events[t]["join"], retire=True)
+            s.append_events(t + 1, chunk=1)
+        done = stop
+        live = sorted({int(x) for x in ev_s[:stop]} - {j for t, js in joins.items() if t < stop for j in js
+                                                       if not any(ev_s[u] == j and ev_n[u] for u in range(t, stop))})
+        rid = np.zeros(len(live), np.int32)
+        rng = np.random.default_rng([seed, stop])
+        q = W.f32_to_bf16_bits(rng.standard_normal((len(live), w.Hq, w.D)).astype(np.float32))
+        qd = to_device(q, w.dtype, s.device)
+        out = torch.empty_like(qd)
+        goffs = np.zeros(len(live) + 1, np.int64)
+        s.h.decode_step(0, rid, live, qd, out, flags=B.DECODE_PLAN_ONLY, dbg_gather_offsets=goffs)
+        grows = torch.full((int(goffs[-1]),), -1, dtype=torch.int32, device=s.device)
+        s.h.decode_step(0, rid, live, qd, out, dbg_gather_offsets=goffs, dbg_gather_rows=grows)
+        got = _out64(w, out)
+        grows = grows.cpu().numpy()
+        for i, sid in enumerate(live):
+            last = int(np.nonzero(ev_s[:stop] == sid)[0][-1])
+            mask = oracle.visible_events(ev_s[:stop], ev_p[:stop], ev_n[:stop], {k: v for k, v in joins.items() if k < stop}, last)
+            assert np.array_equal(grows[goffs[i]:goffs[i + 1]], np.nonzero(mask)[0]), f"stop {stop} stream {sid}"
+            ref, _ = oracle.attention_dense(op.g, op.k, op.v, 0, mask, q[i], w.scale)
+            check_close(got[i], ref, w.dtype, f"stop {stop} stream {sid}")
+    s.close()

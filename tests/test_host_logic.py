@@ -52,7 +52,8 @@ def _plan(h, req, sid, lists=None, flags=0):
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "pasta_attn.h")).read()
     declared = set(re.findall(r"\bint32_t\s+(pasta_attn_\w+)\s*\(", hdr))
-    assert declared == {"pasta_attn_create", "pasta_attn_append_kv", "pasta_attn_decode_step", "pasta_attn_destroy"}
+    assert declared == {"pasta_attn_create", "pasta_attn_append_kv", "pasta_attn_decode_step", "pasta_attn_destroy",
+                        "pasta_attn_sync", "pasta_attn_stream_list"}
     syms = subprocess.run(["nm", "-D", "--defined-only", B.library_path()], capture_output=True, text=True).stdout
     exported = {l.split()[-1] for l in syms.splitlines() if " T " in l}
     assert declared <= exported
@@ -267,3 +268,69 @@ def test_rope_flags_need_theta_and_positions():
         if theta_ok:
             h.decode_step(0, [0], [0], FAKE, FAKE, position=[2], flags=B.DECODE_ROPE_Q | B.DECODE_PLAN_ONLY)
         h.destroy()
+
+
+def _expand(pl, st, ct, sd):
+    out = list(range(pl))
+    for a, c, d in zip(st.tolist(), ct.tolist(), sd.tolist()):
+        out += [a + j * d for j in range(c)]
+    return out
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_maintained_lists_through_forks_syncs_and_id_reuse_equal_reachability(seed):
+    """Drive the library's bookkeeping (no device work) through a random history with nested
+    forks, synchronisations and reuse of stream ids; after every event the maintained list of
+    the stream that just appended must name exactly the slots reachable from its newest token
+    in Figure 2b's graph (the oracle's visible_events)."""
+    import oracle
+    events = W.random_fork_sync_history(100 + seed, n_slots=120, max_ids=5)
+    cfg = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=5, pool_tokens=256, max_ranges=4096)
+    h = B.PastaAttn(cfg, FAKE, FAKE, FAKE, B.query_workspace_bytes(cfg))
+    ev_s = np.array([e["stream"] for e in events], np.int32)
+    ev_p = np.array([e["parent"] for e in events], np.int32)
+    ev_n = np.array([1 if e["new"] else 0 for e in events], np.uint8)
+    joins = {t: e["join"] for t, e in enumerate(events) if e["join"]}
+    assert joins
+    for t, e in enumerate(events):
+        if e["join"]:
+            h.sync(0, e["stream"], e["join"], retire=True)
+        slot = h.append_kv(0, [0], [e["stream"]], None, None, parent_stream=[e["parent"] if e["new"] else -1],
+                           want_slots=True, flags=B.APPEND_RESERVE_ONLY)
+        assert slot[0] == t
+        got = _expand(*h.stream_list(0, e["stream"]))
+        want = np.nonzero(oracle.visible_events(ev_s[: t + 1], ev_p[: t + 1], ev_n[: t + 1],
+                                                {k: v for k, v in joins.items() if k <= t}, t))[0].tolist()
+        assert got == want, f"event {t}: {e}"
+    h.destroy()
+
+
+def test_sync_argument_checks_and_retire_only():
+    cfg = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=4, pool_tokens=64)
+    h = B.PastaAttn(cfg, FAKE, FAKE, FAKE, B.query_workspace_bytes(cfg))
+    app = lambda s, par=-1: h.append_kv(0, [0], [s], None, None, parent_stream=[par], flags=B.APPEND_RESERVE_ONLY)
+    for _ in range(3):
+        app(0)
+    app(1, 0); app(2, 0); app(1); app(2); app(0)          # slots 3..7
+    for args, code in (((0, 0, [0]), B.E_INVAL), ((0, 0, [1, 1]), B.E_INVAL), ((0, 0, [3]), B.E_STATE),
+                       ((0, 3, [1]), B.E_STATE), ((0, 0, [7]), B.E_INVAL), ((1, 0, [1]), B.E_INVAL),
+                       ((0, 0, []), B.E_INVAL)):
+        with pytest.raises(B.PastaError) as e:
+            h.sync(*args)
+        assert e.value.code == code, args
+    with pytest.raises(B.PastaError) as e:
+        h.sync(0, -1, [1])                                  # -1 needs RETIRE
+    assert e.value.code == B.E_INVAL
+    assert _expand(*h.stream_list(0, 0)) == [0, 1, 2, 7]
+    h.sync(0, 0, [1])                                       # join without retiring: stream 1 stays open
+    assert _expand(*h.stream_list(0, 0)) == [0, 1, 2, 3, 5, 7]
+    assert _expand(*h.stream_list(0, 1)) == [0, 1, 2, 3, 5]
+    h.sync(0, 0, [2], retire=True)
+    assert h.stream_list(0, 0)[0] == 8 and len(h.stream_list(0, 0)[1]) == 0   # everything: one contiguous head
+    with pytest.raises(B.PastaError) as e:
+        h.stream_list(0, 2)
+    assert e.value.code == B.E_STATE
+    h.sync(0, -1, [1], retire=True)                         # retire only
+    app(1, 0)                                               # the id opens again, as a fork of stream 0 now
+    assert _expand(*h.stream_list(0, 1)) == list(range(9))
+    h.destroy()

@@ -541,3 +541,85 @@ def test_attention_with_rotated_queries_and_keys_sees_relative_positions_only():
     o32, l32 = oracle.attention(g, kp, vp, [0], [N], [0, 0], [], [], [], q, 0.25)
     o64, l64 = oracle.attention_q64(g, kp, vp, [0], [N], [0, 0], [], [], [], q.astype(np.float64), 0.25)
     assert np.array_equal(o32, o64) and np.array_equal(l32, l64)
+
+
+# ------------------------------------------------------------------ visibility with synchronisation
+def _reach_by_bfs(events, q_slot):
+    """Independent statement of Figure 2b with sync edges, in plain Python: predecessor sets
+    built while walking the history, then a breadth-first search backwards."""
+    last, preds = {}, []
+    for t, e in enumerate(events):
+        ps = set()
+        if e["new"]:
+            if e["parent"] >= 0:
+                ps.add(last[e["parent"]])
+        else:
+            ps.add(last[e["stream"]])
+        for j in e["join"]:
+            ps.add(last[j])
+        preds.append(ps)
+        last[e["stream"]] = t
+    seen, todo = {q_slot}, [q_slot]
+    while todo:
+        for u in preds[todo.pop()]:
+            if u not in seen:
+                seen.add(u)
+                todo.append(u)
+    return sorted(seen)
+
+
+def _events_arrays(events):
+    ev_s = np.array([e["stream"] for e in events], np.int32)
+    ev_p = np.array([e["parent"] for e in events], np.int32)
+    ev_n = np.array([1 if e["new"] else 0 for e in events], np.uint8)
+    joins = {t: e["join"] for t, e in enumerate(events) if e["join"]}
+    return ev_s, ev_p, ev_n, joins
+
+
+def test_paper_worked_example_after_sync():
+    fx = json.load(open(os.path.join(HERE, "golden", "paper_sec3_sync.json")))
+    joins = {int(k): v for k, v in fx["join"].items()}
+    for f in fx["facts"]:
+        mask = oracle.visible_events(fx["ev_stream"], fx["ev_parent"], fx["ev_new"], joins, f["query_slot"])
+        if f.get("sees_all_slots_up_to_itself"):
+            assert mask[: f["query_slot"] + 1].all()
+        else:
+            assert all(mask[t] for t in f["must_see"]) and not any(mask[t] for t in f["must_not_see"])
+    # before the sync token is in the pool the main thread sees neither fork (the first fixture's fact)
+    main_before = oracle.visible_events(fx["ev_stream"], fx["ev_parent"], fx["ev_new"], joins, 24)
+    assert np.nonzero(main_before)[0].tolist() == list(range(22)) + [24]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_visible_events_equals_bfs_on_random_fork_sync_histories(seed):
+    events = W.random_fork_sync_history(seed, n_slots=90, max_ids=5)
+    ev_s, ev_p, ev_n, joins = _events_arrays(events)
+    assert joins, "the generator should produce at least one synchronisation at this length"
+    for q in range(0, len(events), 3):
+        mask = oracle.visible_events(ev_s, ev_p, ev_n, joins, q)
+        assert np.nonzero(mask)[0].tolist() == _reach_by_bfs(events, q)
+    # a joined thread's tokens are visible after the sync token and not before
+    t_sync = min(joins)
+    child = joins[t_sync][0]
+    child_tok = int(np.nonzero(ev_s[:t_sync] == child)[0][-1])
+    owner_before = int(np.nonzero(ev_s[:t_sync] == ev_s[t_sync])[0][-1])
+    assert oracle.visible_events(ev_s, ev_p, ev_n, joins, t_sync)[child_tok] == 1
+    assert oracle.visible_events(ev_s, ev_p, ev_n, joins, owner_before)[child_tok] == 0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_visible_events_without_syncs_is_the_ancestor_rule(seed):
+    """No synchronisation: reachability reduces to the ancestor rule of visible_dense."""
+    ev_s, ev_p = W.random_fork_history(seed, n_slots=60, max_streams=7)
+    n_streams = int(ev_s.max()) + 1
+    parent, spawn, ev_n = np.full(n_streams, -1, np.int32), np.zeros(n_streams, np.int64), np.zeros(len(ev_s), np.uint8)
+    seen = set()
+    for t, (s, p) in enumerate(zip(ev_s.tolist(), ev_p.tolist())):
+        if s not in seen:
+            seen.add(s)
+            parent[s], spawn[s], ev_n[t] = p, t, 1
+    for s in range(n_streams):
+        last = int(np.nonzero(ev_s == s)[0][-1])
+        dense = oracle.visible_dense(ev_s, parent, spawn, s)
+        reach = oracle.visible_events(ev_s, ev_p, ev_n, None, last)
+        assert np.array_equal(reach[: last + 1], dense[: last + 1]) and not reach[last + 1:].any()
