@@ -282,6 +282,63 @@ int32_t pasta_attn_stream_list(pasta_attn *h, int32_t request_id, int32_t stream
                                int32_t *n_ranges, int32_t cap, int32_t *start, int32_t *count,
                                int32_t *stride);
 
+/* Trace replay (Section 3, "Interpreter" and "Efficiency"; Figure 2): runs a whole
+ * response through append_kv / sync / decode_step the way the interpreter would,
+ * from a SYNTHETIC trace of what the main thread emits.  One forward pass feeds one
+ * token of every active thread:
+ *   TEXT a          a ordinary tokens of the main thread, one per pass.
+ *   PROMISE a, b    a promise token; a = the block length the tag predicts (a
+ *                   multiple of ten in the paper), b = content tokens the forked
+ *                   thread really decodes.  The same pass carries the
+ *                   interpreter-inserted <async> token as the fork's first row;
+ *                   the fork then feeds its b content tokens and its </async>
+ *                   token, one per pass, and ends.
+ *   SYNC            the sync token is held back while any spawned thread is alive;
+ *                   then the threads are joined (ids retired), the token is fed
+ *                   and the main thread goes on.
+ * Rows of a pass enter the pool in the order main thread, fork born in this pass,
+ * older forks by age.  Forks take the lowest free stream id >= 1; the prompt must be
+ * in the pool already as stream 0 of the request.  Position ids: the main thread
+ * counts from first_pos; a fork counts on from its promise; the main thread skips
+ * the PREDICTED length a after a promise (estimated ids: Section 4, "Training a
+ * PASTA-SFT model"; appendix "Positional Embedding").
+ * Data is indexed by the order in which rows are fed ("token index" t, the order
+ * of the pool slots): k_rows / v_rows [n_layers][max_tokens][Hkv][D], q_rows / out
+ * [n_layers][max_tokens][Hq][D], all DEVICE; every pass runs on all n_layers pools.
+ * A planning run (PASTA_REPLAY_PLAN_ONLY: no device pointers needed) fills the HOST
+ * outputs and leaves the handle unchanged, so that a caller can lay its data out.
+ * Errors: as append_kv / sync / decode_step; E_CAPACITY also when the trace feeds
+ * more than max_tokens rows or needs more than max_streams threads at once.  A
+ * failing real run may have executed some passes.                              */
+enum { PASTA_OP_TEXT = 0, PASTA_OP_PROMISE = 1, PASTA_OP_SYNC = 2 };
+enum {
+  PASTA_REPLAY_PLAN_ONLY = 1u, /* host outputs only; handle state restored */
+  PASTA_REPLAY_ROPE = 2u       /* PASTA_APPEND_ROPE / PASTA_DECODE_ROPE_Q with the ids above */
+};
+
+typedef struct { int32_t kind, a, b; } pasta_trace_op;
+
+typedef struct {
+  uint32_t struct_size;
+  uint32_t flags;               /* PASTA_REPLAY_* */
+  int32_t request_id;
+  int32_t n_ops;
+  const pasta_trace_op *ops;    /* HOST [n_ops] */
+  int32_t first_pos;            /* position id of the main thread's first fed token */
+  int32_t max_tokens;           /* rows the data arrays hold per layer */
+  const void *k_rows, *v_rows;  /* DEVICE, see above */
+  const void *q_rows;
+  void *out;
+  int32_t *tok_slot;            /* HOST [max_tokens] or NULL: logical slot of token t */
+  int32_t *tok_stream;          /* HOST or NULL: stream id that fed it */
+  int32_t *tok_pos;             /* HOST or NULL: its position id */
+  int32_t *tok_pass;            /* HOST or NULL: the pass that fed it */
+  int64_t *stats;               /* HOST [8] or NULL: {rows fed, passes, most rows in a pass,
+                                   forks, syncs, next main position id, 0, 0} */
+} pasta_replay_args;
+
+int32_t pasta_attn_replay(pasta_attn *h, const pasta_replay_args *a);
+
 /* Frees host state only; does not synchronise (the caller synchronises before
  * freeing pool / workspace).  NULL is a no-op.                               */
 int32_t pasta_attn_destroy(pasta_attn *h);

@@ -22,6 +22,8 @@ TOKEN_MAJOR, HEAD_MAJOR = 0, 1
 DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q = 1, 2, 4
 APPEND_RESERVE_ONLY, APPEND_DEFER, APPEND_ROPE = 1, 2, 4
 SYNC_RETIRE = 1
+OP_TEXT, OP_PROMISE, OP_SYNC = 0, 1, 2
+REPLAY_PLAN_ONLY, REPLAY_ROPE = 1, 2
 _ERR = {E_INVAL: "E_INVAL", E_CAPACITY: "E_CAPACITY", E_NOMEM: "E_NOMEM", E_DEVICE: "E_DEVICE",
         E_STATE: "E_STATE"}
 
@@ -79,6 +81,19 @@ class SyncArgs(C.Structure):
     ]
 
 
+class TraceOp(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("a", C.c_int32), ("b", C.c_int32)]
+
+
+class ReplayArgs(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("request_id", C.c_int32), ("n_ops", C.c_int32),
+        ("ops", C.c_void_p), ("first_pos", C.c_int32), ("max_tokens", C.c_int32), ("k_rows", C.c_void_p),
+        ("v_rows", C.c_void_p), ("q_rows", C.c_void_p), ("out", C.c_void_p), ("tok_slot", C.c_void_p),
+        ("tok_stream", C.c_void_p), ("tok_pos", C.c_void_p), ("tok_pass", C.c_void_p), ("stats", C.c_void_p),
+    ]
+
+
 class DecodeArgs(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("layer", C.c_int32), ("n_streams", C.c_int32),
@@ -112,6 +127,8 @@ def load_library():
         L.pasta_attn_stream_list.restype = C.c_int32
         L.pasta_attn_stream_list.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
+        L.pasta_attn_replay.restype = C.c_int32
+        L.pasta_attn_replay.argtypes = [C.c_void_p, C.POINTER(ReplayArgs)]
         L.pasta_attn_destroy.restype = C.c_int32
         L.pasta_attn_destroy.argtypes = [C.c_void_p]
         _lib = L
@@ -257,6 +274,22 @@ class PastaAttn:
         if rc != OK:
             raise PastaError(rc, "pasta_attn_stream_list")
         return pl.value, st[:nr.value], ct[:nr.value], sd[:nr.value]
+
+    def replay(self, request_id, ops, first_pos, max_tokens, k_rows=None, v_rows=None, q_rows=None, out=None,
+               flags=0):
+        """ops: sequence of (kind, a, b).  Returns dict(slot, stream, pos, pass_, stats) -- host arrays
+        cut to the rows fed.  Without device buffers pass flags=REPLAY_PLAN_ONLY."""
+        arr = (TraceOp * max(len(ops), 1))(*[TraceOp(int(k), int(x), int(y)) for k, x, y in ops])
+        slot, stream, pos, pas = (np.full(max_tokens, -1, np.int32) for _ in range(4))
+        stats = np.zeros(8, np.int64)
+        a = ReplayArgs(C.sizeof(ReplayArgs), flags, request_id, len(ops), C.addressof(arr), first_pos, max_tokens,
+                       _dp(k_rows), _dp(v_rows), _dp(q_rows), _dp(out), _hp(slot), _hp(stream), _hp(pos), _hp(pas),
+                       _hp(stats))
+        rc = self._lib.pasta_attn_replay(self._h, C.byref(a))
+        if rc != OK:
+            raise PastaError(rc, "pasta_attn_replay")
+        n = int(stats[0])
+        return dict(slot=slot[:n], stream=stream[:n], pos=pos[:n], pass_=pas[:n], stats=stats)
 
     def destroy(self):
         if self._h is not None:

@@ -944,3 +944,5 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     return PASTA_E_NOMEM;
   }
 }
+
+#include "replay.hpp"

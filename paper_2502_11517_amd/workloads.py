@@ -440,3 +440,27 @@ def random_fork_sync_history(seed: int, n_slots: int = 80, max_ids: int = 5, p_f
                 del children[c]
                 free_ids.append(c)
     return events
+
+
+def synthetic_trace(seed: int, n_promises: int = 6, text_mean: int = 12, block_median: int = 38,
+                    sync_every: int = 3, tail_text: int = 20):
+    """A synthetic annotation trace for the replay: what the main thread would emit.  Blocks have a
+    log-normal length around `block_median` tokens (the paper reports a median asynchronous block
+    just under 40 tokens); the predicted length is the true length rounded to a multiple of ten,
+    now and then off by ten (the predictions are not exact); a sync follows every `sync_every`
+    promises.  Returns a list of (kind, a, b) with kind 0 = TEXT, 1 = PROMISE, 2 = SYNC."""
+    rng = np.random.default_rng([seed, 4])
+    ops = []
+    for i in range(n_promises):
+        ops.append((0, int(rng.integers(1, 2 * text_mean)), 0))
+        true_len = int(np.clip(np.rint(rng.lognormal(np.log(block_median), 0.6)), 1, 400))
+        pred = max(0, 10 * int(np.rint(true_len / 10.0)) + 10 * int(rng.integers(-1, 2)))
+        ops.append((1, pred, true_len))
+        if (i + 1) % sync_every == 0:
+            ops.append((0, int(rng.integers(1, text_mean)), 0))
+            ops.append((2, 0, 0))
+    if ops[-1][0] != 2:
+        ops.append((0, int(rng.integers(1, text_mean)), 0))
+        ops.append((2, 0, 0))
+    ops.append((0, tail_text, 0))
+    return ops

@@ -631,3 +631,76 @@ def test_maintained_lists_through_syncs_equal_reachability_and_dense_mask_attent
             ref, _ = oracle.attention_dense(op.g, op.k, op.v, 0, mask, q[i], w.scale)
             check_close(got[i], ref, w.dtype, f"stop {stop} stream {sid}")
     s.close()
+
+
+# ------------------------------------------------------------------------- trace replay
+@pytest.mark.parametrize("rope", [False, True])
+def test_trace_replay_matches_the_oracles_interpreter_and_dense_mask_attention(rope):
+    """A whole synthetic response through pasta_attn_replay on two layer pools: every token's slot,
+    stream, position id and pass equal the oracle interpreter's; every token's attention output
+    equals brute-force attention over the final pool masked to what Figure 2b's graph lets that
+    token reach; the pool holds exactly the fed rows (rotated by the estimated ids with rope)."""
+    from oracle import pasta_interp as I
+    from paper_2502_11517_amd.harness import to_device
+    ops = W.synthetic_trace(7, n_promises=5, text_mean=5, block_median=14, sync_every=2, tail_text=6)
+    n_prompt, L = 150, 2
+    w = W.Workload(name="replay", dtype="bf16", Hq=8, Hkv=2, D=128, scale=128 ** -0.5, seed=31, max_requests=1,
+                   pool_tokens=1024, max_streams=6)
+    w.ev_request = np.zeros(n_prompt, np.int32)
+    w.ev_stream = np.zeros(n_prompt, np.int32)
+    w.ev_parent = np.full(n_prompt, -1, np.int32)
+    w.n_prefill = n_prompt
+    s = _session(w, n_layers=L, max_ranges=8192, rope_theta=THETA if rope else 0.0)
+    toks, passes = I.interpret(ops, n_prompt, n_prompt, 6)
+    n = len(toks)
+    rng = np.random.default_rng(99)
+    enc = W.f32_to_bf16_bits
+    kp_rows = enc(rng.standard_normal((L, n_prompt, w.Hkv, w.D)).astype(np.float32))
+    vp_rows = enc(rng.standard_normal((L, n_prompt, w.Hkv, w.D)).astype(np.float32))
+    k_rows = enc(rng.standard_normal((L, n, w.Hkv, w.D)).astype(np.float32))
+    v_rows = enc(rng.standard_normal((L, n, w.Hkv, w.D)).astype(np.float32))
+    q_rows = enc(rng.standard_normal((L, n, w.Hq, w.D)).astype(np.float32))
+    ppos = np.arange(n_prompt, dtype=np.int32)
+    for l in range(L):  # the prompt, as stream 0
+        s.h.append_kv(l, w.ev_request, w.ev_stream, to_device(kp_rows[l], w.dtype, s.device), to_device(vp_rows[l], w.dtype, s.device),
+                      position=ppos, flags=B.APPEND_ROPE if rope else 0)
+    plan = s.h.replay(0, ops, n_prompt, n, flags=B.REPLAY_PLAN_ONLY)  # leaves the handle as it is
+    kd, vd, qd = (to_device(x, w.dtype, s.device) for x in (k_rows, v_rows, q_rows))
+    out = torch.empty_like(qd)
+    r = s.h.replay(0, ops, n_prompt, n, kd, vd, qd, out, flags=B.REPLAY_ROPE if rope else 0)
+    got = _out64(w, out)
+    for key in ("slot", "stream", "pos", "pass_"):
+        assert r[key].tolist() == [t[key] for t in toks] == plan[key].tolist(), key
+    assert r["stats"][1] == passes
+    ev_s = [0] * n_prompt + [t["stream"] for t in toks]
+    ev_p = [-1] * n_prompt + [t["parent"] for t in toks]
+    ev_n = [1] + [0] * (n_prompt - 1) + [1 if t["new"] else 0 for t in toks]
+    joins = {t["slot"]: t["join"] for t in toks if t["join"]}
+    pos_all = np.concatenate([ppos, np.array([t["pos"] for t in toks], np.int32)])
+    g = oracle.Geom(w.dtype, w.Hq, w.Hkv, w.D, pool_tokens=w.pool_tokens)
+    for l in range(L):
+        ka = np.concatenate([kp_rows[l], k_rows[l]])
+        if rope:
+            ka = oracle.round_pool(w.dtype, oracle.rope(oracle.widen_pool(w.dtype, ka), pos_all, THETA))
+        okp, ovp, tail = g.new_pool(), g.new_pool(), np.zeros(1, np.int64)
+        assert oracle.append(g, okp, ovp, np.zeros(n_prompt + n, np.int32), ka, np.concatenate([vp_rows[l], v_rows[l]]), tail)[0] == 0
+        for i in range(0, n, 3 if l else 1):  # every token on layer 0, every third on layer 1
+            mask = oracle.visible_events(ev_s, ev_p, ev_n, joins, toks[i]["slot"])
+            if rope:
+                q64 = oracle.rope(oracle.widen_pool(w.dtype, q_rows[l, i:i + 1]), [toks[i]["pos"]], THETA)[0]
+                rows = np.nonzero(mask)[0]
+                ref, _ = oracle.attention_q64(g, okp, ovp, [0], [0], [0, len(rows)], rows, np.ones(len(rows), np.int32),
+                                              np.ones(len(rows), np.int32), q64[None], w.scale)
+                ref = ref[0]
+            else:
+                ref, _ = oracle.attention_dense(g, okp, ovp, 0, mask, q_rows[l, i], w.scale)
+            check_close(got[l, i], ref, w.dtype, f"layer {l} token {i}")
+        kb, vb = s.pool_bits(l)
+        m = (n_prompt + n) * w.Hkv * w.D
+        assert np.array_equal(vb[:m], ovp[:m])
+        if rope:
+            d = np.abs(oracle.widen_pool(w.dtype, kb[:m]) - oracle.widen_pool(w.dtype, okp[:m]))
+            assert d.max() <= 2.0 ** -7 * np.abs(oracle.widen_pool(w.dtype, okp[:m])).max() and (d != 0).mean() < 0.01
+        else:
+            assert np.array_equal(kb[:m], okp[:m])
+    s.close()

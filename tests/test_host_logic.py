@@ -53,7 +53,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "pasta_attn.h")).read()
     declared = set(re.findall(r"\bint32_t\s+(pasta_attn_\w+)\s*\(", hdr))
     assert declared == {"pasta_attn_create", "pasta_attn_append_kv", "pasta_attn_decode_step", "pasta_attn_destroy",
-                        "pasta_attn_sync", "pasta_attn_stream_list"}
+                        "pasta_attn_sync", "pasta_attn_stream_list", "pasta_attn_replay"}
     syms = subprocess.run(["nm", "-D", "--defined-only", B.library_path()], capture_output=True, text=True).stdout
     exported = {l.split()[-1] for l in syms.splitlines() if " T " in l}
     assert declared <= exported
@@ -333,4 +333,32 @@ def test_sync_argument_checks_and_retire_only():
     h.sync(0, -1, [1], retire=True)                         # retire only
     app(1, 0)                                               # the id opens again, as a fork of stream 0 now
     assert _expand(*h.stream_list(0, 1)) == list(range(9))
+    h.destroy()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_replay_plan_equals_the_oracles_interpreter(seed):
+    """The library's trace replay (planning run: host bookkeeping only) against the oracle's
+    independent simulation of the interpreter: same slot, stream, position id and pass for
+    every token fed, same maintained list for the main thread at the end; and the planning
+    run leaves the handle as it was."""
+    from oracle import pasta_interp as I
+    ops = W.synthetic_trace(50 + seed, n_promises=4 + seed, sync_every=2 + seed % 3)
+    n_prompt = 33
+    cfg = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=6, pool_tokens=4096, max_ranges=8192)
+    h = B.PastaAttn(cfg, FAKE, FAKE, FAKE, B.query_workspace_bytes(cfg))
+    h.append_kv(0, [0] * n_prompt, [0] * n_prompt, None, None, flags=B.APPEND_RESERVE_ONLY)
+    toks, passes = I.interpret(ops, n_prompt, n_prompt, 6)
+    r = h.replay(0, ops, n_prompt, 4000, flags=B.REPLAY_PLAN_ONLY)
+    assert r["stats"][0] == len(toks) and r["stats"][1] == passes
+    assert r["stats"][2] == max(sum(1 for t in toks if t["pass_"] == p) for p in range(passes))
+    for key, name in (("slot", "slot"), ("stream", "stream"), ("pos", "pos"), ("pass_", "pass_")):
+        assert r[key].tolist() == [t[name] for t in toks], key
+    assert h.stream_list(0, 0)[0] == n_prompt                  # unchanged by the planning run
+    with pytest.raises(B.PastaError) as e:
+        h.stream_list(0, 1)
+    assert e.value.code == B.E_STATE
+    with pytest.raises(B.PastaError) as e:                     # too few rows in the caller's arrays
+        h.replay(0, ops, n_prompt, len(toks) - 1, flags=B.REPLAY_PLAN_ONLY)
+    assert e.value.code == B.E_CAPACITY
     h.destroy()

@@ -623,3 +623,60 @@ def test_visible_events_without_syncs_is_the_ancestor_rule(seed):
         dense = oracle.visible_dense(ev_s, parent, spawn, s)
         reach = oracle.visible_events(ev_s, ev_p, ev_n, None, last)
         assert np.array_equal(reach[: last + 1], dense[: last + 1]) and not reach[last + 1:].any()
+
+
+# ------------------------------------------------------------------ the interpreter's control flow
+def test_interpreter_reproduces_the_papers_timeline():
+    from oracle import pasta_interp as I
+    fx = json.load(open(os.path.join(HERE, "golden", "paper_sec3_replay.json")))
+    f = fx["facts"]
+    toks, passes = I.interpret([tuple(o) for o in fx["ops"]], fx["n_prompt"], fx["n_prompt"], 4)
+    for p in range(3):
+        assert [[t["slot"], t["stream"]] for t in toks if t["pass_"] == p] == f[f"pass{p}"]
+    sync = [t for t in toks if t["join"]]
+    assert len(sync) == 1 and sync[0]["slot"] == f["sync_slot"] and sync[0]["pass_"] == f["sync_pass"]
+    assert sync[0]["join"] == f["sync_joins"] and sync[0]["stream"] == 0
+    assert max(t["pass_"] for t in toks if t["stream"] == 2) == f["fork2_last_pass"]
+    assert max(t["pass_"] for t in toks if t["stream"] == 1) == f["fork1_last_pass"]
+    assert len(toks) == f["n_tokens"] and passes == f["n_passes"]
+    # while it waits, the main thread feeds nothing; afterwards its tokens see every slot before them
+    assert not [t for t in toks if t["stream"] == 0 and 1 < t["pass_"] < f["sync_pass"]]
+    ev_s = [0] * fx["n_prompt"] + [t["stream"] for t in toks]
+    ev_p = [-1] * fx["n_prompt"] + [t["parent"] for t in toks]
+    ev_n = [1] + [0] * (fx["n_prompt"] - 1) + [1 if t["new"] else 0 for t in toks]
+    joins = {t["slot"]: t["join"] for t in toks if t["join"]}
+    last = toks[-1]["slot"]
+    assert oracle.visible_events(ev_s, ev_p, ev_n, joins, last)[: last + 1].all()
+    # Fork#1's token of pass 2 (the text's 'find'): sees its thread and the prompt, not the second promise / <async>
+    m = oracle.visible_events(ev_s, ev_p, ev_n, joins, 26)
+    assert m[20] and m[21] and m[22] and m[25] and not m[23] and not m[24] and not m[27]
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_interpreter_invariants_on_synthetic_traces(seed):
+    from oracle import pasta_interp as I
+    ops = W.synthetic_trace(seed, n_promises=5)
+    toks, passes = I.interpret(ops, 100, 40, 8)
+    n_text = sum(a for k, a, b in ops if k == 0)
+    n_prom = sum(1 for k, a, b in ops if k == 1)
+    n_sync = sum(1 for k, a, b in ops if k == 2)
+    assert len(toks) == n_text + n_sync + sum(3 + b for k, a, b in ops if k == 1)  # promise, <async>, b, </async>
+    assert [t["slot"] for t in toks] == list(range(40, 40 + len(toks)))
+    assert sum(1 for t in toks if t["new"]) == n_prom and sum(1 for t in toks if t["join"]) <= n_sync
+    # at most one token per thread and pass (two for the main thread's promise + the inserted <async>)
+    for p in range(passes):
+        ids = [t["stream"] for t in toks if t["pass_"] == p]
+        assert len(ids) == len(set(ids)) and ids
+    # the longest chain: a pass count no smaller than the main thread's own tokens, no larger than all tokens
+    assert n_text + n_prom + n_sync <= passes <= len(toks)
+    # estimated position ids: the main thread's ids increase; behind a promise they jump by 1 + predicted length
+    main = [t for t in toks if t["stream"] == 0]
+    assert all(b["pos"] > a["pos"] for a, b in zip(main, main[1:]))
+    preds = [a for k, a, b in ops if k == 1]
+    jumps = [b["pos"] - a["pos"] - 1 for a, b in zip(main, main[1:]) if b["pos"] - a["pos"] > 1]
+    assert jumps == [x for x in preds if x > 0]
+    # a fork counts on from its promise
+    for t in toks:
+        if t["new"]:
+            prom = [m for m in main if m["slot"] == t["slot"] - 1][0]
+            assert t["pos"] == prom["pos"] + 1
