@@ -46,7 +46,7 @@ def main():
     ap.add_argument("--rope", action="store_true",
                     help="rotary embedding by position ids inside the path: K rotated by the append (a launch of its "
                          "own, not deferred), Q rotated in the attention kernel")
-    ap.add_argument("--workload", choices=["config3", "config2", "config4", "config5"], default="config3",
+    ap.add_argument("--workload", choices=["config3", "config2", "config4", "config5", "replay"], default="config3",
                     help="config3 (default) is the headline line; the others time decode steps only (their "
                          "state is a single step's) and exist to show how the kernels behave on the other shapes")
     ap.add_argument("--calibrate", action="store_true",
@@ -68,6 +68,8 @@ def main():
         raise SystemExit("libpasta_attn.so is not built: run `python __graft_entry__.py` first")
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
+    if args.workload == "replay":
+        return replay_bench(args, dev)
     if args.workload != "config3":
         return decode_only(args, getattr(W, args.workload)(), dev)
     L = args.layers
@@ -315,6 +317,73 @@ def decode_only(args, w, dev):
                      "kernel": "attention-partials launch", "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
         "cpu_baseline": None}))
     s.close()
+
+
+def replay_bench(args, dev):
+    """A whole synthetic response through the interpreter's control flow (pasta_attn_replay) on
+    `--layers` pools, against the same number of tokens decoded as ONE sequential thread: what the
+    asynchronous decoding buys at the attention path.  Trace: blocks of median ~38 tokens (the
+    paper's statistic), predicted lengths in multiples of ten, a sync every third promise."""
+    import torch
+
+    from paper_2502_11517_amd import binding as B
+    from paper_2502_11517_amd import workloads as W
+    from paper_2502_11517_amd.harness import Session
+
+    L, P = args.layers, 1024
+    ops = W.synthetic_trace(2025, n_promises=9, text_mean=12, block_median=38, sync_every=3, tail_text=24)
+    w = W.Workload(name="replay", dtype="bf16", Hq=32, Hkv=8, D=128, scale=1.0, seed=1, max_requests=1,
+                   pool_tokens=4096, max_streams=8, k_std=128 ** -0.5)
+    w.ev_request = np.zeros(P, np.int32)
+    w.ev_stream = np.zeros(P, np.int32)
+    w.ev_parent = np.full(P, -1, np.int32)
+    w.n_prefill = P
+    results = {}
+    n_tok = None
+    for mode in ("pasta", "sequential"):
+        s = Session(w, kv_layout=B.HEAD_MAJOR, n_layers=L, max_ranges=16384, rope_theta=10000.0 if args.rope else 0.0)
+        g = torch.Generator(device=dev).manual_seed(7)
+        kp = torch.randn(P, w.Hkv, w.D, device=dev, generator=g).to(torch.bfloat16) * 0.088
+        vp = torch.randn(P, w.Hkv, w.D, device=dev, generator=g).to(torch.bfloat16)
+        for l in range(L):
+            s.h.append_kv(l, w.ev_request, w.ev_stream, kp, vp, position=np.arange(P, dtype=np.int32),
+                          flags=B.APPEND_ROPE if args.rope else 0)
+        plan = s.h.replay(0, ops, P, 4096 - P, flags=B.REPLAY_PLAN_ONLY)
+        if n_tok is None:
+            n_tok = int(plan["stats"][0])
+            pasta_stats = plan["stats"].copy()
+        run_ops = ops if mode == "pasta" else [(B.OP_TEXT, n_tok, 0)]
+        kd = torch.randn(L, n_tok, w.Hkv, w.D, device=dev, generator=g).to(torch.bfloat16) * 0.088
+        vd = torch.randn(L, n_tok, w.Hkv, w.D, device=dev, generator=g).to(torch.bfloat16)
+        qd = torch.randn(L, n_tok, w.Hq, w.D, device=dev, generator=g).to(torch.bfloat16)
+        out = torch.empty_like(qd)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r = s.h.replay(0, run_ops, P, n_tok, kd, vd, qd, out, flags=B.REPLAY_ROPE if args.rope else 0)
+        torch.cuda.synchronize()
+        results[mode] = (time.perf_counter() - t0, int(r["stats"][1]))
+        assert int(r["stats"][0]) == n_tok and bool(torch.isfinite(out.float()).all())
+        s.close()
+        del s, kd, vd, qd, out
+    t_p, passes_p = results["pasta"]
+    t_s, passes_s = results["sequential"]
+    n_content = sum(a for k, a, b in ops if k == 0) + sum(b for k, a, b in ops if k == 1)
+    print(json.dumps({
+        "metric": "trace replay: tokens/s through the attention path (append + decode on every layer, whole response)",
+        "value": n_tok / t_p, "unit": "tokens/s", "n_gpus": 1, "steps": passes_p * L, "warmup": 0,
+        "ms_per_step": t_p / (passes_p * L) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"replay: prompt {P}, synthetic trace of 9 promises (block median ~38 tokens, predicted "
+                               f"lengths in tens, sync every 3), bf16 32q/8kv heads D=128, {L} layers",
+                   "rope": bool(args.rope)},
+        "trace": {"tokens": n_tok, "passes": passes_p, "most_rows_in_a_pass": int(pasta_stats[2]),
+                  "forks": int(pasta_stats[3]), "syncs": int(pasta_stats[4]),
+                  "theoretical_parallelism": n_content / passes_p,
+                  "rows_per_pass": n_tok / passes_p},
+        "sequential": {"passes": passes_s, "seconds": t_s, "tokens_per_s": n_tok / t_s},
+        "pasta": {"passes": passes_p, "seconds": t_p},
+        "speedup_at_the_attention_path": t_s / t_p,
+        "roofline": None, "cpu_baseline": None}))
 
 
 if __name__ == "__main__":
