@@ -338,7 +338,7 @@ def replay_bench(args, dev):
     w.ev_stream = np.zeros(P, np.int32)
     w.ev_parent = np.full(P, -1, np.int32)
     w.n_prefill = P
-    results = {}
+    results, host_s = {}, {}
     n_tok = None
     for mode in ("pasta", "sequential"):
         s = Session(w, kv_layout=B.HEAD_MAJOR, n_layers=L, max_ranges=16384, rope_theta=10000.0 if args.rope else 0.0)
@@ -360,8 +360,10 @@ def replay_bench(args, dev):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         r = s.h.replay(0, run_ops, P, n_tok, kd, vd, qd, out, flags=B.REPLAY_ROPE if args.rope else 0)
+        t_host = time.perf_counter() - t0  # all launches enqueued
         torch.cuda.synchronize()
         results[mode] = (time.perf_counter() - t0, int(r["stats"][1]))
+        host_s[mode] = t_host
         assert int(r["stats"][0]) == n_tok and bool(torch.isfinite(out.float()).all())
         s.close()
         del s, kd, vd, qd, out
@@ -380,8 +382,9 @@ def replay_bench(args, dev):
                   "forks": int(pasta_stats[3]), "syncs": int(pasta_stats[4]),
                   "theoretical_parallelism": n_content / passes_p,
                   "rows_per_pass": n_tok / passes_p},
-        "sequential": {"passes": passes_s, "seconds": t_s, "tokens_per_s": n_tok / t_s},
-        "pasta": {"passes": passes_p, "seconds": t_p},
+        "sequential": {"passes": passes_s, "seconds": t_s, "tokens_per_s": n_tok / t_s,
+                       "host_enqueue_seconds": host_s["sequential"]},
+        "pasta": {"passes": passes_p, "seconds": t_p, "host_enqueue_seconds": host_s["pasta"]},
         "speedup_at_the_attention_path": t_s / t_p,
         "roofline": None, "cpu_baseline": None}))
 
