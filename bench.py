@@ -43,6 +43,10 @@ def main():
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
     ap.add_argument("--eager-append", action="store_true",
                     help="run the KV-append as a launch of its own instead of letting it ride with the decode launch")
+    ap.add_argument("--no-share", action="store_true",
+                    help="comparison: no shared-prefix items, every stream reads its whole visible set itself")
+    ap.add_argument("--dense-mask", action="store_true",
+                    help="comparison: every stream walks the whole pool under a 0/1 mask (the paper's own formulation)")
     ap.add_argument("--rope", action="store_true",
                     help="rotary embedding by position ids inside the path: K rotated by the append (a launch of its "
                          "own, not deferred), Q rotated in the attention kernel")
@@ -100,6 +104,7 @@ def main():
     q_steps = [to_device(w.q(t), w.dtype, dev) for t in range(tokens)]
     out = torch.empty(L, w.n, w.Hq, w.D, dtype=torch.bfloat16, device=dev)
     flags = (B.DECODE_NO_MFMA if args.no_mfma else 0) | (B.DECODE_ROPE_Q if args.rope else 0)
+    flags |= (B.DECODE_NO_SHARE if args.no_share else 0) | (B.DECODE_DENSE_MASK if args.dense_mask else 0)
     q_pos = [w.q_positions(t) if args.rope else None for t in range(tokens)]
 
     # HIP events around the attention-partials kernels of sampled steps
@@ -231,6 +236,8 @@ def main():
                                "right-aligned round-robin, append+decode per step",
                    "n_layers_cycled": L, "kv_layout": args.layout, "visibility": "maintained lists",
                    "append": "eager (own launch)" if (args.eager_append or args.rope) else "deferred (rides with the decode launch)",
+                   "visibility_mode": "dense mask over the whole pool" if args.dense_mask else
+                                      ("lists, prefix not shared" if args.no_share else "lists, shared prefix"),
                    "rope": "K rotated at append, Q in the attention kernel, theta 1e4" if args.rope else "off (Q, K arrive rotated)",
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -205,19 +205,35 @@ enum {
   PASTA_DECODE_PLAN_ONLY = 1u, /* validate + plan + fill HOST debug outputs, enqueue nothing */
   PASTA_DECODE_NO_MFMA = 2u,   /* route the shared prefix through the private-segment
                                   kernel too (the path F32 always takes) */
-  PASTA_DECODE_ROPE_Q = 4u     /* rotate query row i by position[i] before use (q itself is
+  PASTA_DECODE_ROPE_Q = 4u,    /* rotate query row i by position[i] before use (q itself is
                                   not modified; needs position != NULL, rope_theta > 0) */
+  /* Two comparison modes, same results, more bytes -- what the segment lists and the shared
+   * prefix save (the appendix on the naive interpreter; Section 5.1: the paper's own
+   * implementation runs attention over its whole static pool under a mask): */
+  PASTA_DECODE_NO_SHARE = 8u,  /* no shared-prefix items: every stream reads its whole
+                                  visible set by itself (the prefix once per stream) */
+  PASTA_DECODE_DENSE_MASK = 16u /* every stream walks ALL slots [0, tail) of its request and
+                                  masks what it may not see: the lists are turned into a 0/1
+                                  byte mask per stream on the host, copied to the device, and
+                                  applied to the logits.  BF16, head_dim 128 only. */
 };
 
 typedef struct {
   uint32_t struct_size;
   uint32_t flags;               /* PASTA_DECODE_* */
   int32_t layer;
-  int32_t n_streams;            /* n >= 1 */
+  int32_t n_streams;            /* n >= 1 query tokens, at most max_requests * max_streams */
   const int32_t *request_id;    /* HOST [n] */
   const int32_t *stream_id;     /* HOST [n]; (request, stream) pairs distinct */
   const int32_t *position;      /* HOST [n] or NULL: position id >= 0 of each query token;
                                    used only with PASTA_DECODE_ROPE_Q */
+  const int32_t *causal_skip;   /* HOST [n] or NULL.  Several query tokens of ONE stream in one
+                                   step (the inserted <async> token together with the fork's
+                                   first token; a prompt fed in chunks): maintained mode, the
+                                   stream's rows appended first, then one entry per token with
+                                   causal_skip[i] = how many of the stream's NEWEST own rows
+                                   query i does not see (k-1, ..., 1, 0 for a chunk of k).  With
+                                   it, and in explicit mode, (request, stream) pairs may repeat. */
   const int32_t *prefix_len;    /* HOST [n]   (explicit mode) */
   const int32_t *range_offsets; /* HOST [n+1] (explicit mode) or NULL */
   const int32_t *range_start;   /* HOST [range_offsets[n]] */

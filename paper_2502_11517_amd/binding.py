@@ -19,7 +19,7 @@ _lib = None
 OK, E_INVAL, E_CAPACITY, E_NOMEM, E_DEVICE, E_STATE = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
-DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q = 1, 2, 4
+DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q, DECODE_NO_SHARE, DECODE_DENSE_MASK = 1, 2, 4, 8, 16
 APPEND_RESERVE_ONLY, APPEND_DEFER, APPEND_ROPE = 1, 2, 4
 SYNC_RETIRE = 1
 OP_TEXT, OP_PROMISE, OP_SYNC = 0, 1, 2
@@ -97,7 +97,7 @@ class ReplayArgs(C.Structure):
 class DecodeArgs(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("flags", C.c_uint32), ("layer", C.c_int32), ("n_streams", C.c_int32),
-        ("request_id", C.c_void_p), ("stream_id", C.c_void_p), ("position", C.c_void_p),
+        ("request_id", C.c_void_p), ("stream_id", C.c_void_p), ("position", C.c_void_p), ("causal_skip", C.c_void_p),
         ("prefix_len", C.c_void_p), ("range_offsets", C.c_void_p), ("range_start", C.c_void_p),
         ("range_count", C.c_void_p), ("range_stride", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
         ("out_lse", C.c_void_p), ("dbg_gather_offsets", C.c_void_p), ("dbg_gather_rows", C.c_void_p),
@@ -201,10 +201,10 @@ class PastaAttn:
 
     def decode_step(self, layer, request_id, stream_id, q, out, *, lists=None, out_lse=None, flags=0,
                     position=None, dbg_gather_offsets=None, dbg_gather_rows=None, dbg_plan=None,
-                    prof_events=None):
+                    prof_events=None, causal_skip=None):
         """lists = (prefix_len, range_offsets, start, count, stride) for explicit visibility;
         None uses the lists append_kv has maintained."""
-        rid, sid, pos = _i32(request_id), _i32(stream_id), _i32(position)
+        rid, sid, pos, skip = _i32(request_id), _i32(stream_id), _i32(position), _i32(causal_skip)
         n = int(rid.shape[0])
         if lists is not None:
             pl, offs, st, ct, sd = (_i32(x) for x in lists)
@@ -213,7 +213,7 @@ class PastaAttn:
         else:
             pl = offs = st = ct = sd = None
         ev0, ev1 = prof_events if prof_events is not None else (None, None)
-        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, n, _hp(rid), _hp(sid), _hp(pos), _hp(pl), _hp(offs),
+        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, n, _hp(rid), _hp(sid), _hp(pos), _hp(skip), _hp(pl), _hp(offs),
                        _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), _hp(dbg_gather_offsets),
                        _dp(dbg_gather_rows), _hp(dbg_plan), ev0, ev1)
         rc = self._lib.pasta_attn_decode_step(self._h, C.byref(a))
@@ -243,7 +243,7 @@ class PastaAttn:
         else:
             pl = offs = st = ct = sd = None
         ev0, ev1 = prof_events if prof_events is not None else (None, None)
-        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), _hp(pos), _hp(pl),
+        a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), _hp(pos), None, _hp(pl),
                        _hp(offs), _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), None, None, None,
                        ev0, ev1)
         fn, h, ref = self._lib.pasta_attn_decode_step, self._h, C.byref(a)

@@ -55,6 +55,7 @@ struct AttnLds {
   u32x4 q[32 * 16];            // stacked Q rows, same swizzle (rows >= R are zero)
   float mw[4][32], lw[4][32];  // per-wave row max / row sum at the end of the item
   int pend_pos[32];            // position ids of the rows of a deferred rotating append
+  uint8_t mask[kGatherMax];    // dense-mask comparison mode: the item's slice of its stream's mask
   int rows[kGatherMax];        // listed gather items: row code of every token
   DevRange ranges[kGatherMax]; // listed gather items: the ranges the item overlaps
 };
@@ -133,6 +134,12 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     pend0 = it.pend0;
     pend_src0 = it.pend_src0;
     listed = it.n_ranges > 1;
+    if (p.dense_mask) {  // comparison mode: the list is [0, tail), what may be seen is in the mask
+      const int mb = meta_word(p, p.off_streams + it.stream * (int)(sizeof(DevStream) / 4) +
+                                      (int)(__builtin_offsetof(DevStream, mask_base) / 4));
+      for (int j = tid; j < kGatherMax; j += kAttnThreads)
+        lds.mask[j] = j < n_tok ? p.dense_mask[mb + slot0 + j] : 0;  // published by the Q barrier
+    }
     if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> row code
       const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
       const int nr = it.n_ranges;
@@ -411,21 +418,30 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     for (int i = 0; i < 16; ++i) S[i] += S1[i];
     // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block
     const int tok0 = b * kBlock + 4 * hh;
+    uint32_t mk[4] = {~0u, ~0u, ~0u, ~0u};  // one byte per token: tokens tok0 + 8 k .. + 3 in mk[k]
+    if constexpr (GATHER) {
+      if (p.dense_mask) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mk[k] = *reinterpret_cast<const uint32_t*>(&lds.mask[(tok0 + 8 * k) & (kGatherMax - 1)]);
+      }
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float s = (tok0 + 8 * (i >> 2) + (i & 3)) < n_tok ? S[i] * p.scale_log2e : -INFINITY;
+      const bool seen = (tok0 + 8 * (i >> 2) + (i & 3)) < n_tok && ((mk[i >> 2] >> (8 * (i & 3))) & 0xffu);
+      const float s = seen ? S[i] * p.scale_log2e : -INFINITY;
       S[i] = s;
       mx = fmaxf(mx, s);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float mn = fmaxf(m_run, mx);  // finite: a block holds at least one valid token
-    const float corr = fast_exp2(m_run - mn);
+    const float mn = fmaxf(m_run, mx);            // -inf while the row has seen nothing (dense-mask mode)
+    const float mref = mn == -INFINITY ? 0.f : mn;
+    const float corr = fast_exp2(m_run - mref);
     m_run = mn;
     float ps = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      S[i] = fast_exp2(S[i] - mn);
+      S[i] = fast_exp2(S[i] - mref);
       ps += S[i];
     }
     l_run = l_run * corr + ps;
@@ -502,8 +518,9 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     const int rr = pass * 8 + (tid >> 5), c = tid & 31;
     if (rr < R) {
       const float m0 = lds.mw[0][rr], m1 = lds.mw[1][rr], m2 = lds.mw[2][rr], m3 = lds.mw[3][rr];
-      const float ma = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));  // finite: wave 0 always has a block
-      const float s0 = fast_exp2(m0 - ma), s1 = fast_exp2(m1 - ma), s2 = fast_exp2(m2 - ma), s3 = fast_exp2(m3 - ma);
+      const float ma = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));  // -inf: the row saw nothing in this item (dense-mask mode)
+      const float mr = ma == -INFINITY ? 0.f : ma;
+      const float s0 = fast_exp2(m0 - mr), s1 = fast_exp2(m1 - mr), s2 = fast_exp2(m2 - mr), s3 = fast_exp2(m3 - mr);
       const f32x4* src = reinterpret_cast<const f32x4*>(&lds.tile[0]) + rr * 32 + (c ^ rr);  // + 1024 per wave
       const f32x4 acc = src[0] * s0 + src[1024] * s1 + src[2048] * s2 + src[3072] * s3;
       *reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + rr) * D + 4 * c) = acc;

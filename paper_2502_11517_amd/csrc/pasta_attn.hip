@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <deque>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -54,6 +55,10 @@ struct pasta_attn {
   // workspace carve-up (byte offsets)
   size_t off_page_table = 0, off_meta = 0, meta_bytes = 0, off_ml = 0, off_acc = 0;
   size_t off_rope = 0, off_qrot = 0;  // rotary table (fp64, D/2 entries) and rotated-Q buffer (rope_theta > 0)
+  size_t off_mask = 0, mask_bytes = 0;  // dense-mask comparison mode: one byte per (stream, slot)
+  uint8_t* mask_pinned = nullptr;       // its host staging, allocated at first use
+  hipEvent_t mask_ev{};
+  bool mask_ev_used = false;
   int64_t part_rows_cap = 0;
   // a deferred append (PASTA_APPEND_DEFER): its copy is done by the next decode_step's launch
   struct Pending {
@@ -84,7 +89,7 @@ int64_t meta_words_cap(const pasta_attn_config& c) {
   // items: every stream can split its private list into chunks; bounded by total tokens/chunk + streams
   const int64_t items = ns * ((cap_tokens + kPrivChunk - 1) / kPrivChunk + 1);
   return ns * (int64_t)(sizeof(DevStream) / 4) + (int64_t)c.max_requests * (sizeof(DevReq) / 4) + ns +
-         ranges * 4 + std::min<int64_t>(items, (int64_t)1 << 22) * 4 + 64;
+         ranges * 4 + std::min<int64_t>(items, (int64_t)1 << 22) * (int64_t)(sizeof(DevItem) / 4) + 64;
 }
 
 int validate_cfg(const pasta_attn_config* c) {
@@ -135,6 +140,12 @@ void carve(pasta_attn* h) {
   off += align_up((size_t)h->part_rows_cap * sizeof(float2), 256);
   h->off_acc = off;
   off += align_up((size_t)h->part_rows_cap * c.head_dim * sizeof(float), 256);
+  {
+    const int64_t cap_tokens = c.page_tokens ? (int64_t)c.pages_per_request * c.page_tokens : c.pool_tokens;
+    h->mask_bytes = align_up((size_t)c.max_requests * c.max_streams * (size_t)cap_tokens + 256, 256);
+    h->off_mask = off;
+    off += h->mask_bytes;
+  }
   if (c.rope_theta > 0.f) {
     h->off_rope = off;
     off += align_up((size_t)kRopeTabEntries * sizeof(double), 256);
@@ -404,6 +415,7 @@ extern "C" int32_t pasta_attn_destroy(pasta_attn* h) {
     for (int i = 0; i < kRing; ++i) (void)hipEventDestroy(h->ring_ev[i]);
   }
   if (h->pinned) (void)hipHostFree(h->pinned);
+  if (h->mask_pinned) { (void)hipHostFree(h->mask_pinned); (void)hipEventDestroy(h->mask_ev); }
   delete h;
   return PASTA_OK;
 }
@@ -648,18 +660,23 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
   }
   const bool explicit_mode = a->range_offsets != nullptr;
   if (explicit_mode && !a->prefix_len) return PASTA_E_INVAL;
+  if (explicit_mode && a->causal_skip) return PASTA_E_INVAL;  // the lists say it all there
+  const bool no_share = a->flags & (PASTA_DECODE_NO_SHARE | PASTA_DECODE_DENSE_MASK);
+  const bool dense = a->flags & PASTA_DECODE_DENSE_MASK;
+  if (dense && (c.dtype != PASTA_BF16 || c.head_dim != 128 || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
 
   try {
     // ---- lists + validation
     std::vector<ListView> lv(n);
+    std::deque<std::vector<Range>> trimmed;  // storage of the views that causal_skip shortens (stable addresses)
     std::vector<uint8_t> seen((size_t)c.max_requests * c.max_streams, 0);
     int64_t total_ranges = 0;
     for (int i = 0; i < n; ++i) {
       const int r = a->request_id[i], s = a->stream_id[i];
       if (r < 0 || r >= c.max_requests || s < 0 || s >= c.max_streams) return PASTA_E_INVAL;
       uint8_t& sn = seen[(size_t)r * c.max_streams + s];
-      if (sn) return PASTA_E_INVAL;
+      if (sn && !explicit_mode && !a->causal_skip) return PASTA_E_INVAL;  // one query token per stream, unless said otherwise
       sn = 1;
       ListView& v = lv[i];
       if (explicit_mode) {
@@ -682,11 +699,50 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         const StreamState& ss = sstate(h, r, s);
         if (!ss.open) return PASTA_E_STATE;
         v = ListView{ss.prefix_len, ss.ranges.data(), (int32_t)ss.ranges.size(), nullptr, nullptr, nullptr};
+        const int skip = a->causal_skip ? a->causal_skip[i] : 0;
+        if (skip < 0) return PASTA_E_INVAL;
+        if (skip > 0) {  // a view without the stream's `skip` newest rows: they are the largest slots of its list
+          trimmed.emplace_back(ss.ranges);
+          std::vector<Range>& tr = trimmed.back();
+          int left = skip;
+          while (left > 0 && !tr.empty()) {
+            const int take = std::min(left, tr.back().count);
+            tr.back().count -= take;
+            left -= take;
+            if (tr.back().count == 0) tr.pop_back();
+          }
+          if (left > ss.prefix_len) return PASTA_E_INVAL;
+          v = ListView{ss.prefix_len - left, tr.data(), (int32_t)tr.size(), nullptr, nullptr, nullptr};
+        }
         if (v.prefix_len == 0 && v.n_ranges == 0) return PASTA_E_INVAL;
       }
       total_ranges += v.n_ranges;
     }
     if (total_ranges > c.max_ranges) return PASTA_E_CAPACITY;
+
+    // ---- dense-mask comparison mode: the lists become one 0/1 byte per (stream, slot), and every
+    // stream's list becomes "all slots of its request"
+    std::vector<uint8_t> mask;
+    std::vector<int32_t> mask_base(n, 0);
+    if (dense) {
+      size_t total = 0;
+      for (int i = 0; i < n; ++i) {
+        mask_base[i] = (int32_t)total;
+        total += (size_t)h->tail[a->request_id[i]];
+      }
+      if (total + 256 > h->mask_bytes) return PASTA_E_CAPACITY;
+      mask.assign(total + 256, 0);
+      for (int i = 0; i < n; ++i) {
+        uint8_t* m = mask.data() + mask_base[i];
+        std::memset(m, 1, (size_t)lv[i].prefix_len);
+        for (int k = 0; k < lv[i].n_ranges; ++k) {
+          const Range g = lv[i].at(k);
+          for (int j = 0; j < g.count; ++j) m[(int64_t)g.start + (int64_t)j * g.stride] = 1;
+        }
+        lv[i] = ListView{(int32_t)h->tail[a->request_id[i]], nullptr, 0, nullptr, nullptr, nullptr};
+      }
+      total_ranges = 0;
+    }
 
     // ---- group by request (order of first appearance)
     std::vector<int32_t> req_idx_of(c.max_requests, -1);
@@ -718,7 +774,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G);
     int64_t pc_total = 0, pc_weighted = 0;  // the second counts a prefix once per row group of 32
     for (auto& q : reqs) {
-      if (!mfma || q.pc < kTile) q.pc = 0;
+      if (!mfma || q.pc < kTile || no_share) q.pc = 0;
       pc_total += q.pc;
       pc_weighted += (int64_t)q.pc * ((q.n_streams * G + 31) / 32);
     }
@@ -747,6 +803,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       ds.req_idx = stream_req_idx[i];
       ds.local = stream_local[i];
       ds.pos = rope_q ? a->position[i] : 0;
+      ds.mask_base = mask_base[i];
       ds.pc = q.pc;
       ds.range_begin = (int32_t)ranges.size();
       int32_t cum = 0;
@@ -866,6 +923,23 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       // the blob was built before these fields were known: patch the two tables in place
       std::memcpy(blob.data() + p.off_reqs, reqs.data(), reqs.size() * sizeof(DevReq));
       std::memcpy(blob.data() + p.off_items, items.data(), items.size() * sizeof(DevItem));
+    }
+    if (dense) {  // the masks travel like the paper's mask tensors: host -> device, every step
+      if (!h->mask_pinned) {
+        if (hipHostMalloc((void**)&h->mask_pinned, h->mask_bytes, hipHostMallocDefault) != hipSuccess) {
+          (void)hipGetLastError();
+          h->mask_pinned = nullptr;
+          return PASTA_E_DEVICE;
+        }
+        if (hipEventCreateWithFlags(&h->mask_ev, hipEventDisableTiming) != hipSuccess) return PASTA_E_DEVICE;
+      }
+      if (h->mask_ev_used && hipEventSynchronize(h->mask_ev) != hipSuccess) return PASTA_E_DEVICE;
+      std::memcpy(h->mask_pinned, mask.data(), mask.size());
+      uint8_t* dev_mask = (uint8_t*)c.workspace + h->off_mask;
+      if (hipMemcpyAsync(dev_mask, h->mask_pinned, mask.size(), hipMemcpyHostToDevice, st) != hipSuccess) return PASTA_E_DEVICE;
+      if (hipEventRecord(h->mask_ev, st) != hipSuccess) return PASTA_E_DEVICE;
+      h->mask_ev_used = true;
+      p.dense_mask = dev_mask;
     }
     if (blob.size() <= (size_t)kInlineMetaWords) {  // small plan: rides in the kernel arguments
       p.meta = nullptr;

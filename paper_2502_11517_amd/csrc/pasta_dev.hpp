@@ -52,7 +52,8 @@ struct DevStream {      // one per decoding stream, call order
   int32_t item_end;
   int32_t gather_base;  // first entry of this stream in dbg_gather_rows
   int32_t pos;          // position id of the stream's query token (rotary embedding of Q)
-  int32_t pad[2];
+  int32_t mask_base;    // dense-mask mode: this stream's mask bytes start here (one per slot of its request)
+  int32_t pad[1];
 };
 struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it
   int32_t start, count, stride, cum;
@@ -114,6 +115,7 @@ struct DecodeParams {
                         //    copies them turns them by pend_pos
   int32_t s_items[32];  // single_req with <= 16 streams: stream i's private items are
                         //   [s_items[2i], s_items[2i] + s_items[2i+1]) -- spares the merge a table look-up
+  const uint8_t* dense_mask;  // comparison mode: 0/1 per (stream, slot); null otherwise
   const double* rope_tab;  // theta^(-2f/D) / (2 pi), f < D/2 (device), when Q is rotated in the kernel
   int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
   DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way

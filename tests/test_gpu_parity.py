@@ -704,3 +704,89 @@ def test_trace_replay_matches_the_oracles_interpreter_and_dense_mask_attention(r
         else:
             assert np.array_equal(kb[:m], okp[:m])
     s.close()
+
+
+# ------------------------------------------------------------------------- comparison modes, multi-token steps
+@pytest.mark.parametrize("cfg", ["config2", "config4", "nested"])
+def test_no_share_and_dense_mask_modes_give_the_same_results(cfg):
+    """PASTA_DECODE_NO_SHARE (every stream reads its whole visible set itself) and
+    PASTA_DECODE_DENSE_MASK (every stream walks all slots of its request under a 0/1 mask, the
+    formulation the paper's own implementation uses) are other ways to the same numbers."""
+    if cfg == "nested":
+        ev_s, ev_p = W.random_fork_history(41, n_slots=600, max_streams=7, p_fork=0.02, p_retire=0.0)
+        n_streams = int(ev_s.max()) + 1
+        w = W.Workload(name="nested", dtype="bf16", Hq=16, Hkv=4, D=128, scale=1.0, seed=43, max_requests=1,
+                       pool_tokens=640, max_streams=n_streams, k_std=128 ** -0.5)
+        w.ev_request = np.zeros(len(ev_s), np.int32)
+        w.ev_stream, w.ev_parent, w.n_prefill = ev_s, ev_p, len(ev_s)
+        w.dec_request = np.zeros(n_streams, np.int32)
+        w.dec_stream = np.arange(n_streams, dtype=np.int32)
+        explicit = False
+    else:
+        w = getattr(W, cfg)() if cfg == "config2" else W.config4(n_requests=5, seed=12, pmin=100, pmax=700)
+        explicit = True
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    base, _, _ = s.decode(0, explicit=explicit)
+    base = _out64(w, base)
+    if explicit:
+        ref, _ = op.attention(0)
+        check_close(base, ref, w.dtype, "lists")
+    for flag, name in ((B.DECODE_NO_SHARE, "no share"), (B.DECODE_DENSE_MASK, "dense mask")):
+        out, lse, _ = s.decode(0, explicit=explicit, flags=flag)
+        got = _out64(w, out)
+        assert np.all(np.isfinite(got))
+        check_close(got, base, w.dtype, name + " vs lists")      # two roundings apart at most
+        if explicit:
+            check_close(got, ref, w.dtype, name + " vs oracle")
+    s.close()
+
+
+def test_dense_mask_mode_handles_blocks_and_items_in_which_a_stream_sees_nothing():
+    """A fork that starts right after a long stretch it cannot see: whole blocks, and whole work
+    items, of its dense walk are masked out (running max still -inf when they end)."""
+    w = W.single_request("gap", "bf16", 8, 2, 128, 1.0, 9, 40, [700, 3], "round_robin", k_std=128 ** -0.5)
+    # make stream 2's own rows come last, after ~700 rows of stream 1 that it must not see
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    ref, _ = op.attention(0)
+    for flag in (0, B.DECODE_DENSE_MASK, B.DECODE_NO_SHARE):
+        out, _, _ = s.decode(0, flags=flag)
+        check_close(_out64(w, out), ref, w.dtype, f"flag {flag}")
+    s.close()
+
+
+def test_several_query_tokens_of_one_stream_in_one_step():
+    """causal_skip: a stream feeds a chunk of k rows and gets k outputs in one step, query j seeing
+    the chunk up to its own row; together with one-token streams of the same request."""
+    from paper_2502_11517_amd.harness import to_device
+    w = W.single_request("chunk", "bf16", 16, 4, 128, 1.0, 13, 300, [50, 20], "round_robin", k_std=128 ** -0.5)
+    n0 = w.n_prefill
+    s = _session(w, max_streams=8)  # a step holds at most max_requests * max_streams query tokens
+    op = OraclePool(w).append_events(n0)
+    s.append_events(n0)
+    # stream 1 appends a chunk of 5 more rows (K/V rows: reuse the generator's rows [0, 5))
+    k5, v5 = w.kv_rows(0, 5)
+    s.h.append_kv(0, [0] * 5, [1] * 5, to_device(k5, w.dtype, s.device), to_device(v5, w.dtype, s.device))
+    tail = np.zeros(1, np.int64); tail[0] = n0
+    assert oracle.append(op.g, op.k, op.v, [0] * 5, k5, v5, op.tail)[0] == 0
+    pl, offs, st, ct, sd = w.lists(0)
+    i1 = int(np.nonzero(w.dec_stream == 1)[0][0])
+    i2 = int(np.nonzero(w.dec_stream == 2)[0][0])
+    rng = np.random.default_rng(3)
+    q = W.f32_to_bf16_bits(rng.standard_normal((6, w.Hq, w.D)).astype(np.float32))
+    qd = to_device(q, w.dtype, s.device)
+    out = torch.empty_like(qd)
+    s.h.decode_step(0, [0] * 6, [1, 1, 1, 1, 1, 2], qd, out, causal_skip=[4, 3, 2, 1, 0, 0])
+    got = _out64(w, out)
+    base1 = (int(pl[i1]), st[offs[i1]:offs[i1 + 1]].tolist(), ct[offs[i1]:offs[i1 + 1]].tolist(), sd[offs[i1]:offs[i1 + 1]].tolist())
+    for j in range(5):  # query j of the chunk: the old list plus the chunk's rows n0 .. n0 + j
+        lists = ([base1[0]], [0, len(base1[1]) + 1], base1[1] + [n0], base1[2] + [j + 1], base1[3] + [1])
+        ref, _ = oracle.attention(op.g, op.k, op.v, [0], *lists, q[j:j + 1], w.scale)
+        check_close(got[j], ref[0], w.dtype, f"chunk token {j}")
+    lists2 = ([int(pl[i2])], [0, offs[i2 + 1] - offs[i2]], st[offs[i2]:offs[i2 + 1]], ct[offs[i2]:offs[i2 + 1]], sd[offs[i2]:offs[i2 + 1]])
+    ref, _ = oracle.attention(op.g, op.k, op.v, [0], *lists2, q[5:6], w.scale)
+    check_close(got[5], ref[0], w.dtype, "the other stream")
+    s.close()

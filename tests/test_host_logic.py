@@ -186,9 +186,9 @@ def test_explicit_list_validation():
         with pytest.raises(B.PastaError) as e:
             _plan(h, [0], [1], lists)
         assert e.value.code == B.E_INVAL, lists
-    with pytest.raises(B.PastaError) as e:  # the same (request, stream) twice
-        _plan(h, [0, 0], [1, 1], ([10, 10], [0, 0, 0], [], [], []))
-    assert e.value.code == B.E_INVAL
+    # the same (request, stream) twice is fine with explicit lists (several query tokens of one stream)
+    goffs, _ = _plan(h, [0, 0], [1, 1], ([10, 11], [0, 0, 0], [], [], []))
+    assert goffs.tolist() == [0, 10, 21]
     with pytest.raises(B.PastaError) as e:  # maintained mode, stream never opened
         _plan(h, [0], [2])
     assert e.value.code == B.E_STATE
@@ -361,4 +361,38 @@ def test_replay_plan_equals_the_oracles_interpreter(seed):
     with pytest.raises(B.PastaError) as e:                     # too few rows in the caller's arrays
         h.replay(0, ops, n_prompt, len(toks) - 1, flags=B.REPLAY_PLAN_ONLY)
     assert e.value.code == B.E_CAPACITY
+    h.destroy()
+
+
+def test_comparison_flags_and_causal_skip_argument_checks():
+    cfg = B.make_config("bf16", 8, 2, 128, 1.0, max_streams=4, pool_tokens=1024)
+    h = B.PastaAttn(cfg, FAKE, FAKE, FAKE, B.query_workspace_bytes(cfg))
+    h.append_kv(0, [0] * 300, [0] * 300, None, None, flags=B.APPEND_RESERVE_ONLY)
+    h.append_kv(0, [0], [1], None, None, parent_stream=[0], flags=B.APPEND_RESERVE_ONLY)
+    h.append_kv(0, [0] * 4, [1] * 4, None, None, flags=B.APPEND_RESERVE_ONLY)
+    plan = np.zeros(8, np.int64)
+    h.decode_step(0, [0, 0], [0, 1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY, dbg_plan=plan)
+    assert plan[5] == 300 and plan[1] > 0                      # a shared prefix of 300 rows
+    for flag in (B.DECODE_NO_SHARE, B.DECODE_DENSE_MASK):
+        h.decode_step(0, [0, 0], [0, 1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY | flag, dbg_plan=plan)
+        assert plan[5] == 0 and plan[1] == 0
+    goffs = np.zeros(3, np.int64)
+    h.decode_step(0, [0, 0], [0, 1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY | B.DECODE_DENSE_MASK, dbg_gather_offsets=goffs)
+    assert goffs.tolist() == [0, 305, 610]                     # every stream walks all 305 slots
+    with pytest.raises(B.PastaError) as e:                     # dense masks are for the matrix-core kernel
+        h.decode_step(0, [0], [0], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY | B.DECODE_DENSE_MASK | B.DECODE_NO_MFMA)
+    assert e.value.code == B.E_INVAL
+    # one stream twice needs causal_skip
+    with pytest.raises(B.PastaError) as e:
+        h.decode_step(0, [0, 0], [1, 1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY)
+    assert e.value.code == B.E_INVAL
+    h.decode_step(0, [0] * 3, [1, 1, 1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY, causal_skip=[2, 1, 0], dbg_gather_offsets=(g4 := np.zeros(4, np.int64)))
+    assert np.diff(g4).tolist() == [303, 304, 305]
+    for skip in ([-1, 0, 0], [306, 0, 0]):                     # negative, or nothing left to see
+        with pytest.raises(B.PastaError) as e:
+            h.decode_step(0, [0] * 3, [1, 1, 1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY, causal_skip=skip)
+        assert e.value.code == B.E_INVAL
+    with pytest.raises(B.PastaError) as e:                     # not with explicit lists
+        h.decode_step(0, [0], [1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY, causal_skip=[0], lists=([5], [0, 0], [], [], []))
+    assert e.value.code == B.E_INVAL
     h.destroy()
