@@ -134,7 +134,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     pend0 = it.pend0;
     pend_src0 = it.pend_src0;
     listed = it.n_ranges > 1;
-    if (p.dense_mask) {  // comparison mode: the list is [0, tail), what may be seen is in the mask
+    if (ROPE && p.dense_mask) {  // comparison mode: the list is [0, tail), what may be seen is in the mask
       const int mb = meta_word(p, p.off_streams + it.stream * (int)(sizeof(DevStream) / 4) +
                                       (int)(__builtin_offsetof(DevStream, mask_base) / 4));
       for (int j = tid; j < kGatherMax; j += kAttnThreads)
@@ -321,7 +321,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       const double __attribute__((address_space(4)))* tab_b =
           (const double __attribute__((address_space(4)))*)(p.rope_tab + kRopeTabFactorB);
       u32x4 o_lo = u32x4{0u, 0u, 0u, 0u}, o_hi = o_lo;  // rows past R stay zero
-      if (8 * w < R) {  // wave-uniform: a wave whose eight rows are all past R has nothing to turn
+      if (!p.rope_q) {  // this kernel was chosen for one of its other features: Q goes in as it is
+        o_lo = q_lo;
+        o_hi = q_hi;
+      } else if (8 * w < R) {  // wave-uniform: a wave whose eight rows are all past R has nothing to turn
         const double pa = (double)q_pos * q_fa;
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
@@ -398,7 +401,9 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     if constexpr (!first.value) {
       if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
     }
-    if (p.pend_rope) fixup_block(b);
+    if constexpr (ROPE) {
+      if (p.pend_rope) fixup_block(b);
+    }
 
     // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
     f32x16 S, S1;  // two accumulation chains (even / odd steps) halve the dependent-MFMA latency
@@ -419,7 +424,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block
     const int tok0 = b * kBlock + 4 * hh;
     uint32_t mk[4] = {~0u, ~0u, ~0u, ~0u};  // one byte per token: tokens tok0 + 8 k .. + 3 in mk[k]
-    if constexpr (GATHER) {
+    if constexpr (GATHER && ROPE) {
       if (p.dense_mask) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) mk[k] = *reinterpret_cast<const uint32_t*>(&lds.mask[(tok0 + 8 * k) & (kGatherMax - 1)]);
@@ -536,6 +541,9 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 
 // One launch for all partials of a decode step with at most 32 stacked rows per request;
 // the shared-prefix items' work-groups come first, the private (gather) items' after them.
+// ROPE = the variant with the less common features compiled in: rotation of Q (p.rope_q), of the
+// keys of a deferred rotating append (p.pend_rope), the dense-mask comparison mode
+// (p.dense_mask).  The plain variant carries none of that code.
 template <bool PAGED, bool ROPE>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   __shared__ AttnLds lds;
@@ -544,8 +552,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   // plane f = 8 a + b turns by position * fa[a] * fb[b]; a is tid % 8 wherever a thread turns a
   // piece, so its a-factor is fetched here, before everything else; the b-factors are scalars.
   double fa_lane = 0.0;
-  if (ROPE || p.pend_rope) fa_lane = p.rope_tab[kRopeTabFactorA + (threadIdx.x & 7)];
-  if (p.pend_rope && threadIdx.x < 32) lds.pend_pos[threadIdx.x] = pend_pos_of(p)[threadIdx.x];  // published by the Q barrier
+  if constexpr (ROPE) {
+    if (p.rope_tab) fa_lane = p.rope_tab[kRopeTabFactorA + (threadIdx.x & 7)];
+    if (p.pend_rope && threadIdx.x < 32) lds.pend_pos[threadIdx.x] = pend_pos_of(p)[threadIdx.x];  // published by the Q barrier
+  }
   if (p.pend_n > 0) {
     // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads
     // those pool rows -- lists that name them are served from k_pend / v_pend -- so the copy
@@ -558,7 +568,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
       const int u = is_v ? t - total / 2 : t;
       const int row = u / pieces, gh = (u % pieces) >> 4, pc16 = u & 15;
       u32x4 val = reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
-      if (p.pend_rope && !is_v) {  // a rotating append: K is turned on its way into the pool
+      if (ROPE && p.pend_rope && !is_v) {  // a rotating append: K is turned on its way into the pool
         const u32x4 par = reinterpret_cast<const u32x4*>(p.k_pend)[u ^ 8];
         const uint32_t own[4] = {val[0], val[1], val[2], val[3]}, pr[4] = {par[0], par[1], par[2], par[3]};
         const double __attribute__((address_space(4)))* tab_b =

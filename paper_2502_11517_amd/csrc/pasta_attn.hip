@@ -986,8 +986,11 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       return PASTA_E_DEVICE;
     if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
-      if (rope_q) {  // Q is rotated on its way into the kernel's LDS
-        p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
+      if (rope_q || p.pend_rope || dense) {  // the variant that carries these features
+        if (rope_q) {  // Q is rotated on its way into the kernel's LDS
+          p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
+          p.rope_q = 1;
+        }
         if (h->lay.paged) k_attn<true, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
         else k_attn<false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
       } else {

@@ -111,6 +111,7 @@ struct DecodeParams {
   int pend_n;           // rows of the deferred append (0: none)
   int32_t pend_dst[32]; // their physical rows
   int32_t pend_pos[32]; // their position ids, when pend_rope
+  int rope_q;           // 1: Q rows are turned by their streams' position ids on the way into the kernel
   int pend_rope;        // 1: the deferred K rows are still unrotated (PASTA_APPEND_ROPE): whoever reads or
                         //    copies them turns them by pend_pos
   int32_t s_items[32];  // single_req with <= 16 streams: stream i's private items are
