@@ -222,11 +222,11 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       const int j = min(b * kBlock + r, n_tok - 1);
       off[i] = src_of(j, pnd[i]) + (piece ^ (r & 15)) * 16;
     }
+    // all of K first: S = K Q^T can start while V is still on its way
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      load_to_lds16((pnd[i] ? kpend : kb) + off[i], ktw + 64 * i);
-      load_to_lds16((pnd[i] ? vpend : vb) + off[i], vtw + 64 * i);
-    }
+    for (int i = 0; i < 8; ++i) load_to_lds16((pnd[i] ? kpend : kb) + off[i], ktw + 64 * i);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) load_to_lds16((pnd[i] ? vpend : vb) + off[i], vtw + 64 * i);
   };
   // Deferred rows of a rotating append (PASTA_APPEND_DEFER | PASTA_APPEND_ROPE) arrive unrotated
   // from k_pend: once a block is in the tile, its deferred rows are turned in place -- the 16
@@ -382,9 +382,9 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 
   auto compute_block = [&](int b, auto first) {
     if constexpr (first.value) {
-      // the first block was loaded straight into the tile: done once only the second block's
-      // 16 register loads (if any) are still outstanding
-      if (has2) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      // the first block was loaded straight into the tile, K before V: K is there once only V's 8
+      // loads and the second block's 16 register loads (if any) are still outstanding
+      if (has2) wait_vmcnt<24>(); else wait_vmcnt<8>();
       PASTA_CLK(3);
     } else {
       // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
@@ -455,6 +455,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
+    }
+    if constexpr (first.value) {  // now V of the block loaded straight into the tile is needed
+      if (has2) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     // P^T as B operand: contraction step ks holds registers 8 ks .. 8 ks + 7
     bf16x8 Pb[2];
