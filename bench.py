@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
     ap.add_argument("--eager-append", action="store_true",
                     help="run the KV-append as a launch of its own instead of letting it ride with the decode launch")
+    ap.add_argument("--streams", type=int, default=8, help="config 3 with another number of decoding streams (side measurement)")
+    ap.add_argument("--prefix", type=int, default=8192, help="config 3 with another shared-prefix length (side measurement)")
     ap.add_argument("--no-share", action="store_true",
                     help="comparison: no shared-prefix items, every stream reads its whole visible set itself")
     ap.add_argument("--dense-mask", action="store_true",
@@ -78,7 +80,7 @@ def main():
         return decode_only(args, getattr(W, args.workload)(), dev)
     L = args.layers
     tokens = -(-args.steps // L)  # token steps needed
-    w = W.config3(steps=max(tokens, 2))
+    w = W.config3(steps=max(tokens, 2), prefix=args.prefix, n_streams=args.streams)
     layout = B.HEAD_MAJOR if args.layout == "head" else B.TOKEN_MAJOR
     theta = 10000.0
     s = Session(w, kv_layout=layout, n_layers=L, rope_theta=theta if args.rope else 0.0)
@@ -203,8 +205,8 @@ def main():
             reps += 1
         cpu = {"value": w.n * reps / t_cpu, "unit": "stream-tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle",
-               "sample": f"{reps} decode steps (8 streams x 32 heads, {ne} pool rows) of one layer, fp64, "
-                         f"{t_cpu:.1f} s; append not included (a 32 KiB copy)"}
+               "sample": f"{reps} decode steps ({w.n} streams x 32 heads, {ne} pool rows) of one layer, fp64, "
+                         f"{t_cpu:.1f} s; append not included (a {w.n * 4} KiB copy)"}
         chk = torch.empty(w.n, w.Hq, w.D, dtype=torch.bfloat16, device=dev)
         s.h.decode_step(0, w.dec_request, w.dec_stream, q_steps[last], chk, lists=lists, flags=flags,
                         position=q_pos[last])
@@ -232,7 +234,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "config 3: bf16 32q/8kv heads D=128, prefix 8192, 8 streams L~U[64,512] "
+        "config": {"workload": f"config 3: bf16 32q/8kv heads D=128, prefix {args.prefix}, {args.streams} streams L~U[64,512] "
                                "right-aligned round-robin, append+decode per step",
                    "n_layers_cycled": L, "kv_layout": args.layout, "visibility": "maintained lists",
                    "append": "eager (own launch)" if (args.eager_append or args.rope) else "deferred (rides with the decode launch)",

@@ -123,7 +123,13 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     const int item = wi / p.Hkv;
     g = wi % p.Hkv;
     const DevItem it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item];
-    req = it.req;
+    if (p.single_req) {  // scalars from the kernel arguments
+      req = p.req0.req; pend0 = p.req0.pend0; pend_src0 = p.req0.pend_src0;
+    } else {
+      const int qi = reinterpret_cast<const DevStream*>(meta + p.off_streams)[it.stream].req_idx;
+      const DevReq rq = reinterpret_cast<const DevReq*>(meta + p.off_reqs)[qi];
+      req = rq.req; pend0 = rq.pend0; pend_src0 = rq.pend_src0;
+    }
     R = G;
     q_stream = it.stream;
     n_tok = it.tok_count;
@@ -131,8 +137,6 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     stride = it.stride;
     part_row0 = p.priv_part_base + (long long)(item * p.Hkv + g) * G;
     gather_pos = it.gather_pos;
-    pend0 = it.pend0;
-    pend_src0 = it.pend_src0;
     listed = it.n_ranges > 1;
     if (ROPE && p.dense_mask) {  // comparison mode: the list is [0, tail), what may be seen is in the mask
       const int mb = meta_word(p, p.off_streams + it.stream * (int)(sizeof(DevStream) / 4) +

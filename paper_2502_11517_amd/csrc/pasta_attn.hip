@@ -829,11 +829,9 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         int32_t rlast = rcur;
         while (rlast + 1 < ds.range_end && ranges[rlast + 1].cum < t + it.tok_count) rlast++;
         it.n_ranges = rlast - rcur + 1;
-        it.req = q.req;
         it.gather_pos = (int32_t)(gather_total + q.pc + t);
         it.slot0 = ranges[rcur].start + (t - ranges[rcur].cum) * ranges[rcur].stride;
         it.stride = it.n_ranges == 1 ? ranges[rcur].stride : 0;  // 0: rows come from the expanded list
-        it.pend0 = INT32_MAX;
         items.push_back(it);
       }
       ds.item_end = (int32_t)items.size();
@@ -910,7 +908,6 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     if (take_pending) {
       const pasta_attn::Pending& pd = h->pending;
       for (auto& q : reqs) { q.pend0 = pd.req_pend0[q.req]; q.pend_src0 = pd.req_src0[q.req]; }
-      for (auto& it : items) { it.pend0 = pd.req_pend0[it.req]; it.pend_src0 = pd.req_src0[it.req]; }
       p.k_pend = pd.k_new;
       p.v_pend = pd.v_new;
       p.pend_n = pd.n_rows;
@@ -920,9 +917,8 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         std::memcpy(p.pend_pos, pd.pos, sizeof(p.pend_pos));
         p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
       }
-      // the blob was built before these fields were known: patch the two tables in place
+      // the blob was built before these fields were known: patch the table in place
       std::memcpy(blob.data() + p.off_reqs, reqs.data(), reqs.size() * sizeof(DevReq));
-      std::memcpy(blob.data() + p.off_items, items.data(), items.size() * sizeof(DevItem));
     }
     if (dense) {  // the masks travel like the paper's mask tensors: host -> device, every step
       if (!h->mask_pinned) {

@@ -62,14 +62,10 @@ struct DevItem {        // a chunk of one stream's private token list
   int32_t stream, tok_begin, tok_count;
   int32_t range_first;  // the range that holds token tok_begin
   int32_t n_ranges;     // ranges the chunk overlaps
-  int32_t req;          // request of the stream
   int32_t gather_pos;   // first entry of this chunk in dbg_gather_rows
   int32_t slot0;        // n_ranges == 1: token j of the chunk is logical slot slot0 + j*stride
   int32_t stride;
-  int32_t pend0;        // slots >= pend0 of the request are rows of a deferred append: slot t
-  int32_t pend_src0;    //   is row pend_src0 + (t - pend0) of k_pend / v_pend (pend0 = INT_MAX: none)
-  int32_t pad;
-};
+};                      // (8 words: the request and its deferred rows are found through the stream's DevReq)
 struct DevReq {         // one per request present in the call
   int32_t req;
   int32_t pc;           // common prefix handled by the shared-prefix kernel
