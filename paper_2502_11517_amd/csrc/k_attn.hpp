@@ -594,6 +594,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   }
   // shared-prefix items first: they are the longer ones (up to two blocks per wave against one)
   const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
+  // the longer items issue their loads first where a SIMD holds a wave of each kind
+  if ((int)blockIdx.x < n_prefix_wgs) __builtin_amdgcn_s_setprio(3);
   if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, ROPE>(p, lds, meta, blockIdx.x, fa_lane);
   else attn_item<PAGED, true, ROPE>(p, lds, meta, blockIdx.x - n_prefix_wgs, fa_lane);
 }
