@@ -564,20 +564,21 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
     if (p.rope_tab) fa_lane = p.rope_tab[kRopeTabFactorA + (threadIdx.x & 7)];
     if (p.pend_rope && threadIdx.x < 32) lds.pend_pos[threadIdx.x] = pend_pos_of(p)[threadIdx.x];  // published by the Q barrier
   }
-  if (p.pend_n > 0) {
-    // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads
-    // those pool rows -- lists that name them are served from k_pend / v_pend -- so the copy
-    // needs no ordering against the rest of the launch.
-    const int pieces = p.Hkv * 16;  // 16-byte pieces per row
-    const int total = 2 * p.pend_n * pieces;
-    const int32_t* dst = pend_dst_of(p);
-    for (int t = blockIdx.x * kAttnThreads + threadIdx.x; t < total; t += gridDim.x * kAttnThreads) {
-      const bool is_v = t >= total / 2;
-      const int u = is_v ? t - total / 2 : t;
-      const int row = u / pieces, gh = (u % pieces) >> 4, pc16 = u & 15;
-      u32x4 val = reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
-      if (ROPE && p.pend_rope && !is_v) {  // a rotating append: K is turned on its way into the pool
-        const u32x4 par = reinterpret_cast<const u32x4*>(p.k_pend)[u ^ 8];
+  // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads those
+  // pool rows -- lists that name them are served from k_pend / v_pend -- so the copy needs no
+  // ordering against the rest of the launch.  Normally it is spread thin: work-group b moves
+  // the 16 pieces of one (row, kv head) of K or V with its first 16 threads, which fetch them
+  // here, carry them through their item, and store them at the very end -- nobody waits for it.
+  u32x4 pend_val = u32x4{0u, 0u, 0u, 0u}, pend_par = pend_val;
+  int pend_u = -1;  // this thread's piece of the copy, -1: none
+  const int pend_pieces = p.Hkv * 16;  // 16-byte pieces per row
+  const int pend_total = 2 * p.pend_n * pend_pieces;
+  auto pend_store = [&](int t, u32x4 val, u32x4 par) {
+    const bool is_v = t >= pend_total / 2;
+    const int u = is_v ? t - pend_total / 2 : t;
+    const int row = u / pend_pieces, gh = (u % pend_pieces) >> 4, pc16 = u & 15;
+    if constexpr (ROPE) {
+      if (p.pend_rope && !is_v) {  // a rotating append: K is turned on its way into the pool
         const uint32_t own[4] = {val[0], val[1], val[2], val[3]}, pr[4] = {par[0], par[1], par[2], par[3]};
         const double __attribute__((address_space(4)))* tab_b =
             (const double __attribute__((address_space(4)))*)(p.rope_tab + kRopeTabFactorB);
@@ -588,8 +589,30 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
         rope_piece_bf16_factored(own, pr, rot, pc16 >= 8, pend_pos_of(p)[row], fa_lane, fb);  // pc16 % 8 == tid % 8
         val = u32x4{rot[0], rot[1], rot[2], rot[3]};
       }
-      char* base = reinterpret_cast<char*>(const_cast<void*>(is_v ? p.v : p.k));
-      *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, dst[row], gh) + pc16 * 8) * 2) = val;
+    }
+    char* base = reinterpret_cast<char*>(const_cast<void*>(is_v ? p.v : p.k));
+    *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, pend_dst_of(p)[row], gh) + pc16 * 8) * 2) = val;
+  };
+  auto pend_load = [&](int t, u32x4& val, u32x4& par) {
+    const bool is_v = t >= pend_total / 2;
+    const int u = is_v ? t - pend_total / 2 : t;
+    val = reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
+    if constexpr (ROPE) {
+      if (p.pend_rope && !is_v) par = reinterpret_cast<const u32x4*>(p.k_pend)[u ^ 8];
+    }
+  };
+  if (p.pend_n > 0) {
+    if (pend_total <= (int)gridDim.x * 16) {
+      if (threadIdx.x < 16 && (int)blockIdx.x * 16 < pend_total) {
+        pend_u = blockIdx.x * 16 + threadIdx.x;
+        pend_load(pend_u, pend_val, pend_par);
+      }
+    } else {  // few work-groups, many rows: all of it here and now
+      for (int t = blockIdx.x * kAttnThreads + threadIdx.x; t < pend_total; t += gridDim.x * kAttnThreads) {
+        u32x4 val, par = u32x4{0u, 0u, 0u, 0u};
+        pend_load(t, val, par);
+        pend_store(t, val, par);
+      }
     }
   }
   // shared-prefix items first: they are the longer ones (up to two blocks per wave against one)
@@ -598,6 +621,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   if ((int)blockIdx.x < n_prefix_wgs) __builtin_amdgcn_s_setprio(3);
   if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, ROPE>(p, lds, meta, blockIdx.x, fa_lane);
   else attn_item<PAGED, true, ROPE>(p, lds, meta, blockIdx.x - n_prefix_wgs, fa_lane);
+  if (pend_u >= 0) pend_store(pend_u, pend_val, pend_par);
 }
 
 }  // namespace pasta
