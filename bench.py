@@ -61,7 +61,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(sharding across GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(the path would shard by kv head, by request or by sequence; none of that is built)", file=sys.stderr)
         sys.exit(2)
 
     import torch
