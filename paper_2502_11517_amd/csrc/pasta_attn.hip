@@ -899,6 +899,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     int rc = ensure_device(h);
     if (rc != PASTA_OK) return rc;
     hipStream_t st = (hipStream_t)c.hip_stream;
+    int meta_slot = -1;  // pinned staging slot that this call's kernels read, if any
     // a deferred append rides along with the matrix-core launch of its layer; otherwise K1 runs now
     const bool take_pending = h->pending.active && mfma && h->pending.layer == a->layer;
     if (h->pending.active && !take_pending) {
@@ -941,10 +942,17 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       p.meta = nullptr;
       std::memcpy(p.inline_meta, blob.data(), blob.size() * 4);
     } else {
-      const int32_t* dev_meta = nullptr;
-      rc = upload_meta(h, blob.data(), blob.size() * 4, &dev_meta);
-      if (rc != PASTA_OK) return rc;
-      p.meta = dev_meta;
+      // large plan: it stays in pinned host memory and the kernels read it in place -- each
+      // work-group touches a few dozen bytes of it, and a copy-engine transfer ahead of the
+      // attention launch costs tens of microseconds on the stream (config 4: 97 -> 61 us per
+      // step).  The slot is reused only after the launches that read it have completed.
+      if (blob.size() * 4 > h->meta_bytes) return PASTA_E_CAPACITY;
+      meta_slot = h->ring_next;
+      h->ring_next = (meta_slot + 1) % kRing;
+      if (h->ring_used[meta_slot] && hipEventSynchronize(h->ring_ev[meta_slot]) != hipSuccess) return PASTA_E_DEVICE;
+      char* host = h->pinned + (size_t)meta_slot * h->meta_bytes;
+      std::memcpy(host, blob.data(), blob.size() * 4);
+      p.meta = (const int32_t*)host;
     }
     p.k = (const char*)c.k_pool + (size_t)a->layer * h->layer_elems * h->elem;
     p.v = (const char*)c.v_pool + (size_t)a->layer * h->layer_elems * h->elem;
@@ -1011,6 +1019,10 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       return PASTA_E_DEVICE;
     rc = launch_merge(h, dim3((unsigned)n * c.n_q_heads), st, p);
     if (rc != PASTA_OK) return rc;
+    if (meta_slot >= 0) {
+      if (hipEventRecord(h->ring_ev[meta_slot], st) != hipSuccess) return PASTA_E_DEVICE;
+      h->ring_used[meta_slot] = true;
+    }
     if (hipGetLastError() != hipSuccess) return PASTA_E_DEVICE;
     return PASTA_OK;
   } catch (const std::bad_alloc&) {
