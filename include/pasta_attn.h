@@ -152,8 +152,9 @@ enum {
                                     per append + decode step; ignored for more than 32 rows. */
   PASTA_APPEND_ROPE = 4u         /* rotate every K row by position[i] on its way into the
                                     pool (needs position != NULL and rope_theta > 0; not
-                                    with RESERVE_ONLY).  Combined with DEFER the copy is not
-                                    deferred: it runs as a launch of its own now. */
+                                    with RESERVE_ONLY).  Combines with DEFER: the rows are then
+                                    turned by the small launch that a decode_step with
+                                    rotations puts ahead of its attention launch. */
 };
 
 typedef struct {

@@ -38,7 +38,6 @@
 #pragma once
 #include <type_traits>
 
-#include "k_rope.hpp"
 #include "mfma_util.hpp"
 
 namespace pasta {
@@ -54,7 +53,6 @@ struct AttnLds {
   AttnTile tile[4];           // first member: wave w's area starts at byte w * 16 KB
   u32x4 q[32 * 16];            // stacked Q rows, same swizzle (rows >= R are zero)
   float mw[4][32], lw[4][32];  // per-wave row max / row sum at the end of the item
-  int pend_pos[32];            // position ids of the rows of a deferred rotating append
   uint8_t mask[kGatherMax];    // dense-mask comparison mode: the item's slice of its stream's mask
   int rows[kGatherMax];        // listed gather items: row code of every token
   DevRange ranges[kGatherMax]; // listed gather items: the ranges the item overlaps
@@ -62,9 +60,8 @@ struct AttnLds {
 
 struct BlockRegs { u32x4 k[8], v[8]; };  // one lane's share of a 32-token block
 
-template <bool PAGED, bool GATHER, bool ROPE>
-__device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi,
-                                          double fa_lane) {  // fa_lane: rotary a-factor of plane group tid % 8
+template <bool PAGED, bool GATHER, bool DENSE>
+__device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -138,7 +135,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     part_row0 = p.priv_part_base + (long long)(item * p.Hkv + g) * G;
     gather_pos = it.gather_pos;
     listed = it.n_ranges > 1;
-    if (ROPE && p.dense_mask) {  // comparison mode: the list is [0, tail), what may be seen is in the mask
+    if (DENSE && p.dense_mask) {  // comparison mode: the list is [0, tail), what may be seen is in the mask
       const int mb = meta_word(p, p.off_streams + it.stream * (int)(sizeof(DevStream) / 4) +
                                       (int)(__builtin_offsetof(DevStream, mask_base) / 4));
       for (int j = tid; j < kGatherMax; j += kAttnThreads)
@@ -232,68 +229,12 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 #pragma unroll
     for (int i = 0; i < 8; ++i) load_to_lds16((pnd[i] ? vpend : vb) + off[i], vtw + 64 * i);
   };
-  // Deferred rows of a rotating append (PASTA_APPEND_DEFER | PASTA_APPEND_ROPE) arrive unrotated
-  // from k_pend: once a block is in the tile, its deferred rows are turned in place -- the 16
-  // lanes that own a row read their piece and the piece 64 elements away, then write theirs
-  // back (all reads of the wave precede its writes).
-  auto pend_index = [&](int j) -> int {  // row of token j in k_pend, or -1: it comes from the pool
-    const int t = slot0 + j * stride;
-    int pidx = t >= pend0 ? pend_src0 + (t - pend0) : -1;
-    if constexpr (GATHER) {
-      if (listed) { const int code = lds.rows[j]; pidx = code < 0 ? -1 - code : -1; }
-    }
-    return pidx;
-  };
-  auto fixup_block = [&](int b) {
-    bool anyp = false;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) anyp |= pend_index(min(b * kBlock + rbase + 4 * i, n_tok - 1)) >= 0;
-    if (!__any(anyp)) return;
-    const double __attribute__((address_space(4)))* tab_b =
-        (const double __attribute__((address_space(4)))*)(p.rope_tab + kRopeTabFactorB);
-    double fb[8];  // the same for every lane: scalar loads
-#pragma unroll
-    for (int k = 0; k < 8; ++k) fb[k] = tab_b[k];
-#pragma unroll 1
-    for (int i = 0; i < 8; ++i) {
-      const int r = rbase + 4 * i;
-      const int pidx = pend_index(min(b * kBlock + r, n_tok - 1));
-      if (pidx < 0) continue;
-      u32x4* mine = ktw + r * 16 + (piece ^ (r & 15));
-      const u32x4 o = *mine, q = ktw[r * 16 + ((piece ^ 8) ^ (r & 15))];
-      const uint32_t own[4] = {o[0], o[1], o[2], o[3]}, par[4] = {q[0], q[1], q[2], q[3]};
-      uint32_t rot[4];
-      rope_piece_bf16_factored(own, par, rot, piece >= 8, lds.pend_pos[pidx], fa_lane, fb);
-      *mine = u32x4{rot[0], rot[1], rot[2], rot[3]};
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  };
   // ---- everything this wave needs first is requested here, before anything is waited for:
   // its share of the stacked Q rows (2 loads), its first block (16 loads into LDS), and its
   // second block (16 loads into registers).  Loads return in issue order, so Q is waited for
   // with the blocks still in flight.
-  // With the rotary option Q goes through registers instead: thread (row r = tid / 8, p = tid % 8)
-  // fetches pieces p and p + 8 of its row -- both halves of the planes 8 p .. 8 p + 7 -- and,
-  // once the block loads have been issued, turns them by the stream's position id: one cos / sin
-  // per plane serves both pieces.
-  const char* qg = reinterpret_cast<const char*>(p.q);
-  const int qr = tid >> 3, qp = tid & 7;  // ROPE: this thread's row and plane group
-  u32x4 q_lo = u32x4{0u, 0u, 0u, 0u}, q_hi = q_lo;
-  int q_pos = 0;
-  double q_fa = 0.0;
-  if constexpr (ROPE) {
-    if (qr < R) {
-      const int ra = row0 + qr;  // row of the request's stack
-      const int s = GATHER ? q_stream : (req_streams ? req_streams[ra / G] : ra / G);
-      const char* row = qg + ((long long)s * p.Hq + (g * G + ra % G)) * 256;
-      q_lo = *reinterpret_cast<const u32x4*>(row + qp * 16);
-      q_hi = *reinterpret_cast<const u32x4*>(row + (qp + 8) * 16);
-      q_pos = meta_word(p, p.off_streams + s * (int)(sizeof(DevStream) / 4) + (int)(__builtin_offsetof(DevStream, pos) / 4));
-      q_fa = fa_lane;
-    }
-  } else {
+  {
+    const char* qg = reinterpret_cast<const char*>(p.q);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {  // wave w fills pieces [128 w + 64 i, + 64) of lds.q: rows 8 w + 4 i + rbase
       const int r = 8 * w + 4 * i + rbase;
@@ -317,42 +258,8 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     if constexpr (h1.value) dma_block(w);
     if constexpr (h2.value) load_block(br, w + 4);
     PASTA_CLK(1);
-    if constexpr (ROPE) {
-      // nothing of the rotation may be scheduled above the K/V loads (it would wait for Q there)
-      __builtin_amdgcn_sched_barrier(0);
-      asm volatile("" : "+v"(q_pos), "+v"(q_fa), "+v"(q_lo), "+v"(q_hi));
-      // the eight b-factors are the same for every lane: scalar loads from read-only memory
-      const double __attribute__((address_space(4)))* tab_b =
-          (const double __attribute__((address_space(4)))*)(p.rope_tab + kRopeTabFactorB);
-      u32x4 o_lo = u32x4{0u, 0u, 0u, 0u}, o_hi = o_lo;  // rows past R stay zero
-      if (!p.rope_q) {  // this kernel was chosen for one of its other features: Q goes in as it is
-        o_lo = q_lo;
-        o_hi = q_hi;
-      } else if (8 * w < R) {  // wave-uniform: a wave whose eight rows are all past R has nothing to turn
-        const double pa = (double)q_pos * q_fa;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-          float lo_r[2], hi_r[2];
-#pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            const float x = hf ? bf16_hi(q_lo[e2]) : bf16_lo(q_lo[e2]);
-            const float y = hf ? bf16_hi(q_hi[e2]) : bf16_lo(q_hi[e2]);
-            const double rev = pa * tab_b[2 * e2 + hf];
-            const float fr = (float)(rev - __builtin_floor(rev));
-            const float c = __builtin_amdgcn_cosf(fr), sn = __builtin_amdgcn_sinf(fr);
-            lo_r[hf] = x * c - y * sn;
-            hi_r[hf] = y * c + x * sn;
-          }
-          o_lo[e2] = (uint32_t)f32_to_bf16_rne(lo_r[0]) | ((uint32_t)f32_to_bf16_rne(lo_r[1]) << 16);
-          o_hi[e2] = (uint32_t)f32_to_bf16_rne(hi_r[0]) | ((uint32_t)f32_to_bf16_rne(hi_r[1]) << 16);
-        }
-      }
-      lds.q[qr * 16 + (qp ^ (qr & 15))] = o_lo;
-      lds.q[qr * 16 + ((qp + 8) ^ (qr & 15))] = o_hi;
-    } else {
-      // Q has landed once at most the block loads issued behind it are outstanding
-      wait_vmcnt<h2.value ? 32 : (h1.value ? 16 : 0)>();
-    }
+    // Q has landed once at most the block loads issued behind it are outstanding
+    wait_vmcnt<h2.value ? 32 : (h1.value ? 16 : 0)>();
   };
   if (has2) issue_blocks_finish_q(std::true_type{}, std::true_type{});
   else if (has1) issue_blocks_finish_q(std::true_type{}, std::false_type{});
@@ -405,9 +312,6 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     if constexpr (!first.value) {
       if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
     }
-    if constexpr (ROPE) {
-      if (p.pend_rope) fixup_block(b);
-    }
 
     // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
     f32x16 S, S1;  // two accumulation chains (even / odd steps) halve the dependent-MFMA latency
@@ -428,7 +332,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block
     const int tok0 = b * kBlock + 4 * hh;
     uint32_t mk[4] = {~0u, ~0u, ~0u, ~0u};  // one byte per token: tokens tok0 + 8 k .. + 3 in mk[k]
-    if constexpr (GATHER && ROPE) {
+    if constexpr (GATHER && DENSE) {
       if (p.dense_mask) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) mk[k] = *reinterpret_cast<const uint32_t*>(&lds.mask[(tok0 + 8 * k) & (kGatherMax - 1)]);
@@ -549,69 +453,42 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 
 // One launch for all partials of a decode step with at most 32 stacked rows per request;
 // the shared-prefix items' work-groups come first, the private (gather) items' after them.
-// ROPE = the variant with the less common features compiled in: rotation of Q (p.rope_q), of the
-// keys of a deferred rotating append (p.pend_rope), the dense-mask comparison mode
-// (p.dense_mask).  The plain variant carries none of that code.
-template <bool PAGED, bool ROPE>
+// DENSE = the variant that also carries the dense-mask comparison mode (p.dense_mask); the plain
+// variant has none of that code.
+template <bool PAGED, bool DENSE>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   __shared__ AttnLds lds;
   const int32_t* meta = meta_of(p);
-  // Rotary embedding inside this launch (of Q, or of the keys of a deferred rotating append):
-  // plane f = 8 a + b turns by position * fa[a] * fb[b]; a is tid % 8 wherever a thread turns a
-  // piece, so its a-factor is fetched here, before everything else; the b-factors are scalars.
-  double fa_lane = 0.0;
-  if constexpr (ROPE) {
-    if (p.rope_tab) fa_lane = p.rope_tab[kRopeTabFactorA + (threadIdx.x & 7)];
-    if (p.pend_rope && threadIdx.x < 32) lds.pend_pos[threadIdx.x] = pend_pos_of(p)[threadIdx.x];  // published by the Q barrier
-  }
   // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads those
   // pool rows -- lists that name them are served from k_pend / v_pend -- so the copy needs no
   // ordering against the rest of the launch.  Normally it is spread thin: work-group b moves
   // the 16 pieces of one (row, kv head) of K or V with its first 16 threads, which fetch them
   // here, carry them through their item, and store them at the very end -- nobody waits for it.
-  u32x4 pend_val = u32x4{0u, 0u, 0u, 0u}, pend_par = pend_val;
+  u32x4 pend_val = u32x4{0u, 0u, 0u, 0u};
   int pend_u = -1;  // this thread's piece of the copy, -1: none
   const int pend_pieces = p.Hkv * 16;  // 16-byte pieces per row
   const int pend_total = 2 * p.pend_n * pend_pieces;
-  auto pend_store = [&](int t, u32x4 val, u32x4 par) {
+  auto pend_store = [&](int t, u32x4 val) {
     const bool is_v = t >= pend_total / 2;
     const int u = is_v ? t - pend_total / 2 : t;
     const int row = u / pend_pieces, gh = (u % pend_pieces) >> 4, pc16 = u & 15;
-    if constexpr (ROPE) {
-      if (p.pend_rope && !is_v) {  // a rotating append: K is turned on its way into the pool
-        const uint32_t own[4] = {val[0], val[1], val[2], val[3]}, pr[4] = {par[0], par[1], par[2], par[3]};
-        const double __attribute__((address_space(4)))* tab_b =
-            (const double __attribute__((address_space(4)))*)(p.rope_tab + kRopeTabFactorB);
-        double fb[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) fb[k] = tab_b[k];
-        uint32_t rot[4];
-        rope_piece_bf16_factored(own, pr, rot, pc16 >= 8, pend_pos_of(p)[row], fa_lane, fb);  // pc16 % 8 == tid % 8
-        val = u32x4{rot[0], rot[1], rot[2], rot[3]};
-      }
-    }
     char* base = reinterpret_cast<char*>(const_cast<void*>(is_v ? p.v : p.k));
     *reinterpret_cast<u32x4*>(base + (elem_off(p.lay, pend_dst_of(p)[row], gh) + pc16 * 8) * 2) = val;
   };
-  auto pend_load = [&](int t, u32x4& val, u32x4& par) {
+  auto pend_load = [&](int t) -> u32x4 {
     const bool is_v = t >= pend_total / 2;
     const int u = is_v ? t - pend_total / 2 : t;
-    val = reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
-    if constexpr (ROPE) {
-      if (p.pend_rope && !is_v) par = reinterpret_cast<const u32x4*>(p.k_pend)[u ^ 8];
-    }
+    return reinterpret_cast<const u32x4*>(is_v ? p.v_pend : p.k_pend)[u];
   };
   if (p.pend_n > 0) {
     if (pend_total <= (int)gridDim.x * 16) {
       if (threadIdx.x < 16 && (int)blockIdx.x * 16 < pend_total) {
         pend_u = blockIdx.x * 16 + threadIdx.x;
-        pend_load(pend_u, pend_val, pend_par);
+        pend_val = pend_load(pend_u);
       }
     } else {  // few work-groups, many rows: all of it here and now
       for (int t = blockIdx.x * kAttnThreads + threadIdx.x; t < pend_total; t += gridDim.x * kAttnThreads) {
-        u32x4 val, par = u32x4{0u, 0u, 0u, 0u};
-        pend_load(t, val, par);
-        pend_store(t, val, par);
+        pend_store(t, pend_load(t));
       }
     }
   }
@@ -619,9 +496,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
   // the longer items issue their loads first where a SIMD holds a wave of each kind
   if ((int)blockIdx.x < n_prefix_wgs) __builtin_amdgcn_s_setprio(3);
-  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, ROPE>(p, lds, meta, blockIdx.x, fa_lane);
-  else attn_item<PAGED, true, ROPE>(p, lds, meta, blockIdx.x - n_prefix_wgs, fa_lane);
-  if (pend_u >= 0) pend_store(pend_u, pend_val, pend_par);
+  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE>(p, lds, meta, blockIdx.x);
+  else attn_item<PAGED, true, DENSE>(p, lds, meta, blockIdx.x - n_prefix_wgs);
+  if (pend_u >= 0) pend_store(pend_u, pend_val);
 }
 
 }  // namespace pasta

@@ -54,7 +54,8 @@ struct pasta_attn {
   std::vector<StreamState> streams;      // [max_requests * max_streams]
   // workspace carve-up (byte offsets)
   size_t off_page_table = 0, off_meta = 0, meta_bytes = 0, off_ml = 0, off_acc = 0;
-  size_t off_rope = 0, off_qrot = 0;  // rotary table (fp64, D/2 entries) and rotated-Q buffer (rope_theta > 0)
+  size_t off_rope = 0, off_qrot = 0, off_krot = 0;  // rope_theta > 0: rotary table (fp64, D/2 entries), rotated Q,
+                                                   // rotated K rows of a deferred append
   size_t off_mask = 0, mask_bytes = 0;  // dense-mask comparison mode: one byte per (stream, slot)
   uint8_t* mask_pinned = nullptr;       // its host staging, allocated at first use
   hipEvent_t mask_ev{};
@@ -148,9 +149,11 @@ void carve(pasta_attn* h) {
   }
   if (c.rope_theta > 0.f) {
     h->off_rope = off;
-    off += align_up((size_t)kRopeTabEntries * sizeof(double), 256);
+    off += align_up((size_t)(c.head_dim / 2) * sizeof(double), 256);
     h->off_qrot = off;
     off += align_up((size_t)c.max_requests * c.max_streams * c.n_q_heads * c.head_dim * h->elem, 256);
+    h->off_krot = off;
+    off += align_up((size_t)kAppendInline * c.n_kv_heads * c.head_dim * h->elem, 256);
   }
   h->cfg.workspace_bytes = off;
 }
@@ -171,13 +174,9 @@ int ensure_device(pasta_attn* h) {
   }
   if (h->cfg.rope_theta > 0.f) {  // theta^(-2f/D) / (2 pi) in fp64: angles are taken in revolutions
     const int D = h->cfg.head_dim;
-    const double two_pi = 6.283185307179586476925286766559, th = (double)h->cfg.rope_theta;
-    std::vector<double> tab(kRopeTabEntries, 0.0);
-    for (int f = 0; f < D / 2; ++f) tab[f] = std::pow(th, -2.0 * f / D) / two_pi;
-    for (int k = 0; k < 8; ++k) {  // f = 8 a + b (the attention kernel, D = 128)
-      tab[kRopeTabFactorA + k] = std::pow(th, -16.0 * k / D) / two_pi;
-      tab[kRopeTabFactorB + k] = std::pow(th, -2.0 * k / D);
-    }
+    std::vector<double> tab(D / 2);
+    for (int f = 0; f < D / 2; ++f)
+      tab[f] = std::pow((double)h->cfg.rope_theta, -2.0 * f / D) / 6.283185307179586476925286766559;
     if (hipMemcpy((char*)h->cfg.workspace + h->off_rope, tab.data(), tab.size() * sizeof(double),
                   hipMemcpyHostToDevice) != hipSuccess)
       return PASTA_E_DEVICE;
@@ -498,9 +497,7 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
     if (rc != PASTA_OK) return rc;
     rc = flush_pending(h);  // at most one deferred append is outstanding
     if (rc != PASTA_OK) return rc;
-    // (a deferred rotating append can only ride with the matrix-core kernel: bf16, D = 128)
-    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline &&
-                 (!rope || (c.dtype == PASTA_BF16 && c.head_dim == 128));
+    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline;
     std::vector<int32_t> p0, s0;
     if (defer) {  // rows of one request must be consecutive in the call: slot t <-> row src0 + (t - pend0)
       p0.assign(c.max_requests, INT32_MAX);
@@ -913,10 +910,9 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       p.v_pend = pd.v_new;
       p.pend_n = pd.n_rows;
       std::memcpy(p.pend_dst, pd.dst_rows, sizeof(p.pend_dst));
-      if (pd.rope) {
+      if (pd.rope) {  // turned by the small launch below, before the attention launch reads them
         p.pend_rope = 1;
         std::memcpy(p.pend_pos, pd.pos, sizeof(p.pend_pos));
-        p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
       }
       // the blob was built before these fields were known: patch the table in place
       std::memcpy(blob.data() + p.off_reqs, reqs.data(), reqs.size() * sizeof(DevReq));
@@ -986,15 +982,24 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     }
     p.req0 = reqs[0];
 
+    if (rope_q || p.pend_rope) {
+      // one small launch turns what has to be turned: Q into its buffer, the deferred K rows into theirs
+      p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
+      p.rope_q = rope_q ? 1 : 0;
+      uint4* q_rot = (uint4*)((char*)c.workspace + h->off_qrot);
+      uint4* k_rot = (uint4*)((char*)c.workspace + h->off_krot);
+      const int pph = D * h->elem / 16;
+      const long long nq = rope_q ? (long long)n * c.n_q_heads * pph : 0;
+      const long long nk = p.pend_rope ? (long long)p.pend_n * Hkv * pph : 0;
+      k_rope_prep<<<dim3((unsigned)((nq + nk + 255) / 256)), 256, 0, st>>>(p, q_rot, k_rot, pph, h->elem == 4, nq);
+      if (rope_q) p.q = q_rot;
+      if (p.pend_rope) { p.k_pend = k_rot; p.pend_rope = 0; }
+    }
     if (a->prof_event_start && hipEventRecord((hipEvent_t)a->prof_event_start, st) != hipSuccess)
       return PASTA_E_DEVICE;
     if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
-      if (rope_q || p.pend_rope || dense) {  // the variant that carries these features
-        if (rope_q) {  // Q is rotated on its way into the kernel's LDS
-          p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
-          p.rope_q = 1;
-        }
+      if (dense) {  // the variant that carries the dense-mask mode
         if (h->lay.paged) k_attn<true, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
         else k_attn<false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
       } else {
@@ -1003,14 +1008,6 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       }
       if (take_pending) h->pending.active = false;
     } else if (!items.empty()) {
-      if (rope_q) {  // the vector-ALU walker reads Q from a rotated copy
-        p.rope_tab = (const double*)((const char*)c.workspace + h->off_rope);
-        uint4* q_rot = (uint4*)((char*)c.workspace + h->off_qrot);
-        const int pph = D * h->elem / 16;
-        const long long total = (long long)n * c.n_q_heads * pph;
-        k_rope_q<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>(p, q_rot, pph, h->elem == 4);
-        p.q = q_rot;
-      }
       const unsigned waves = (unsigned)items.size() * Hkv;
       rc = launch_private(h, dim3((waves + 3) / 4), st, p);
       if (rc != PASTA_OK) return rc;
