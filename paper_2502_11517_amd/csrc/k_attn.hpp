@@ -70,7 +70,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   const int G = p.Hq / p.Hkv;
   PASTA_CLK(0);
 
-  // ---- decode the work item (as in attn_item)
+  // ---- decode the work item
   int req, g, R, n_tok, slot0, stride, gather_pos, pend0, pend_src0;
   int row0 = 0;  // first stacked row of this item's row group (shared-prefix items)
   long long part_row0;

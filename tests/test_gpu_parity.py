@@ -327,6 +327,46 @@ def test_multi_layer_pools_share_slots():
     s.close()
 
 
+def test_pool_filled_to_its_last_slot_with_every_stream_id_decoding():
+    """Maximum sizes: the history fills the request's pool share exactly, and the step carries
+    max_requests * max_streams query rows (all seven forks and the root).  The next append is
+    refused with E_CAPACITY and leaves pool and lists as they were."""
+    from paper_2502_11517_amd.harness import to_device, to_host_bits
+    w = W.single_request("full", "bf16", 8, 2, 128, 1.0, 21, 448, [10, 9, 9, 9, 9, 9, 9], "random",
+                         k_std=128 ** -0.5, slack=0)
+    assert w.pool_tokens == w.n_prefill == 512 and w.max_streams == 8
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    pl, offs, st, ct, sd = w.lists(0)
+    # the root as eighth query row: it sees its own 448 rows
+    rid = np.zeros(8, np.int32)
+    sid = np.arange(1, 9, dtype=np.int32) % 8  # forks 1..7, then the root
+    lists = (np.append(pl, 448), np.append(offs, offs[-1]), st, ct, sd)
+    rng = np.random.default_rng(21)
+    q = W.f32_to_bf16_bits(rng.standard_normal((8, w.Hq, w.D), dtype=np.float32))
+    qd = to_device(q, w.dtype, s.device)
+    ref, _ = oracle.attention(op.g, op.k, op.v, rid, *lists, q, w.scale)
+    outs = []
+    for explicit in (True, False):
+        out = torch.empty_like(qd)
+        s.h.decode_step(0, rid, sid, qd, out, lists=lists if explicit else None)
+        check_close(_out64(w, out), ref, w.dtype, f"full pool, explicit={explicit}")
+        outs.append(to_host_bits(out, w.dtype).copy())
+    # slot 511 (the last of the pool) is somebody's newest row and was read
+    assert max(int(a + (c - 1) * d) for a, c, d in zip(st, ct, sd)) == 511
+    k1, v1 = w.kv_rows(0, 1)
+    with pytest.raises(B.PastaError) as e:
+        s.h.append_kv(0, [0], [3], to_device(k1, w.dtype, s.device), to_device(v1, w.dtype, s.device))
+    assert e.value.code == B.E_CAPACITY
+    _check_pool(w, s, op)
+    out = torch.empty_like(qd)
+    s.h.decode_step(0, rid, sid, qd, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_bits(out, w.dtype), outs[1])
+    s.close()
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_maintained_lists_on_random_fork_histories_equal_dense_mask(seed):
     """Every live thread keeps decoding, forks open from any thread (nested too): the lists the

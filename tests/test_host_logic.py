@@ -396,3 +396,27 @@ def test_comparison_flags_and_causal_skip_argument_checks():
         h.decode_step(0, [0], [1], FAKE, FAKE, flags=B.DECODE_PLAN_ONLY, causal_skip=[0], lists=([5], [0, 0], [], [], []))
     assert e.value.code == B.E_INVAL
     h.destroy()
+
+
+def test_full_pool_and_maximum_number_of_query_rows():
+    """The request's share of the pool filled to its last slot, max_requests * max_streams query
+    rows in one step; one row more is E_CAPACITY and changes neither the tail nor the lists."""
+    w = W.single_request("full", "bf16", 8, 2, 128, 1.0, 21, 448, [10, 9, 9, 9, 9, 9, 9], "random", slack=0)
+    h = _handle(Hq=8, Hkv=2, max_streams=8, pool_tokens=w.pool_tokens)
+    slots = _reserve(h, w.ev_request, w.ev_stream, w.ev_parent)
+    assert slots.tolist() == list(range(512))
+    rid, sid = np.zeros(8, np.int32), np.arange(1, 9, dtype=np.int32) % 8
+    goffs, plan = _plan(h, rid, sid)
+    pl, offs, st, ct, sd = w.lists(0)
+    sizes = [int(pl[i] + ct[offs[i]:offs[i + 1]].sum()) for i in range(7)] + [448]
+    assert np.diff(goffs).tolist() == sizes
+    with pytest.raises(B.PastaError) as e:
+        _reserve(h, [0], [3])
+    assert e.value.code == B.E_CAPACITY
+    goffs2, plan2 = _plan(h, rid, sid)
+    assert np.array_equal(goffs, goffs2) and np.array_equal(plan, plan2)
+    with pytest.raises(B.PastaError) as e:  # a ninth query row is more than the handle was sized for
+        _plan(h, np.zeros(9, np.int32), np.arange(9, dtype=np.int32) % 8,
+              lists=(np.full(9, 10), np.zeros(10, np.int32), [], [], []))
+    assert e.value.code == B.E_INVAL
+    h.destroy()
