@@ -22,7 +22,8 @@
 //     straight into its LDS tile (global_load_lds, 16 B per lane), its second block into
 //     registers, both requested before anything is waited for; later blocks follow through the
 //     registers, one block ahead of the computation;
-//   * the wave's LDS tile holds K and V of one block with a 16-byte XOR swizzle;
+//   * the wave's LDS tile holds K and V of one block, each with the 16-byte XOR swizzle that
+//     makes its kind of read free of bank conflicts;
 //     S^T[32 tok x 32 rows] = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows, B = Q rows);
 //   * online softmax in registers: a lane holds 16 tokens of one row, its partner lane
 //     (lane ^ 32) the other 16 -- one lane exchange per block for the row max;
@@ -46,8 +47,16 @@ constexpr int kBlock = 32;  // tokens per wave block
 
 struct AttnTile {             // one wave's 16 KB: K and V block, later its O^T on the way out
   u32x4 kt[kBlock * 16];      // K block [row][16 pieces], piece p of row r at p ^ (r & 15)
-  u32x4 vt[kBlock * 16];      // V block, same swizzle
+  u32x4 vt[kBlock * 16];      // V block [row][16 pieces], piece p of row r at p ^ v_swizzle(r)
 };
+
+// The two operands are read differently, so they are swizzled differently.  K (and Q): 16 lanes
+// read one 16-byte piece each of 16 consecutive rows -- p ^ (r & 15) spreads them over all 64
+// banks.  V: a transposing read takes 64 contiguous bytes of each of FOUR consecutive rows per
+// bank cycle; rows are 256 bytes = one trip round the banks apart, so the four rows must land in
+// four different quarters of the row (with K's swizzle they would share one: a 4-way conflict,
+// 8 instead of 2 cycles per read -- measured).
+__device__ __forceinline__ int v_swizzle(int r) { return (r & 3) << 2; }
 
 struct AttnLds {
   AttnTile tile[4];           // first member: wave w's area starts at byte w * 16 KB
@@ -227,7 +236,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 #pragma unroll
     for (int i = 0; i < 8; ++i) load_to_lds16((pnd[i] ? kpend : kb) + off[i], ktw + 64 * i);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_to_lds16((pnd[i] ? vpend : vb) + off[i], vtw + 64 * i);
+    for (int i = 0; i < 8; ++i) {  // the row offset is a multiple of 256: bits 4..7 hold the piece alone
+      const int r = rbase + 4 * i;
+      load_to_lds16((pnd[i] ? vpend : vb) + (off[i] ^ (((r & 15) ^ v_swizzle(r)) << 4)), vtw + 64 * i);
+    }
   };
   // ---- everything this wave needs first is requested here, before anything is waited for:
   // its share of the stacked Q rows (2 loads), its first block (16 loads into LDS), and its
@@ -303,7 +315,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       for (int i = 0; i < 8; ++i) {
         const int r = rbase + 4 * i;
         ktw[r * 16 + (piece ^ (r & 15))] = br.k[i];
-        vtw[r * 16 + (piece ^ (r & 15))] = br.v[i];
+        vtw[r * 16 + (piece ^ v_swizzle(r))] = br.v[i];
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -390,7 +402,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
         for (int e4 = 0; e4 < 2; ++e4) {
           const int trow = 16 * ks + 8 * e4 + 4 * hh + (bl >> 2);
           const int col = 32 * mt + 16 * cblk + 4 * (bl & 3);
-          part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ (trow & 15))) * 8 + (col & 7));
+          part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ v_swizzle(trow))) * 8 + (col & 7));
         }
         u32x4 a4;
         a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
