@@ -107,13 +107,14 @@ struct DecodeParams {
   int pend_n;           // rows of the deferred append (0: none)
   int32_t pend_dst[32]; // their physical rows
   int32_t pend_pos[32]; // their position ids, when pend_rope
-  int rope_q;           // 1: Q rows are turned by their streams' position ids on the way into the kernel
-  int pend_rope;        // 1: the deferred K rows are still unrotated (PASTA_APPEND_ROPE): whoever reads or
-                        //    copies them turns them by pend_pos
+  // Rotary embedding: both flags are for the small launch ahead of the attention launch (k_rope_prep),
+  // which writes rotated copies; the attention launch then gets q / k_pend pointing at those.
+  int rope_q;           // 1: Q rows are to be turned by their streams' position ids
+  int pend_rope;        // 1: the deferred K rows are still unrotated (PASTA_APPEND_ROPE), to be turned by pend_pos
   int32_t s_items[32];  // single_req with <= 16 streams: stream i's private items are
                         //   [s_items[2i], s_items[2i] + s_items[2i+1]) -- spares the merge a table look-up
   const uint8_t* dense_mask;  // comparison mode: 0/1 per (stream, slot); null otherwise
-  const double* rope_tab;  // theta^(-2f/D) / (2 pi), f < D/2 (device), when Q is rotated in the kernel
+  const double* rope_tab;  // theta^(-2f/D) / (2 pi), f < D/2 (device), for k_rope_prep
   int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
   DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way
                         //    to the first K/V load)
