@@ -173,7 +173,8 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   }
   // (work-group-uniform values, but loaded per lane: tell the compiler, so that the branches on
   // them are scalar and its wait-count bookkeeping sees an exhaustive if / else)
-  const int n_blocks = __builtin_amdgcn_readfirstlane((n_tok + kBlock - 1) / kBlock);
+  n_tok = __builtin_amdgcn_readfirstlane(n_tok);
+  const int n_blocks = (n_tok + kBlock - 1) / kBlock;
 
   // ---- block loads: lane -> piece (lane & 15) of rows (lane >> 4) + 4 i, i < 8
   const char* kb = reinterpret_cast<const char*>(p.k);
@@ -300,8 +301,17 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 #pragma unroll
     for (int i = 0; i < 16; ++i) O[mt][i] = 0.f;
 
-  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vtw);
-  const int bl = lane & 15, cblk = (lane >> 4) & 1;
+  // V^T reads: token row 16 ks + 8 e4 + 4 hh + r2 (r2 = bits 2..3 of the lane), columns
+  // 32 mt + 16 cblk + 4 (lane & 3) ...: with V's swizzle the lane's byte address is a per-M-tile
+  // lane part (the 64-byte quarter is mt ^ r2) plus a constant that fits the instruction's offset.
+  const char* vrd[4];
+  {
+    const int bl = lane & 15, cblk = (lane >> 4) & 1, r2 = bl >> 2;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+      vrd[mt] = reinterpret_cast<const char*>(vtw) + (4 * hh + r2) * 256 + (mt ^ r2) * 64 +
+                (2 * cblk + ((bl >> 1) & 1)) * 16 + (bl & 1) * 8;
+  }
 
   auto compute_block = [&](int b, auto first) {
     if constexpr (first.value) {
@@ -326,39 +336,59 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     }
 
     // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
-    f32x16 S, S1;  // two accumulation chains (even / odd steps) halve the dependent-MFMA latency
+    f32x16 S;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { S[i] = 0.f; S1[i] = 0.f; }
+    for (int i = 0; i < 16; ++i) S[i] = 0.f;
+    {  // operands of step kk + 1 are requested before step kk is issued: LDS latency once, not 8 times
+      u32x4 a[2], qv[2];
+      const int pc0 = hh ^ (l32 & 15);
+      a[0] = ktw[l32 * 16 + pc0];
+      qv[0] = lds.q[l32 * 16 + pc0];
 #pragma unroll
-    for (int kk = 0; kk < 8; kk += 2) {
-      const int pc0 = (2 * kk + hh) ^ (l32 & 15), pc1 = (2 * kk + 2 + hh) ^ (l32 & 15);
-      const u32x4 a0 = ktw[l32 * 16 + pc0], q0 = lds.q[l32 * 16 + pc0];
-      const u32x4 a1 = ktw[l32 * 16 + pc1], q1 = lds.q[l32 * 16 + pc1];
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a0),
-                                                  *reinterpret_cast<const bf16x8*>(&q0), S, 0, 0, 0);
-      S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a1),
-                                                   *reinterpret_cast<const bf16x8*>(&q1), S1, 0, 0, 0);
+      for (int kk = 0; kk < 8; ++kk) {
+        if (kk + 1 < 8) {
+          const int pc = (2 * kk + 2 + hh) ^ (l32 & 15);
+          a[(kk + 1) & 1] = ktw[l32 * 16 + pc];
+          qv[(kk + 1) & 1] = lds.q[l32 * 16 + pc];
+        }
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a[kk & 1]),
+                                                    *reinterpret_cast<const bf16x8*>(&qv[kk & 1]), S, 0, 0, 0);
+      }
+      // (left alone, the scheduler pulls each pair of reads back behind the MFMA before it)
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // 4 LDS reads
+#pragma unroll
+      for (int kk = 0; kk < 6; ++kk) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // 2 LDS reads
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
     }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) S[i] += S1[i];
-    // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block
+    // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block.  Only a block
+    // that reaches past the item's end (or the dense-mask mode) has tokens to hide.
     const int tok0 = b * kBlock + 4 * hh;
-    uint32_t mk[4] = {~0u, ~0u, ~0u, ~0u};  // one byte per token: tokens tok0 + 8 k .. + 3 in mk[k]
-    if constexpr (GATHER && DENSE) {
-      if (p.dense_mask) {
+    bool hide = b * kBlock + kBlock > n_tok;
+    if constexpr (GATHER && DENSE) hide = hide || p.dense_mask != nullptr;
+    if (hide) {
+      asm volatile("" ::: "memory");  // keeps this a branch: the common case has nothing to hide
+      const int left = n_tok - tok0;  // this lane's tokens 8 (i / 4) + i % 4 below `left` exist
+      uint32_t mk[4] = {~0u, ~0u, ~0u, ~0u};  // one byte per token: tokens tok0 + 8 k .. + 3 in mk[k]
+      if constexpr (GATHER && DENSE) {
+        if (p.dense_mask) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) mk[k] = *reinterpret_cast<const uint32_t*>(&lds.mask[(tok0 + 8 * k) & (kGatherMax - 1)]);
+          for (int k = 0; k < 4; ++k) mk[k] = *reinterpret_cast<const uint32_t*>(&lds.mask[(tok0 + 8 * k) & (kGatherMax - 1)]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const bool seen = (8 * (i >> 2) + (i & 3)) < left && ((mk[i >> 2] >> (8 * (i & 3))) & 0xffu);
+        S[i] = seen ? S[i] : -INFINITY;
       }
     }
+    // online softmax in log2 units; the scale (> 0) is applied inside the exponent: 2^(s z - m)
     float mx = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const bool seen = (tok0 + 8 * (i >> 2) + (i & 3)) < n_tok && ((mk[i >> 2] >> (8 * (i & 3))) & 0xffu);
-      const float s = seen ? S[i] * p.scale_log2e : -INFINITY;
-      S[i] = s;
-      mx = fmaxf(mx, s);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * p.scale_log2e;
     const float mn = fmaxf(m_run, mx);            // -inf while the row has seen nothing (dense-mask mode)
     const float mref = mn == -INFINITY ? 0.f : mn;
     const float corr = fast_exp2(m_run - mref);
@@ -366,7 +396,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     float ps = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      S[i] = fast_exp2(S[i] - mref);
+      S[i] = fast_exp2(fmaf(S[i], p.scale_log2e, -mref));
       ps += S[i];
     }
     l_run = l_run * corr + ps;
@@ -399,11 +429,8 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       for (int mt = 0; mt < 4; ++mt) {
         s16x4 part[2];
 #pragma unroll
-        for (int e4 = 0; e4 < 2; ++e4) {
-          const int trow = 16 * ks + 8 * e4 + 4 * hh + (bl >> 2);
-          const int col = 32 * mt + 16 * cblk + 4 * (bl & 3);
-          part[e4] = lds_read_tr16(vt16 + (trow * 16 + ((col >> 3) ^ v_swizzle(trow))) * 8 + (col & 7));
-        }
+        for (int e4 = 0; e4 < 2; ++e4)
+          part[e4] = lds_read_tr16(reinterpret_cast<const uint16_t*>(vrd[mt] + (16 * ks + 8 * e4) * 256));
         u32x4 a4;
         a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
         a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
