@@ -44,6 +44,7 @@
 namespace pasta {
 
 constexpr int kBlock = 32;  // tokens per wave block
+constexpr int kRawBuffer = 0x00020000;  // buffer descriptor word 3: raw buffer of 32-bit data, no swizzle
 
 struct AttnTile {             // one wave's 16 KB: K and V block, later its O^T on the way out
   u32x4 kt[kBlock * 16];      // K block [row][16 pieces], piece p of row r at p ^ (r & 15)
@@ -69,7 +70,7 @@ struct AttnLds {
 
 struct BlockRegs { u32x4 k[8], v[8]; };  // one lane's share of a 32-token block
 
-template <bool PAGED, bool GATHER, bool DENSE>
+template <bool PAGED, bool GATHER, bool DENSE, bool LONG>
 __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
   const int tid = threadIdx.x;
@@ -175,6 +176,13 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   // them are scalar and its wait-count bookkeeping sees an exhaustive if / else)
   n_tok = __builtin_amdgcn_readfirstlane(n_tok);
   const int n_blocks = (n_tok + kBlock - 1) / kBlock;
+  req = __builtin_amdgcn_readfirstlane(req);
+  g = __builtin_amdgcn_readfirstlane(g);
+  slot0 = __builtin_amdgcn_readfirstlane(slot0);
+  stride = __builtin_amdgcn_readfirstlane(stride);
+  pend0 = __builtin_amdgcn_readfirstlane(pend0);
+  pend_src0 = __builtin_amdgcn_readfirstlane(pend_src0);
+  listed = __builtin_amdgcn_readfirstlane((int)listed) != 0;
 
   // ---- block loads: lane -> piece (lane & 15) of rows (lane >> 4) + 4 i, i < 8
   const char* kb = reinterpret_cast<const char*>(p.k);
@@ -204,7 +212,35 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     const long long off_pend = ((long long)pidx * p.Hkv + g) * D * 2;
     return is_pend ? off_pend : off_pool;
   };
-  auto load_block = [&](BlockRegs& br, int b) {  // block b -> registers, natural piece order
+  // A PLAIN block: 32 existing tokens at an arithmetic progression of rows of a contiguous pool,
+  // none of them a deferred row.  Its addresses are a wave-uniform base per load (scalar
+  // arithmetic) plus a 32-bit lane part that is the same for every block of the item; all other
+  // blocks (listed, paged, ragged, with deferred rows) compute one address per row, which costs
+  // about 12 vector instructions per row.  Only the LONG instantiation has this path, and only in
+  // its steady-state loop: launches whose waves have at most two blocks never get there, and
+  // merely carrying the code made them slower (measured: +0.9 us on a 13 us launch).
+  const long long row_bytes = (long long)stride * p.lay.slot_stride * 2;
+  const bool arith = LONG && !listed && row_bytes < (1ll << 26);  // 31 row steps fit 32 bits
+  const long long item_off = arith ? elem_off(p.lay, req * p.lay.pool_tokens + slot0, g) * 2 : 0;  // token 0, piece 0
+  const uint32_t lane_row = (uint32_t)rbase * (uint32_t)row_bytes;
+  auto plain = [&](int b) -> bool {
+    return arith && b * kBlock + kBlock <= n_tok && slot0 + (b * kBlock + kBlock - 1) * stride < pend0;
+  };
+  auto load_block = [&](BlockRegs& br, int b, auto try_plain) {  // block b -> registers, natural piece order
+    if (try_plain.value && plain(b)) {
+      // buffer loads: descriptor base = the block's first row (scalar), lane part in the offset
+      // register, row step i in the scalar offset -- no vector arithmetic per load
+      const long long blk = item_off + (long long)(b * kBlock) * row_bytes;
+      const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kb + blk), 0, 0x7fffffff, kRawBuffer);
+      const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vb + blk), 0, 0x7fffffff, kRawBuffer);
+      const uint32_t lo = lane_row + piece * 16, step = 4u * (uint32_t)row_bytes;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        br.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, lo, i * step, 0);
+        br.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, lo, i * step, 0);
+      }
+      return;
+    }
     long long off[8];
     bool pnd[8];
 #pragma unroll
@@ -269,7 +305,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   // that count a constant -- merged, the wait would be for everything, the blocks included.
   auto issue_blocks_finish_q = [&](auto h1, auto h2) {
     if constexpr (h1.value) dma_block(w);
-    if constexpr (h2.value) load_block(br, w + 4);
+    if constexpr (h2.value) load_block(br, w + 4, std::false_type{});
     PASTA_CLK(1);
     // Q has landed once at most the block loads issued behind it are outstanding
     wait_vmcnt<h2.value ? 32 : (h1.value ? 16 : 0)>();
@@ -332,7 +368,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if constexpr (!first.value) {
-      if (b + 4 < n_blocks) load_block(br, b + 4);  // in flight while this block is computed
+      if (b + 4 < n_blocks) load_block(br, b + 4, std::true_type{});  // in flight while this block is computed
     }
 
     // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
@@ -490,12 +526,14 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   PASTA_CLK(7);
 }
 
-// One launch for all partials of a decode step with at most 32 stacked rows per request;
-// the shared-prefix items' work-groups come first, the private (gather) items' after them.
+// One launch for all partials of a decode step; the shared-prefix items' work-groups come
+// first, the private (gather) items' after them.
 // DENSE = the variant that also carries the dense-mask comparison mode (p.dense_mask); the plain
-// variant has none of that code.
-template <bool PAGED, bool DENSE>
+// variant has none of that code.  LONG = the variant for launches with long items (contiguous
+// pools only): its steady-state loop addresses plain blocks through buffer loads.
+template <bool PAGED, bool DENSE, bool LONG = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
+  static_assert(!LONG || (!PAGED && !DENSE), "the long-item variant exists for contiguous pools, list mode");
   __shared__ AttnLds lds;
   const int32_t* meta = meta_of(p);
   // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads those
@@ -535,8 +573,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
   // the longer items issue their loads first where a SIMD holds a wave of each kind
   if ((int)blockIdx.x < n_prefix_wgs) __builtin_amdgcn_s_setprio(3);
-  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE>(p, lds, meta, blockIdx.x);
-  else attn_item<PAGED, true, DENSE>(p, lds, meta, blockIdx.x - n_prefix_wgs);
+  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE, LONG>(p, lds, meta, blockIdx.x);
+  else attn_item<PAGED, true, DENSE, LONG>(p, lds, meta, blockIdx.x - n_prefix_wgs);
   if (pend_u >= 0) pend_store(pend_u, pend_val);
 }
 
