@@ -212,32 +212,51 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     const long long off_pend = ((long long)pidx * p.Hkv + g) * D * 2;
     return is_pend ? off_pend : off_pool;
   };
-  // A PLAIN block: 32 existing tokens at an arithmetic progression of rows of a contiguous pool,
-  // none of them a deferred row.  Its addresses are a wave-uniform base per load (scalar
-  // arithmetic) plus a 32-bit lane part that is the same for every block of the item; all other
-  // blocks (listed, paged, ragged, with deferred rows) compute one address per row, which costs
-  // about 12 vector instructions per row.  Only the LONG instantiation has this path, and only in
-  // its steady-state loop: launches whose waves have at most two blocks never get there, and
-  // merely carrying the code made them slower (measured: +0.9 us on a 13 us launch).
+  // A PLAIN block: 32 existing tokens whose rows are an arithmetic progression in memory (a
+  // contiguous pool: any stride; a paged pool: consecutive slots starting at a multiple of 32,
+  // pages of 16 tokens or more, so each half of the block lies inside one page), none of them a
+  // deferred row.  Its addresses are a wave-uniform base per half block (scalar arithmetic, the
+  // page-table entries through scalar loads) plus a 32-bit lane part that is the same for every
+  // block of the item; all other blocks (listed, ragged, with deferred rows) compute one address
+  // per row, which costs about 12 vector instructions per row.  Only the LONG instantiation has
+  // this path, and only in its steady-state loop: launches whose waves have at most two blocks
+  // never get there, and merely carrying the code made them slower (measured: +0.9 us on a
+  // 13 us launch).
   const long long row_bytes = (long long)stride * p.lay.slot_stride * 2;
-  const bool arith = LONG && !listed && row_bytes < (1ll << 26);  // 31 row steps fit 32 bits
-  const long long item_off = arith ? elem_off(p.lay, req * p.lay.pool_tokens + slot0, g) * 2 : 0;  // token 0, piece 0
+  const bool arith = LONG && !listed && row_bytes < (1ll << 26) &&  // 31 row steps fit 32 bits
+                     (!PAGED || (stride == 1 && (slot0 & 31) == 0 && p.lay.page_shift >= 4));
   const uint32_t lane_row = (uint32_t)rbase * (uint32_t)row_bytes;
   auto plain = [&](int b) -> bool {
     return arith && b * kBlock + kBlock <= n_tok && slot0 + (b * kBlock + kBlock - 1) * stride < pend0;
   };
   auto load_block = [&](BlockRegs& br, int b, auto try_plain) {  // block b -> registers, natural piece order
     if (try_plain.value && plain(b)) {
-      // buffer loads: descriptor base = the block's first row (scalar), lane part in the offset
-      // register, row step i in the scalar offset -- no vector arithmetic per load
-      const long long blk = item_off + (long long)(b * kBlock) * row_bytes;
-      const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kb + blk), 0, 0x7fffffff, kRawBuffer);
-      const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vb + blk), 0, 0x7fffffff, kRawBuffer);
+      // buffer loads: descriptor base = the first row of each half block (scalar), lane part in
+      // the offset register, row step in the scalar offset -- no vector arithmetic per load
       const uint32_t lo = lane_row + piece * 16, step = 4u * (uint32_t)row_bytes;
+      long long off2[2];
+      int pp[2] = {0, 0};
+      if constexpr (PAGED) {  // both page look-ups first (scalar loads)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        br.k[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, lo, i * step, 0);
-        br.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, lo, i * step, 0);
+        for (int hb = 0; hb < 2; ++hb)
+          pp[hb] = scalar_load_i32(p.page_table, req * p.lay.pages_per_request + ((slot0 + b * kBlock + 16 * hb) >> p.lay.page_shift));
+      }
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) {
+        const int t = slot0 + (b * kBlock + 16 * hb) * stride;  // uniform
+        const int phys = PAGED ? ((pp[hb] << p.lay.page_shift) | (t & p.lay.page_mask)) : req * p.lay.pool_tokens + t;
+        off2[hb] = elem_off(p.lay, phys, g) * 2;
+      }
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) {
+        const long long off = off2[hb];
+        const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kb + off), 0, 0x7fffffff, kRawBuffer);
+        const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vb + off), 0, 0x7fffffff, kRawBuffer);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          br.k[4 * hb + i] = __builtin_amdgcn_raw_buffer_load_b128(kr, lo, i * step, 0);
+          br.v[4 * hb + i] = __builtin_amdgcn_raw_buffer_load_b128(vr, lo, i * step, 0);
+        }
       }
       return;
     }
@@ -529,11 +548,11 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 // One launch for all partials of a decode step; the shared-prefix items' work-groups come
 // first, the private (gather) items' after them.
 // DENSE = the variant that also carries the dense-mask comparison mode (p.dense_mask); the plain
-// variant has none of that code.  LONG = the variant for launches with long items (contiguous
-// pools only): its steady-state loop addresses plain blocks through buffer loads.
+// variant has none of that code.  LONG = the variant for launches with long items: its
+// steady-state loop addresses plain blocks through buffer loads.
 template <bool PAGED, bool DENSE, bool LONG = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
-  static_assert(!LONG || (!PAGED && !DENSE), "the long-item variant exists for contiguous pools, list mode");
+  static_assert(!LONG || !DENSE, "the long-item variant exists for the list mode");
   __shared__ AttnLds lds;
   const int32_t* meta = meta_of(p);
   // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads those

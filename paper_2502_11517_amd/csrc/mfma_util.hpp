@@ -55,6 +55,14 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// A 32-bit word of read-only device memory at a wave-uniform address, through the scalar
+// data path (s_load_dword): it neither occupies the vector-memory queue nor counts in vmcnt.
+// Only for memory that no launch in flight writes (the page table).
+__device__ __forceinline__ int32_t scalar_load_i32(const int32_t* ptr, int idx) {
+  typedef const int32_t __attribute__((address_space(4))) * const_ptr;
+  return ((const_ptr)(uintptr_t)ptr)[idx];
+}
+
 // Phase clocks for kernel tuning (compiled in only with -DPASTA_PHASE_CLOCKS): thread 0 of every
 // work-group stores the 100 MHz wall clock at a few points into the tail of the partials buffer.
 #ifdef PASTA_PHASE_CLOCKS

@@ -1005,9 +1005,14 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       } else {
         // prefix chunks of more than two 32-token blocks per wave: the variant whose loop has the
         // cheap addressing of plain blocks
-        if (h->lay.paged) k_attn<true, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-        else if (n_prefix_wgs > 0 && chunk_tokens > 2 * 4 * 32) k_attn<false, false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-        else k_attn<false, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        const bool long_items = n_prefix_wgs > 0 && chunk_tokens > 2 * 4 * 32;
+        if (h->lay.paged) {
+          if (long_items) k_attn<true, false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+          else k_attn<true, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        } else {
+          if (long_items) k_attn<false, false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+          else k_attn<false, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        }
       }
       if (take_pending) h->pending.active = false;
     } else if (!items.empty()) {

@@ -396,6 +396,48 @@ def test_maintained_lists_on_random_fork_histories_equal_dense_mask(seed):
     s.close()
 
 
+# ------------------------------------------------------------------------- long prefix chunks
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_long_prefix_chunks_contiguous_pool_with_deferred_steps(layout):
+    """A prefix long enough that every wave walks more than two 32-token blocks of its chunk (the
+    kernel variant with the cheap addressing of plain blocks), of a ragged length so that full,
+    ragged and deferred-row blocks meet in one launch; three append+decode steps."""
+    w = W.config3(steps=3, prefix=12007, n_streams=5)
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR))
+    s.append_events(w.n_prefill)
+    op.append_events(w.n_prefill)
+    plan = np.zeros(8, np.int64)
+    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY, dbg_plan=plan)
+    assert plan[4] > 256, "the chunk must span more than two blocks per wave"
+    keep = []
+    for step in range(w.steps):
+        hi = w.n_events(step)
+        s.append_events(hi, chunk=w.n, flags=B.APPEND_DEFER if step else 0)
+        keep.append(getattr(s, "_keep_rows", None))
+        op.append_events(hi)
+        _check_step(w, s, op, step, explicit=(step == 1), what=f"long chunks, step {step}")
+    _check_pool(w, s, op)
+    s.close()
+
+
+@pytest.mark.parametrize("page_tokens", [16, 64, 8])
+def test_long_prefix_chunks_paged_pool(page_tokens):
+    """The same variant on paged pools: pages of 16 and 64 tokens take the plain-block path
+    (each half block inside one page), pages of 8 tokens must fall back to per-row addresses."""
+    w = W.config4(n_requests=2, seed=77, pmin=9000, pmax=9500, page_tokens=page_tokens)
+    for layout in LAYOUTS:
+        s = _session(w, kv_layout=layout)
+        op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR)).append_events(w.n_prefill)
+        s.append_events(w.n_prefill)
+        plan = np.zeros(8, np.int64)
+        s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY, dbg_plan=plan)
+        assert plan[4] > 256
+        _check_step(w, s, op, what=f"paged {page_tokens}, layout {layout}")
+        _check_step(w, s, op, explicit=False, streams=list(range(min(3, w.n))))
+        s.close()
+
+
 # ------------------------------------------------------------------------- deferred append
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_deferred_append_rides_with_the_decode_launch(layout):
