@@ -523,22 +523,39 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     if (hh == 0) { lds.mw[w][l32] = m_run; lds.lw[w][l32] = lw; }
   }
   __syncthreads();
-  float l_all = 0.f, m_all = -INFINITY;
+  // Thread (rr = 8 pass + tid / 32, c = tid % 32) adds the four waves' 16-byte piece c of row rr.
+  // Everything is read from LDS first, for all four passes and without a branch in between (rows
+  // past R hold stale tile bytes: read, never stored), so the LDS latency is paid once.
+  {
+    const int r0 = tid >> 5, c = tid & 31;
+    float mw4[4][4], lw4[4][4];
+    f32x4 pc[4][4];
 #pragma unroll
-  for (int pass = 0; pass < 4; ++pass) {
-    const int rr = pass * 8 + (tid >> 5), c = tid & 31;
-    if (rr < R) {
-      const float m0 = lds.mw[0][rr], m1 = lds.mw[1][rr], m2 = lds.mw[2][rr], m3 = lds.mw[3][rr];
-      const float ma = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));  // -inf: the row saw nothing in this item (dense-mask mode)
-      const float mr = ma == -INFINITY ? 0.f : ma;
-      const float s0 = fast_exp2(m0 - mr), s1 = fast_exp2(m1 - mr), s2 = fast_exp2(m2 - mr), s3 = fast_exp2(m3 - mr);
+    for (int pass = 0; pass < 4; ++pass) {
+      const int rr = pass * 8 + r0;
       const f32x4* src = reinterpret_cast<const f32x4*>(&lds.tile[0]) + rr * 32 + (c ^ rr);  // + 1024 per wave
-      const f32x4 acc = src[0] * s0 + src[1024] * s1 + src[2048] * s2 + src[3072] * s3;
-      *reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + rr) * D + 4 * c) = acc;
-      if (c == 0) {  // one lane per row also writes (m, l)
-        l_all = lds.lw[0][rr] * s0 + lds.lw[1][rr] * s1 + lds.lw[2][rr] * s2 + lds.lw[3][rr] * s3;
-        m_all = ma;
-        p.part_ml[part_row0 + rr] = make_float2(m_all, l_all);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        mw4[pass][k] = lds.mw[k][rr];
+        lw4[pass][k] = lds.lw[k][rr];
+        pc[pass][k] = src[1024 * k];
+      }
+    }
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int rr = pass * 8 + r0;
+      const float ma = fmaxf(fmaxf(mw4[pass][0], mw4[pass][1]), fmaxf(mw4[pass][2], mw4[pass][3]));
+      const float mr = ma == -INFINITY ? 0.f : ma;  // -inf: the row saw nothing in this item (dense-mask mode)
+      float sc[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) sc[k] = fast_exp2(mw4[pass][k] - mr);
+      const f32x4 acc = pc[pass][0] * sc[0] + pc[pass][1] * sc[1] + pc[pass][2] * sc[2] + pc[pass][3] * sc[3];
+      if (rr < R) {
+        *reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + rr) * D + 4 * c) = acc;
+        if (c == 0) {  // one lane per row also writes (m, l)
+          const float l_all = lw4[pass][0] * sc[0] + lw4[pass][1] * sc[1] + lw4[pass][2] * sc[2] + lw4[pass][3] * sc[3];
+          p.part_ml[part_row0 + rr] = make_float2(ma, l_all);
+        }
       }
     }
   }
