@@ -49,25 +49,30 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
 
   // The running state of this thread: max-free accumulation is not possible, so each batch
   // is folded with the running max of what the thread has seen (one more online softmax).
+  // No early exit and no branch on the loaded values: with one, the compiler requests a part's
+  // accumulator only after its (m, l) has arrived and been looked at -- two memory round trips
+  // per batch instead of one.
   float m_t = -INFINITY, l_t = 0.f, o_t = 0.f;
   auto fold = [&](const float2* ml, const float* a, int n_valid) {
     float mb = m_t;
 #pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (u < n_valid && ml[u].y > 0.f) mb = fmaxf(mb, ml[u].x);
-    if (mb == -INFINITY) return;
-    const float c = fast_exp2(m_t - mb);  // 0 when m_t was -inf
+    for (int u = 0; u < UNR; ++u) mb = fmaxf(mb, (u < n_valid && ml[u].y > 0.f) ? ml[u].x : -INFINITY);
+    const float mref = mb == -INFINITY ? 0.f : mb;  // nothing seen yet: every weight below is 0
+    const float c = fast_exp2(m_t - mref);           // 0 when m_t was -inf
     l_t *= c;
     o_t *= c;
     m_t = mb;
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      const float wgt = (u < n_valid && ml[u].y > 0.f) ? fast_exp2(ml[u].x - mb) : 0.f;
+      const float wgt = (u < n_valid && ml[u].y > 0.f) ? fast_exp2(ml[u].x - mref) : 0.f;
       l_t = fmaf(ml[u].y, wgt, l_t);
       o_t = fmaf(a[u], wgt, o_t);
     }
   };
-  auto run = [&](int row0, int row_step, int n) {  // parts grp, grp + NGRP, ... < n of one kind
+  // parts [0, n_a) of kind A (row a0 + i * a_step), then parts [0, n_b) of kind B, as ONE list:
+  // group grp takes list entries grp, grp + NGRP, ..., UNR of them per batch
+  auto run = [&](int a0, int a_step, int n_a, int b0, int b_step, int n_b) {
+    const int n = n_a + n_b;
     for (int i0 = grp; i0 < n; i0 += NGRP * UNR) {
       float2 ml[UNR];
       float a[UNR];
@@ -75,24 +80,23 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
         const int i = i0 + (u < n_valid ? u : 0) * NGRP;  // lanes past the end repeat a valid row
-        const int row = row0 + i * row_step;
+        const int row = i < n_a ? a0 + i * a_step : b0 + (i - n_a) * b_step;
         ml[u] = p.part_ml[row];
         a[u] = p.part_acc[(long long)row * D + d];
       }
       fold(ml, a, n_valid);
     }
   };
-  int item_begin, n_priv;
-  if (p.single_req == 2) {  // the stream's item range rides in the kernel arguments
+  if (p.single_req == 2) {  // the stream's item range rides in the kernel arguments: one list, one round trip
     const int32_t* si = s_items_of(p);
-    item_begin = si[2 * s];
-    n_priv = si[2 * s + 1];
+    const int item_begin = si[2 * s], n_priv = si[2 * s + 1];
+    run(pre0, R, n_pre, p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv);
   } else {
-    item_begin = stp->item_begin;  // requested here, needed after the prefix parts
-    n_priv = stp->item_end - item_begin;
+    const int item_begin = stp->item_begin;  // requested here, needed after the prefix parts
+    const int n_priv = stp->item_end - item_begin;
+    run(pre0, R, n_pre, 0, 0, 0);
+    run(p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv, 0, 0, 0);
   }
-  run(pre0, R, n_pre);
-  run(p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv);
 
   // ---- common max over the work-group, then rescale and add the groups through LDS
   float mx = m_t;
