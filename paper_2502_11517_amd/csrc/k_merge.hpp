@@ -6,10 +6,10 @@
 // One work-group of NT threads per (stream, query head): the threads form NT/D groups,
 // group k takes parts k, k + NT/D, ... with one head-dim element per thread (a part's
 // row is read as one coalesced 4D-byte line).  The kernel is a chain of memory round
-// trips, so everything that can be requested early is: the shared-prefix parts first
-// (their rows follow from kernel-argument scalars when the call holds one request), the
-// stream's record meanwhile, its private parts next.  The maximum is taken over what each
-// thread already holds plus an LDS exchange; the groups are added through LDS.
+// trips, kept to one (a step of one request with few streams: all the merge needs rides in the
+// kernel arguments) or two (the stream's record, then all its parts in one list).  The maximum
+// is taken over what each thread already holds plus an LDS exchange; the groups are added
+// through LDS.
 // NT = 1024 for steps with few output rows (they are a chain of latencies, and wide work-groups
 // shorten it); with many rows the launch is bound by the rate at which wavefronts can be
 // started, and NT = 256 starts a quarter as many.
@@ -38,15 +38,6 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
   const int h = g * G + gi;
   const int32_t* meta = meta_of(p);
   const DevStream* stp = reinterpret_cast<const DevStream*>(meta + p.off_streams) + s;
-  int R, n_pre, part_base, local;
-  if (p.single_req) {  // scalars from the kernel arguments; stream i is stacked-row block i
-    R = p.req0.n_streams * G; n_pre = p.req0.n_chunks; part_base = p.req0.part_base; local = s;
-  } else {
-    const DevReq rq = reinterpret_cast<const DevReq*>(meta + p.off_reqs)[stp->req_idx];
-    R = rq.n_streams * G; n_pre = rq.n_chunks; part_base = rq.part_base; local = stp->local;
-  }
-  const int pre0 = part_base + g * n_pre * R + local * G + gi;  // prefix part i: row pre0 + i * R
-
   // The running state of this thread: max-free accumulation is not possible, so each batch
   // is folded with the running max of what the thread has seen (one more online softmax).
   // No early exit and no branch on the loaded values: with one, the compiler requests a part's
@@ -87,16 +78,23 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
       fold(ml, a, n_valid);
     }
   };
-  if (p.single_req == 2) {  // the stream's item range rides in the kernel arguments: one list, one round trip
+  // shared-prefix part i of this (stream, head): row pre0 + i * R; private part j: row priv0 + j * Hkv * G
+  int pre0, n_pre, R, item_begin, n_priv;
+  if (p.single_req == 2) {  // one request, few streams: everything rides in the kernel arguments -- one round trip
     const int32_t* si = s_items_of(p);
-    const int item_begin = si[2 * s], n_priv = si[2 * s + 1];
-    run(pre0, R, n_pre, p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv);
-  } else {
-    const int item_begin = stp->item_begin;  // requested here, needed after the prefix parts
-    const int n_priv = stp->item_end - item_begin;
-    run(pre0, R, n_pre, 0, 0, 0);
-    run(p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv, 0, 0, 0);
+    item_begin = si[2 * s];
+    n_priv = si[2 * s + 1];
+    R = p.req0.n_streams * G;  // stream i is stacked-row block i
+    n_pre = p.req0.n_chunks;
+    pre0 = p.req0.part_base + s * G;
+  } else {  // the stream's record first (it carries what the merge needs of its request), then all parts
+    pre0 = stp->m_pre0;
+    n_pre = stp->m_n_pre;
+    R = stp->m_R;
+    item_begin = stp->item_begin;
+    n_priv = stp->item_end - item_begin;
   }
+  run(pre0 + g * n_pre * R + gi, R, n_pre, p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv);
 
   // ---- common max over the work-group, then rescale and add the groups through LDS
   float mx = m_t;

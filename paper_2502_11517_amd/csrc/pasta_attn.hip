@@ -862,6 +862,12 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       if (priv_rows > h->part_rows_cap) return PASTA_E_CAPACITY;
     }
 
+    for (int i = 0; i < n; ++i) {  // the merge's view of each stream's request (known now that the chunks are)
+      const DevReq& q = reqs[stream_req_idx[i]];
+      streams[i].m_pre0 = q.part_base + streams[i].local * G;
+      streams[i].m_n_pre = q.n_chunks;
+      streams[i].m_R = q.n_streams * G;
+    }
     // ---- metadata blob
     std::vector<int32_t> blob;
     DecodeParams p{};

@@ -53,8 +53,11 @@ struct DevStream {      // one per decoding stream, call order
   int32_t gather_base;  // first entry of this stream in dbg_gather_rows
   int32_t pos;          // position id of the stream's query token (rotary embedding of Q)
   int32_t mask_base;    // dense-mask mode: this stream's mask bytes start here (one per slot of its request)
-  int32_t pad[1];
-};
+  // what the merge needs of the stream's request, copied here so that it is one record away:
+  int32_t m_pre0;       // part_base + local * G: first shared-prefix partial row of the stream (kv head 0, chunk 0, head 0)
+  int32_t m_n_pre;      // split-K chunks of the request's common prefix
+  int32_t m_R;          // stacked rows of the request: shared-prefix part i of kv head g is row m_pre0 + (g * m_n_pre + i) * m_R + gi
+};                      // 14 words
 struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it
   int32_t start, count, stride, cum;
 };
