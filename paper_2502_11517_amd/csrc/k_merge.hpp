@@ -8,8 +8,7 @@
 // row is read as one coalesced 4D-byte line).  The kernel is a chain of memory round
 // trips, kept to one (a step of one request with few streams: all the merge needs rides in the
 // kernel arguments) or two (the stream's record, then all its parts in one list).  The maximum
-// is taken over what each thread already holds plus an LDS exchange; the groups are added
-// through LDS.
+// and the sum over the groups are taken by group 0 after one LDS exchange.
 // NT = 1024 for steps with few output rows (they are a chain of latencies, and wide work-groups
 // shorten it); with many rows the launch is bound by the rate at which wavefronts can be
 // started, and NT = 256 starts a quarter as many.
@@ -27,7 +26,7 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
   constexpr int kMergeThreads = NT;
   constexpr int NGRP = kMergeThreads / D;
   constexpr int UNR = 8;  // parts per thread and batch
-  __shared__ float red[kMergeThreads / kWave];
+  __shared__ float msum[NGRP];
   __shared__ float osum[NGRP][D];
   __shared__ float lsum[NGRP];
   const int tid = threadIdx.x;
@@ -96,22 +95,22 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
   }
   run(pre0 + g * n_pre * R + gi, R, n_pre, p.priv_part_base + (item_begin * p.Hkv + g) * G + gi, p.Hkv * G, n_priv);
 
-  // ---- common max over the work-group, then rescale and add the groups through LDS
-  float mx = m_t;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-  if ((tid & 63) == 0) red[tid >> 6] = mx;
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < kMergeThreads / kWave; ++i) mx = fmaxf(mx, red[i]);
-  const float c = (m_t == -INFINITY) ? 0.f : fast_exp2(m_t - mx);
-  osum[grp][d] = o_t * c;
-  if (d == 0) lsum[grp] = l_t * c;
+  // ---- the groups meet once: each leaves its (m, l, o) in LDS as it is, group 0 takes the common
+  // max, rescales and adds (a group's m and l are the same for all its head-dim elements)
+  osum[grp][d] = o_t;
+  if (d == 0) { msum[grp] = m_t; lsum[grp] = l_t; }
   __syncthreads();
   if (grp == 0) {
+    float mg[NGRP], mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < NGRP; ++k) { mg[k] = msum[k]; mx = fmaxf(mx, mg[k]); }
     float o = 0.f, L = 0.f;
 #pragma unroll
-    for (int k = 0; k < NGRP; ++k) { o += osum[k][d]; L += lsum[k]; }
+    for (int k = 0; k < NGRP; ++k) {
+      const float c = (mg[k] == -INFINITY) ? 0.f : fast_exp2(mg[k] - mx);
+      o = fmaf(osum[k][d], c, o);
+      L = fmaf(lsum[k], c, L);
+    }
     const long long ob = ((long long)s * p.Hq + h) * D + d;
     const float val = o / L;
     if constexpr (sizeof(T) == 4) reinterpret_cast<float*>(p.out)[ob] = val;
