@@ -223,7 +223,8 @@ typedef struct {
   uint32_t struct_size;
   uint32_t flags;               /* PASTA_DECODE_* */
   int32_t layer;
-  int32_t n_streams;            /* n >= 1 query tokens, at most max_requests * max_streams */
+  int32_t n_streams;            /* n >= 1 query tokens, at most max_requests * max_streams
+                                   (and at most 65535 per call: E_CAPACITY beyond) */
   const int32_t *request_id;    /* HOST [n] */
   const int32_t *stream_id;     /* HOST [n]; (request, stream) pairs distinct */
   const int32_t *position;      /* HOST [n] or NULL: position id >= 0 of each query token;

@@ -31,9 +31,10 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
   __shared__ float lsum[NGRP];
   const int tid = threadIdx.x;
   const int grp = tid / D, d = tid % D;
-  // work-group index = (s * G + gi) * Hkv + g: index mod Hkv is the kv head, as in the attention
-  // launch, so that with 8 kv heads the partials are read on the XCD whose L2 holds them
-  const int g = blockIdx.x % p.Hkv, gi = (blockIdx.x / p.Hkv) % G, s = blockIdx.x / p.Hq;
+  // grid (Hkv, G, streams): the linear work-group index is (s * G + gi) * Hkv + g, whose remainder
+  // mod Hkv is the kv head, as in the attention launch, so that with 8 kv heads the partials are
+  // read on the XCD whose L2 holds them (three grid dimensions spare the kernel the divisions)
+  const int g = blockIdx.x, gi = blockIdx.y, s = blockIdx.z;
   const int h = g * G + gi;
   const int32_t* meta = meta_of(p);
   const DevStream* stp = reinterpret_cast<const DevStream*>(meta + p.off_streams) + s;

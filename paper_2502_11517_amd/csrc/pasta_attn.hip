@@ -239,7 +239,7 @@ int launch_private_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
 }
 template <typename T, int D>
 int launch_merge_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
-  if (grid.x >= (unsigned)kMergeManyRows) {
+  if (grid.x * grid.y * grid.z >= (unsigned)kMergeManyRows) {
     switch (G) {
       case 1: k_merge<T, D, 1, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
       case 2: k_merge<T, D, 2, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
@@ -266,7 +266,7 @@ int launch_private(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeP
   return D == 64 ? launch_private_g<uint16_t, 64>(h->G, grid, st, p)
                  : launch_private_g<uint16_t, 128>(h->G, grid, st, p);
 }
-int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {  // grid = n * Hq
+int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {  // grid = (Hkv, G, n)
   const int D = h->cfg.head_dim;
   if (h->cfg.dtype == PASTA_F32)
     return D == 64 ? launch_merge_g<float, 64>(h->G, grid, st, p) : launch_merge_g<float, 128>(h->G, grid, st, p);
@@ -645,6 +645,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
   if (a->layer < 0 || a->layer >= c.n_layers) return PASTA_E_STATE;
   const int n = a->n_streams;
   if (n < 1 || n > c.max_requests * c.max_streams) return PASTA_E_INVAL;
+  if (n > 65535) return PASTA_E_CAPACITY;  // one grid dimension of the merge launch counts the query rows
   if (!a->request_id || !a->stream_id) return PASTA_E_INVAL;
   const bool plan_only = a->flags & PASTA_DECODE_PLAN_ONLY;
   if (!plan_only && (!a->q || !a->out)) return PASTA_E_INVAL;
@@ -1028,7 +1029,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     }
     if (a->prof_event_stop && hipEventRecord((hipEvent_t)a->prof_event_stop, st) != hipSuccess)
       return PASTA_E_DEVICE;
-    rc = launch_merge(h, dim3((unsigned)n * c.n_q_heads), st, p);
+    rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p);
     if (rc != PASTA_OK) return rc;
     if (meta_slot >= 0) {
       if (hipEventRecord(h->ring_ev[meta_slot], st) != hipSuccess) return PASTA_E_DEVICE;
