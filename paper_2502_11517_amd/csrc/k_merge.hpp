@@ -70,10 +70,14 @@ __global__ __launch_bounds__(NT) void k_merge(DecodeParams p) {
       const int n_valid = min(UNR, (n - i0 + NGRP - 1) / NGRP);
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
-        const int i = i0 + (u < n_valid ? u : 0) * NGRP;  // lanes past the end repeat a valid row
-        const int row = i < n_a ? a0 + i * a_step : b0 + (i - n_a) * b_step;
-        ml[u] = p.part_ml[row];
-        a[u] = p.part_acc[(long long)row * D + d];
+        ml[u] = make_float2(-INFINITY, 0.f);
+        a[u] = 0.f;
+        if (u < n_valid) {  // the same in all lanes of a wave: a scalar branch, no load for what is not there
+          const int i = i0 + u * NGRP;
+          const int row = i < n_a ? a0 + i * a_step : b0 + (i - n_a) * b_step;
+          ml[u] = p.part_ml[row];
+          a[u] = p.part_acc[(long long)row * D + d];
+        }
       }
       fold(ml, a, n_valid);
     }
