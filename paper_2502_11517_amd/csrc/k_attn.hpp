@@ -177,6 +177,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   n_tok = __builtin_amdgcn_readfirstlane(n_tok);
   const int n_blocks = (n_tok + kBlock - 1) / kBlock;
   req = __builtin_amdgcn_readfirstlane(req);
+  R = __builtin_amdgcn_readfirstlane(R);
   g = __builtin_amdgcn_readfirstlane(g);
   slot0 = __builtin_amdgcn_readfirstlane(slot0);
   stride = __builtin_amdgcn_readfirstlane(stride);
@@ -532,6 +533,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     f32x4 pc[4][4];
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
+      if (pass * 8 >= R) break;  // (R is the same for the whole work-group: private items stop after one pass)
       const int rr = pass * 8 + r0;
       const f32x4* src = reinterpret_cast<const f32x4*>(&lds.tile[0]) + rr * 32 + (c ^ rr);  // + 1024 per wave
 #pragma unroll
@@ -543,6 +545,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     }
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
+      if (pass * 8 >= R) break;
       const int rr = pass * 8 + r0;
       const float ma = fmaxf(fmaxf(mw4[pass][0], mw4[pass][1]), fmaxf(mw4[pass][2], mw4[pass][3]));
       const float mr = ma == -INFINITY ? 0.f : ma;  // -inf: the row saw nothing in this item (dense-mask mode)
