@@ -786,7 +786,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       chunk_tokens = std::max<int64_t>(kTile, pc_weighted * Hkv / kNumCUs / kTile * kTile);
       priv_chunk = 128;
       if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
-      if (h->tune_priv_chunk >= kTile) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / kTile * kTile, kGatherMax);
+      if (h->tune_priv_chunk >= 32) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / 32 * 32, kGatherMax);  // whole 32-token blocks
     }
     // private items
     std::vector<DevStream> streams(n);
