@@ -396,6 +396,44 @@ def test_maintained_lists_on_random_fork_histories_equal_dense_mask(seed):
     s.close()
 
 
+# ------------------------------------------------------------------------- random shapes
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_layouts_and_append_modes(seed):
+    """Seeded random draws over what the launch plan depends on: heads per group, kv heads, prefix
+    length (none, short, long enough for the long-chunk kernel variant), number and lengths of the
+    streams, interleave, layout, contiguous or paged pool, eager or deferred append, two steps."""
+    rng = np.random.default_rng(1000 + seed)
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    layout = LAYOUTS[int(rng.integers(2))]
+    if seed % 3 == 2:  # paged, several requests
+        w = W.config4(n_requests=int(rng.integers(1, 4)), seed=2000 + seed, pmin=int(rng.integers(1, 300)),
+                      pmax=int(rng.integers(300, 5000)), page_tokens=int(rng.choice([8, 16, 32])))
+        steps = 1
+    else:
+        n = int(rng.integers(1, 11))
+        prefix = int(rng.choice([0, 1, 37, 500, 3000, 11000])) + int(rng.integers(0, 64))
+        lengths = rng.integers(1, 300, size=n).tolist()
+        steps = 2
+        w = W.single_request("rand", "bf16", Hkv * G, Hkv, 128, 1.0, 3000 + seed, max(prefix, 1), lengths,
+                             ["random", "round_robin"][int(rng.integers(2))], steps=steps, k_std=128 ** -0.5)
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR))
+    s.append_events(w.n_prefill)
+    op.append_events(w.n_prefill)
+    keep = []
+    for step in range(steps):
+        if w.steps > 1:
+            hi = w.n_events(step)
+            s.append_events(hi, chunk=w.n, flags=B.APPEND_DEFER if (seed + step) % 2 else 0)
+            keep.append(getattr(s, "_keep_rows", None))
+            op.append_events(hi)
+        sel = None if w.n <= 12 else sorted(set(rng.choice(w.n, size=12, replace=False).tolist()))
+        _check_step(w, s, op, step, explicit=bool((seed + step) % 2), streams=sel, what=f"random shape {seed}, step {step}")
+    _check_pool(w, s, op)
+    s.close()
+
+
 # ------------------------------------------------------------------------- long prefix chunks
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_long_prefix_chunks_contiguous_pool_with_deferred_steps(layout):
