@@ -39,9 +39,9 @@ def main():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--layout", choices=["token", "head"], default="head")
     ap.add_argument("--event-every", type=int, default=33,
-                    help="time the attention kernel of every n-th step with a HIP event pair (each pair adds about 5 us "
-                         "to its step: at every 8th step the run reads 0.7 us per step slower than without events; 33 is "
-                         "co-prime with the 32 pools, so the samples cover all of them)")
+                    help="time the attention kernel of every n-th step with a HIP event pair attached to its dispatch "
+                         "(a timed dispatch costs its step about 5 us: at every 8th step the run reads 0.6 us per step "
+                         "slower than without events; 33 is co-prime with the 32 pools, so the samples cover all of them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
     ap.add_argument("--eager-append", action="store_true",

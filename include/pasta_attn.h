@@ -253,8 +253,10 @@ typedef struct {
                                    prefix work-groups, private items, partial rows,
                                    tokens per prefix chunk, common-prefix tokens
                                    summed over requests, metadata bytes, 0} */
-  void *prof_event_start;       /* hipEvent_t or NULL: recorded on the stream right */
-  void *prof_event_stop;        /* before / after the attention-partials kernel */
+  void *prof_event_start;       /* hipEvent_t or NULL (both or neither): they receive the start and the */
+  void *prof_event_stop;        /* end of the attention-partials kernel's execution (attached to its
+                                   dispatch; with PASTA_DECODE_NO_MFMA or F32: recorded on the stream
+                                   before and after that launch) */
 } pasta_decode_args;
 
 /* Errors: E_INVAL (see above), E_STATE (unknown stream in maintained mode,

@@ -4,6 +4,7 @@
 // at the pool tail (Figure 2c), and the launch plan.  Every step of the arithmetic runs in
 // the gfx950 kernels included below.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -1002,23 +1003,31 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       if (rope_q) p.q = q_rot;
       if (p.pend_rope) { p.k_pend = k_rot; p.pend_rope = 0; }
     }
-    if (a->prof_event_start && hipEventRecord((hipEvent_t)a->prof_event_start, st) != hipSuccess)
-      return PASTA_E_DEVICE;
+    // Profiling events: the matrix-core launch hands them to the dispatch itself, so they carry the
+    // start and the end of that kernel's execution (what a kernel trace reports) and put no packet of
+    // their own on the stream; around the vector-ALU form they are recorded on the stream.
+    const hipEvent_t ev0 = (hipEvent_t)a->prof_event_start, ev1 = (hipEvent_t)a->prof_event_stop;
+    const bool ev_in_dispatch = mfma && ev0 && ev1;
+    if (ev0 && !ev_in_dispatch && hipEventRecord(ev0, st) != hipSuccess) return PASTA_E_DEVICE;
     if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
+      auto launch = [&](auto kernel) {
+        if (ev_in_dispatch) hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kAttnThreads), 0, st, ev0, ev1, 0, p);
+        else kernel<<<dim3(grid), kAttnThreads, 0, st>>>(p);
+      };
       if (dense) {  // the variant that carries the dense-mask mode
-        if (h->lay.paged) k_attn<true, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-        else k_attn<false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+        if (h->lay.paged) launch(k_attn<true, true>);
+        else launch(k_attn<false, true>);
       } else {
         // prefix chunks of more than two 32-token blocks per wave: the variant whose loop has the
         // cheap addressing of plain blocks
         const bool long_items = n_prefix_wgs > 0 && chunk_tokens > 2 * 4 * 32;
         if (h->lay.paged) {
-          if (long_items) k_attn<true, false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-          else k_attn<true, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+          if (long_items) launch(k_attn<true, false, true>);
+          else launch(k_attn<true, false>);
         } else {
-          if (long_items) k_attn<false, false, true><<<dim3(grid), kAttnThreads, 0, st>>>(p);
-          else k_attn<false, false><<<dim3(grid), kAttnThreads, 0, st>>>(p);
+          if (long_items) launch(k_attn<false, false, true>);
+          else launch(k_attn<false, false>);
         }
       }
       if (take_pending) h->pending.active = false;
@@ -1027,8 +1036,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       rc = launch_private(h, dim3((waves + 3) / 4), st, p);
       if (rc != PASTA_OK) return rc;
     }
-    if (a->prof_event_stop && hipEventRecord((hipEvent_t)a->prof_event_stop, st) != hipSuccess)
-      return PASTA_E_DEVICE;
+    if (ev1 && !ev_in_dispatch && hipEventRecord(ev1, st) != hipSuccess) return PASTA_E_DEVICE;
     rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p);
     if (rc != PASTA_OK) return rc;
     if (meta_slot >= 0) {
