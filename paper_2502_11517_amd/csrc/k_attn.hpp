@@ -610,8 +610,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   }
   // shared-prefix items first: they are the longer ones (up to two blocks per wave against one)
   const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
-  // the longer items issue their loads first where a SIMD holds a wave of each kind
-  if ((int)blockIdx.x < n_prefix_wgs) __builtin_amdgcn_s_setprio(3);
+  // (a raised wave priority for the shared-prefix items, so that the longer items issue their loads
+  // first where a SIMD holds a wave of each kind, paid while the private items' compute was heavier;
+  // with the present kernel it costs 0.25 us per launch and is gone)
   if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE, LONG>(p, lds, meta, blockIdx.x);
   else attn_item<PAGED, true, DENSE, LONG>(p, lds, meta, blockIdx.x - n_prefix_wgs);
   if (pend_u >= 0) pend_store(pend_u, pend_val);
