@@ -27,7 +27,7 @@
 //     S^T[32 tok x 32 rows] = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows, B = Q rows);
 //   * online softmax in registers: a lane holds 16 tokens of one row, its partner lane
 //     (lane ^ 32) the other 16 -- one lane exchange per block for the row max;
-//   * P = 2^(S - m) goes to bf16 IN REGISTERS: the S^T accumulator layout is already the
+//   * P = 2^(scale S - m) goes to bf16 IN REGISTERS: the S^T accumulator layout is already the
 //     B-operand layout of the next MFMA for a suitable token order inside the contraction
 //     (slot (ks, half, e) <-> token 16 ks + 8 (e / 4) + 4 half + e % 4), and V^T is fetched
 //     from LDS with the transposing read in exactly that order;
