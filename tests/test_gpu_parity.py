@@ -4,6 +4,8 @@ bit-exact; outputs must be within max-abs 2e-2 AND relative-L2 1e-2 for bf16, 1e
 for fp32."""
 from __future__ import annotations
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -397,7 +399,7 @@ def test_maintained_lists_on_random_fork_histories_equal_dense_mask(seed):
 
 
 # ------------------------------------------------------------------------- random shapes
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("PASTA_RANDOM_SHAPES", "10"))))
 def test_random_shapes_layouts_and_append_modes(seed):
     """Seeded random draws over what the launch plan depends on: heads per group, kv heads, prefix
     length (none, short, long enough for the long-chunk kernel variant), number and lengths of the
