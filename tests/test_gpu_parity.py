@@ -126,6 +126,29 @@ def test_config3_prefix8k_8_streams_64_steps(layout):
     s.close()
 
 
+def test_config3_in_the_launch_configuration_of_the_bench():
+    """Config 3 at full size exactly as bench.py runs it: head-major pool, the step's eight rows
+    appended with PASTA_APPEND_DEFER (they ride with the decode launch), lists maintained by the
+    library; outputs, lse and gather maps of sampled steps against the oracle, the pool at the end."""
+    w = W.config3()
+    s = _session(w, kv_layout=B.HEAD_MAJOR)
+    op = OraclePool(w, head_major=True)
+    s.append_events(w.n_prefill)
+    op.append_events(w.n_prefill)
+    keep = []
+    for step in range(w.steps):
+        hi = w.n_events(step)
+        s.append_events(hi, chunk=w.n, flags=B.APPEND_DEFER)
+        keep.append(s._keep_rows)
+        if step in (0, 1, 2, 30, 62, 63):
+            op.append_events(hi)
+            _check_step(w, s, op, step, explicit=False, what=f"cfg3 as benched, step {step}")
+        else:
+            s.decode(step, explicit=False, want_lse=False)
+    _check_pool(w, s, op)
+    s.close()
+
+
 def test_config4_ragged_paged_batch():
     w = W.config4()
     for layout in LAYOUTS:
