@@ -162,10 +162,11 @@ def test_config4_ragged_paged_batch():
         s.close()
 
 
-def test_config5_long_context_nested_fork():
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_config5_long_context_nested_fork(layout):
     w = W.config5()
-    s = _session(w)
-    op = OraclePool(w).append_events(w.n_prefill)
+    s = _session(w, kv_layout=layout)
+    op = OraclePool(w, head_major=(layout == B.HEAD_MAJOR)).append_events(w.n_prefill)
     s.append_events(w.n_prefill)
     # a nested child, a root-level fork, and the longest stream; all 64 heads each
     pl, offs, st, ct, sd = w.lists(0)
