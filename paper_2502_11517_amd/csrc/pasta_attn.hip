@@ -238,26 +238,26 @@ int launch_private_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
   }
   return PASTA_OK;
 }
-template <typename T, int D>
-int launch_merge_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
-  if (grid.x * grid.y * grid.z >= (unsigned)kMergeManyRows) {
-    switch (G) {
-      case 1: k_merge<T, D, 1, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
-      case 2: k_merge<T, D, 2, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
-      case 4: k_merge<T, D, 4, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
-      case 8: k_merge<T, D, 8, kMergeThreadsSmall><<<grid, kMergeThreadsSmall, 0, st>>>(p); break;
-      default: return PASTA_E_INVAL;
-    }
-    return PASTA_OK;
-  }
+template <typename T, int D, int NT>
+int launch_merge_nt(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
   switch (G) {
-    case 1: k_merge<T, D, 1, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
-    case 2: k_merge<T, D, 2, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
-    case 4: k_merge<T, D, 4, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
-    case 8: k_merge<T, D, 8, kMergeThreads><<<grid, kMergeThreads, 0, st>>>(p); break;
+    case 1: k_merge<T, D, 1, NT><<<grid, NT, 0, st>>>(p); break;
+    case 2: k_merge<T, D, 2, NT><<<grid, NT, 0, st>>>(p); break;
+    case 4: k_merge<T, D, 4, NT><<<grid, NT, 0, st>>>(p); break;
+    case 8: k_merge<T, D, 8, NT><<<grid, NT, 0, st>>>(p); break;
     default: return PASTA_E_INVAL;
   }
   return PASTA_OK;
+}
+// Width of the merge work-groups: wide for steps with few output rows (a chain of latencies);
+// with many rows the launch is bound by the rate at which wavefronts start, so it gets as few
+// as the rows' parts can feed: one group of D threads when a row has about a batch of parts.
+template <typename T, int D>
+int launch_merge_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p, int64_t total_parts) {
+  const int64_t rows = (int64_t)grid.x * grid.y * grid.z;
+  if (rows < kMergeManyRows) return launch_merge_nt<T, D, kMergeThreads>(G, grid, st, p);
+  if (total_parts <= 8 * rows) return launch_merge_nt<T, D, D>(G, grid, st, p);
+  return launch_merge_nt<T, D, kMergeThreadsSmall>(G, grid, st, p);
 }
 
 int launch_private(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {
@@ -267,11 +267,14 @@ int launch_private(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeP
   return D == 64 ? launch_private_g<uint16_t, 64>(h->G, grid, st, p)
                  : launch_private_g<uint16_t, 128>(h->G, grid, st, p);
 }
-int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p) {  // grid = (Hkv, G, n)
+// grid = (Hkv, G, n); total_parts = partial rows that the launch reads, over all its output rows
+int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodeParams& p, int64_t total_parts) {
   const int D = h->cfg.head_dim;
   if (h->cfg.dtype == PASTA_F32)
-    return D == 64 ? launch_merge_g<float, 64>(h->G, grid, st, p) : launch_merge_g<float, 128>(h->G, grid, st, p);
-  return D == 64 ? launch_merge_g<uint16_t, 64>(h->G, grid, st, p) : launch_merge_g<uint16_t, 128>(h->G, grid, st, p);
+    return D == 64 ? launch_merge_g<float, 64>(h->G, grid, st, p, total_parts)
+                   : launch_merge_g<float, 128>(h->G, grid, st, p, total_parts);
+  return D == 64 ? launch_merge_g<uint16_t, 64>(h->G, grid, st, p, total_parts)
+                 : launch_merge_g<uint16_t, 128>(h->G, grid, st, p, total_parts);
 }
 
 int launch_append(pasta_attn* h, int layer, int n_rows, const void* k_new, const void* v_new,
@@ -1037,7 +1040,10 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       if (rc != PASTA_OK) return rc;
     }
     if (ev1 && !ev_in_dispatch && hipEventRecord(ev1, st) != hipSuccess) return PASTA_E_DEVICE;
-    rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p);
+    int64_t merge_parts = 0;  // every output row reads its request's prefix chunks and its stream's items
+    for (int i = 0; i < n; ++i)
+      merge_parts += (int64_t)(reqs[stream_req_idx[i]].n_chunks + streams[i].item_end - streams[i].item_begin) * c.n_q_heads;
+    rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p, merge_parts);
     if (rc != PASTA_OK) return rc;
     if (meta_slot >= 0) {
       if (hipEventRecord(h->ring_ev[meta_slot], st) != hipSuccess) return PASTA_E_DEVICE;
