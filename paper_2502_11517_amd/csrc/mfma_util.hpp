@@ -63,9 +63,9 @@ __device__ __forceinline__ int32_t scalar_load_i32(const int32_t* ptr, int idx) 
   return ((const_ptr)(uintptr_t)ptr)[idx];
 }
 
-// Phase clocks for kernel tuning (compiled in only with -DPASTA_PHASE_CLOCKS): thread 0 of every
+// Phase clocks for kernel tuning (compiled in only with -DPASTA_TUNING=2, which the library build never sets): thread 0 of every
 // work-group stores the 100 MHz wall clock at a few points into the tail of the partials buffer.
-#ifdef PASTA_PHASE_CLOCKS
+#if defined(PASTA_TUNING) && PASTA_TUNING >= 2
 #define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < 512) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
     __builtin_bit_cast(float2, (unsigned long long)__builtin_amdgcn_s_memrealtime()); } while (0)
 #else

@@ -28,7 +28,7 @@ namespace {
 
 constexpr uint32_t kMagic = 0x50415354u;  // "PAST"
 constexpr int kRing = 8;                  // metadata staging buffers in flight
-constexpr int kNumCUs = 256;              // MI355X
+constexpr int kNumCUs = 256;              // MI355X; planning default until the device has been asked
 constexpr int kTargetPrefixWgs = 768;     // most shared-prefix work-groups budgeted for
 
 struct Range { int32_t start, count, stride; };
@@ -72,11 +72,13 @@ struct pasta_attn {
     int32_t pos[kAppendInline]{};
     std::vector<int32_t> req_pend0, req_src0;  // per request: first deferred slot, its row in k_new
   } pending;
-  int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // PASTA_PREFIX_CHUNK / PASTA_PRIV_CHUNK (tokens; 0 = heuristic)
+  int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // forced chunk sizes (tokens; 0 = heuristic): set only by -DPASTA_TUNING builds
   // device-side readiness (deferred so that the host logic works without a GPU)
   bool device_ready = false;
   char* pinned = nullptr;                // kRing * meta_bytes
   hipEvent_t ring_ev[kRing]{};
+  int ring_ev_made = 0;                  // events created so far (all kRing once the device is ready)
+  int device = 0, n_cus = kNumCUs;       // the device current at first use and its compute-unit count
   bool ring_used[kRing]{};
   int ring_next = 0;
 };
@@ -161,17 +163,30 @@ void carve(pasta_attn* h) {
 
 int ensure_device(pasta_attn* h) {
   if (h->device_ready) return PASTA_OK;
-  if (hipHostMalloc((void**)&h->pinned, h->meta_bytes * kRing, hipHostMallocDefault) != hipSuccess) {
+  // every step is skipped on re-entry once it has succeeded, so a failure leaks nothing
+  if (!h->pinned && hipHostMalloc((void**)&h->pinned, h->meta_bytes * kRing, hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
     h->pinned = nullptr;
     return PASTA_E_DEVICE;
   }
-  for (int i = 0; i < kRing; ++i)
-    if (hipEventCreateWithFlags(&h->ring_ev[i], hipEventDisableTiming) != hipSuccess) return PASTA_E_DEVICE;
+  for (; h->ring_ev_made < kRing; ++h->ring_ev_made)
+    if (hipEventCreateWithFlags(&h->ring_ev[h->ring_ev_made], hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      return PASTA_E_DEVICE;
+    }
+  int n_cu = 0;
+  if (hipGetDevice(&h->device) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, h->device) != hipSuccess || n_cu < 1) {
+    (void)hipGetLastError();
+    return PASTA_E_DEVICE;
+  }
+  h->n_cus = n_cu;
   if (h->cfg.page_tokens) {
     if (hipMemcpy((char*)h->cfg.workspace + h->off_page_table, h->page_table.data(),
-                  h->page_table.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
+                  h->page_table.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipGetLastError();
       return PASTA_E_DEVICE;
+    }
   }
   if (h->cfg.rope_theta > 0.f) {  // theta^(-2f/D) / (2 pi) in fp64: angles are taken in revolutions
     const int D = h->cfg.head_dim;
@@ -179,8 +194,10 @@ int ensure_device(pasta_attn* h) {
     for (int f = 0; f < D / 2; ++f)
       tab[f] = std::pow((double)h->cfg.rope_theta, -2.0 * f / D) / 6.283185307179586476925286766559;
     if (hipMemcpy((char*)h->cfg.workspace + h->off_rope, tab.data(), tab.size() * sizeof(double),
-                  hipMemcpyHostToDevice) != hipSuccess)
+                  hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipGetLastError();
       return PASTA_E_DEVICE;
+    }
   }
   h->device_ready = true;
   return PASTA_OK;
@@ -390,19 +407,26 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
   if (cfg->page_tokens) {
     if (!cfg->page_table) return fail(PASTA_E_INVAL);
     const size_t n = (size_t)cfg->max_requests * cfg->pages_per_request;
-    h->page_table.assign(cfg->page_table, cfg->page_table + n);
-    for (int32_t pp : h->page_table)
-      if (pp < 0 || pp >= cfg->n_phys_pages) return fail(PASTA_E_INVAL);
+    try {
+      h->page_table.assign(cfg->page_table, cfg->page_table + n);
+      std::vector<uint8_t> taken((size_t)cfg->n_phys_pages, 0);  // entries must be distinct: a page named twice
+      for (int32_t pp : h->page_table) {                         // would alias two logical pages
+        if (pp < 0 || pp >= cfg->n_phys_pages || taken[pp]) return fail(PASTA_E_INVAL);
+        taken[pp] = 1;
+      }
+    } catch (const std::bad_alloc&) { return fail(PASTA_E_NOMEM); }
     h->cfg.page_table = nullptr;  // the caller's array is not kept
   }
+#ifdef PASTA_TUNING  // tuning builds only: forced chunk sizes from the environment
   if (const char* e = std::getenv("PASTA_PREFIX_CHUNK")) h->tune_prefix_chunk = std::atoi(e);
   if (const char* e = std::getenv("PASTA_PRIV_CHUNK")) h->tune_priv_chunk = std::atoi(e);
+#endif
   try {
     h->tail.assign(cfg->max_requests, 0);
     h->tail_before.assign(cfg->max_requests, 0);
     h->streams.resize((size_t)cfg->max_requests * cfg->max_streams);
   } catch (...) { return fail(PASTA_E_NOMEM); }
-#ifdef PASTA_PHASE_CLOCKS
+#if defined(PASTA_TUNING) && PASTA_TUNING >= 2
   std::fprintf(stderr, "PASTA_CLOCKS byte offset in workspace: %zu\n", h->off_ml + (size_t)(h->part_rows_cap - 8192) * 8);
 #endif
   *out = h;
@@ -414,9 +438,7 @@ extern "C" int32_t pasta_attn_destroy(pasta_attn* h) {
   if (h->magic != kMagic) return PASTA_E_STATE;
   if (h->device_ready) (void)flush_pending(h);  // a deferred append still owes its copy
   h->magic = 0;
-  if (h->device_ready) {
-    for (int i = 0; i < kRing; ++i) (void)hipEventDestroy(h->ring_ev[i]);
-  }
+  for (int i = 0; i < h->ring_ev_made; ++i) (void)hipEventDestroy(h->ring_ev[i]);
   if (h->pinned) (void)hipHostFree(h->pinned);
   if (h->mask_pinned) { (void)hipHostFree(h->mask_pinned); (void)hipEventDestroy(h->mask_ev); }
   delete h;
@@ -496,10 +518,13 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
 
   // ---- enqueue K1, or leave the copy to the next decode_step (PASTA_APPEND_DEFER)
   int rc = PASTA_OK;
+  // At most one deferred append is outstanding, and the slots it covers are the newest of their
+  // requests: any later append -- also one that only reserves slots for the caller's own kernel --
+  // first sends the deferred rows to the pool (a deferred append exists only on a ready device).
+  rc = flush_pending(h);
+  if (rc != PASTA_OK) return rc;
   if (!reserve_only) {
     rc = ensure_device(h);
-    if (rc != PASTA_OK) return rc;
-    rc = flush_pending(h);  // at most one deferred append is outstanding
     if (rc != PASTA_OK) return rc;
     bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline;
     std::vector<int32_t> p0, s0;
@@ -667,6 +692,10 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
   const bool dense = a->flags & PASTA_DECODE_DENSE_MASK;
   if (dense && (c.dtype != PASTA_BF16 || c.head_dim != 128 || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
+  if (!plan_only) {  // before planning: the plan is sized to the device's compute-unit count
+    const int rc0 = ensure_device(h);
+    if (rc0 != PASTA_OK) return rc0;
+  }
 
   try {
     // ---- lists + validation
@@ -787,7 +816,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     // items stay at 128 tokens: they are few and their rows are scattered.
     int64_t priv_chunk = kPrivChunk, chunk_tokens = kTile;
     if (mfma) {
-      chunk_tokens = std::max<int64_t>(kTile, pc_weighted * Hkv / kNumCUs / kTile * kTile);
+      chunk_tokens = std::max<int64_t>(kTile, pc_weighted * Hkv / h->n_cus / kTile * kTile);
       priv_chunk = 128;
       if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
       if (h->tune_priv_chunk >= 32) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / 32 * 32, kGatherMax);  // whole 32-token blocks
@@ -904,8 +933,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     if (plan_only) return PASTA_OK;
 
     // ---- enqueue
-    int rc = ensure_device(h);
-    if (rc != PASTA_OK) return rc;
+    int rc = PASTA_OK;
     hipStream_t st = (hipStream_t)c.hip_stream;
     int meta_slot = -1;  // pinned staging slot that this call's kernels read, if any
     // a deferred append rides along with the matrix-core launch of its layer; otherwise K1 runs now
@@ -980,7 +1008,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     p.Hq = c.n_q_heads;
     p.Hkv = Hkv;
     p.scale_log2e = c.softmax_scale * kLog2e;
-#ifdef PASTA_PHASE_CLOCKS
+#if defined(PASTA_TUNING) && PASTA_TUNING >= 2
     p.clock_row0 = h->part_rows_cap - 8192 + (a->layer & 1) * 4096;  // the last 64 KiB of the (m, l) array, two halves
 #endif
     p.single_req = reqs.size() == 1 ? 1 : 0;

@@ -100,7 +100,7 @@ struct DecodeParams {
   int priv_part_base;   // private partial row = priv_part_base + ((item*Hkv + g)*G + i)
   int Hq, Hkv;
   float scale_log2e;    // softmax_scale * log2(e): logits are kept in log2 units
-#ifdef PASTA_PHASE_CLOCKS
+#if defined(PASTA_TUNING) && PASTA_TUNING >= 2
   long long clock_row0; // first float2 slot of the phase-clock area (tuning builds only)
 #endif
   // A deferred append (PASTA_APPEND_DEFER) rides along: its rows are read from k_pend / v_pend

@@ -88,6 +88,15 @@ def test_create_validation_and_query_mode():
     with pytest.raises(B.PastaError) as e:
         B.PastaAttn(pc, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc), page_table=[[0, 4]])
     assert e.value.code == B.E_INVAL
+    # ... and distinct: a physical page named twice would alias two logical pages
+    with pytest.raises(B.PastaError) as e:
+        B.PastaAttn(pc, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc), page_table=[[3, 3]])
+    assert e.value.code == B.E_INVAL
+    pc2 = B.make_config(**{**ok, "page_tokens": 16, "n_phys_pages": 4, "pages_per_request": 2, "max_requests": 2})
+    with pytest.raises(B.PastaError) as e:  # across requests too
+        B.PastaAttn(pc2, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc2), page_table=[[0, 1], [2, 0]])
+    assert e.value.code == B.E_INVAL
+    B.PastaAttn(pc2, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc2), page_table=[[0, 1], [2, 3]]).destroy()
 
 
 def test_slots_follow_call_order_per_request():

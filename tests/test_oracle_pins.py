@@ -680,3 +680,13 @@ def test_interpreter_invariants_on_synthetic_traces(seed):
         if t["new"]:
             prom = [m for m in main if m["slot"] == t["slot"] - 1][0]
             assert t["pos"] == prom["pos"] + 1
+
+
+def test_committed_fixtures_are_what_their_script_writes():
+    """tests/golden/make_fixtures.py derives the two timeline fixtures from the numbers the paper
+    prints (it calls neither the library nor the oracle); the committed files must be its output."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(HERE, "golden", "make_fixtures.py"), "--check"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr

@@ -60,11 +60,28 @@ def tolerances(dtype: str):
 
 
 def check_close(got64: np.ndarray, ref64: np.ndarray, dtype: str, what: str = ""):
+    """The parity bar, four checks that must all hold (rows = the last axis, one (stream, head) each):
+    global max|d| <= atol; global relative L2 <= rtol; relative L2 of EVERY row <= rtol; and element by
+    element |d| <= rtol * (max|ref_row| + |ref|) -- the absolute part scaled to the row's magnitude, since
+    outputs of long softmaxes are small and a fixed 2e-2 would pass anything there."""
     atol, rtol = tolerances(dtype)
+    assert got64.shape == ref64.shape, f"{what}: shape {got64.shape} != {ref64.shape}"
+    assert np.all(np.isfinite(got64)), f"{what}: non-finite output"
     d = got64 - ref64
     max_abs = float(np.max(np.abs(d))) if d.size else 0.0
     rel = float(np.linalg.norm(d.ravel()) / max(np.linalg.norm(ref64.ravel()), 1e-300))
-    assert np.all(np.isfinite(got64)), f"{what}: non-finite output"
     assert max_abs <= atol, f"{what}: max|d|={max_abs:.3e} > {atol}"
     assert rel <= rtol, f"{what}: rel L2={rel:.3e} > {rtol}"
+    if d.size:
+        D = d.shape[-1]
+        d2, r2 = d.reshape(-1, D), ref64.reshape(-1, D)
+        row_ref = np.linalg.norm(r2, axis=1)
+        row_rel = np.linalg.norm(d2, axis=1) / np.maximum(row_ref, 1e-300)
+        row_rel = np.where((row_ref == 0) & (np.linalg.norm(d2, axis=1) == 0), 0.0, row_rel)
+        worst = int(np.argmax(row_rel))
+        assert row_rel[worst] <= rtol, f"{what}: row {worst} of {len(row_rel)}: rel L2={row_rel[worst]:.3e} > {rtol}"
+        bound = rtol * (np.max(np.abs(r2), axis=1, keepdims=True) + np.abs(r2))
+        bad = np.abs(d2) > bound
+        assert not bad.any(), (f"{what}: {int(bad.sum())} elements beyond rtol*(max|ref_row|+|ref|); first at row "
+                               f"{int(np.argwhere(bad)[0][0])} col {int(np.argwhere(bad)[0][1])}")
     return max_abs, rel
