@@ -96,8 +96,10 @@ typedef struct {
                              n_layers * rows_per_layer * Hkv * D elements */
   void *v_pool;           /* DEVICE, same shape */
   const int32_t *page_table; /* HOST [max_requests][pages_per_request], copied at
-                             create (paged mode; NULL otherwise).  Entries must be
-                             distinct and in [0, n_phys_pages). */
+                             create (paged mode; NULL otherwise).  A request's assigned
+                             pages come first, each in [0, n_phys_pages) and distinct over
+                             the whole table; -1 = no page assigned (only after the
+                             assigned ones): the request's capacity ends there. */
   void *workspace;        /* DEVICE, borrowed, 256-byte aligned */
   uint64_t workspace_bytes; /* in: bytes provided; query mode writes bytes needed */
   void *hip_stream;       /* hipStream_t of the caller; all work is enqueued here */

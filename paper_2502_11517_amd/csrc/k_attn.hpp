@@ -320,9 +320,12 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   }
   BlockRegs br;
   const bool has1 = w < n_blocks, has2 = w + 4 < n_blocks;
-  // Block loads, then Q into LDS.  Written once per (has1, has2) case: how many loads stand
-  // behind Q's decides how long Q is waited for, and only inside one straight-line case is
-  // that count a constant -- merged, the wait would be for everything, the blocks included.
+  // Block loads, then Q into LDS.  Everything from here to the end of the wave's first block is
+  // written once per (has1, has2) case, as straight-line code of its own: how many loads stand
+  // behind Q's, and behind the first block's, decides how long each is waited for, and only
+  // inside one straight-line case are those counts constants -- where the cases merge, every
+  // wait for a load that went straight into LDS becomes a wait for everything, the second block
+  // included.
   auto issue_blocks_finish_q = [&](auto h1, auto h2) {
     if constexpr (h1.value) dma_block(w);
     if constexpr (h2.value) load_block(br, w + 4, std::false_type{});
@@ -330,25 +333,21 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     // Q has landed once at most the block loads issued behind it are outstanding
     wait_vmcnt<h2.value ? 32 : (h1.value ? 16 : 0)>();
   };
-  if (has2) issue_blocks_finish_q(std::true_type{}, std::true_type{});
-  else if (has1) issue_blocks_finish_q(std::true_type{}, std::false_type{});
-  else issue_blocks_finish_q(std::false_type{}, std::false_type{});
 
-  if (p.dbg_rows && g == 0 && row0 == 0 && !listed) {  // listed items reported their rows while expanding
-    const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
-    for (int j = tid; j < n_tok; j += kAttnThreads) {
-      const int phys = phys_of(j);
-      if constexpr (GATHER) {
-        p.dbg_rows[gather_pos + j] = phys;
-      } else {
-        for (int k = 0; k < n_req_streams; ++k)
-          p.dbg_rows[streams[req_streams ? req_streams[k] : k].gather_base + gather_pos + j] = phys;
+  auto report_rows = [&]() {
+    if (p.dbg_rows && g == 0 && row0 == 0 && !listed) {  // listed items reported their rows while expanding
+      const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
+      for (int j = tid; j < n_tok; j += kAttnThreads) {
+        const int phys = phys_of(j);
+        if constexpr (GATHER) {
+          p.dbg_rows[gather_pos + j] = phys;
+        } else {
+          for (int k = 0; k < n_req_streams; ++k)
+            p.dbg_rows[streams[req_streams ? req_streams[k] : k].gather_base + gather_pos + j] = phys;
+        }
       }
     }
-  }
-  lds_barrier();  // Q visible to every wave; the only barrier before the end of the item, and it
-                  // does not wait for the block loads still in flight
-  PASTA_CLK(2);
+  };
 
   f32x16 O[4];  // O^T M-tile mt: d = 32 mt + 8 (i / 4) + 4 hh + i % 4, row l32
   float m_run = -INFINITY, l_run = 0.f;  // row l32; l_run covers this lane's 16 tokens of every block
@@ -369,11 +368,11 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
                 (2 * cblk + ((bl >> 1) & 1)) * 16 + (bl & 1) * 8;
   }
 
-  auto compute_block = [&](int b, auto first) {
+  auto compute_block = [&](int b, auto first, auto h2) {  // h2: a second block is in flight behind the first
     if constexpr (first.value) {
       // the first block was loaded straight into the tile, K before V: K is there once only V's 8
       // loads and the second block's 16 register loads (if any) are still outstanding
-      if (has2) wait_vmcnt<24>(); else wait_vmcnt<8>();
+      wait_vmcnt<h2.value ? 24 : 8>();
       PASTA_CLK(3);
     } else {
       // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
@@ -463,7 +462,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
         for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
     }
     if constexpr (first.value) {  // now V of the block loaded straight into the tile is needed
-      if (has2) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      wait_vmcnt<h2.value ? 16 : 0>();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     // P^T as B operand: contraction step ks holds registers 8 ks .. 8 ks + 7
@@ -500,11 +499,21 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   };
 
   // this wave's blocks w, w + 4, ...
-  if (has1) {
-    compute_block(w, std::true_type{});
-    PASTA_CLK(4);
-    for (int b = w + 4; b < n_blocks; b += 4) compute_block(b, std::false_type{});
-  }
+  auto first_part = [&](auto h1, auto h2) {
+    issue_blocks_finish_q(h1, h2);
+    report_rows();
+    lds_barrier();  // Q visible to every wave; the only barrier before the end of the item, and it
+                    // does not wait for the block loads still in flight
+    PASTA_CLK(2);
+    if constexpr (h1.value) {
+      compute_block(w, std::true_type{}, h2);
+      PASTA_CLK(4);
+    }
+  };
+  if (has2) first_part(std::true_type{}, std::true_type{});
+  else if (has1) first_part(std::true_type{}, std::false_type{});
+  else first_part(std::false_type{}, std::false_type{});
+  for (int b = w + 4; b < n_blocks; b += 4) compute_block(b, std::false_type{}, std::false_type{});
   PASTA_CLK(6);
 
   // ---- combine the four waves.  Each wave parks its (unscaled) O^T in its OWN tile area as soon

@@ -50,6 +50,7 @@ struct pasta_attn {
   int64_t rows_per_layer = 0, layer_elems = 0, req_capacity = 0;
   Layout lay{};
   std::vector<int32_t> page_table;
+  std::vector<int32_t> req_pages;        // paged mode: pages assigned to each request (its capacity)
   std::vector<int64_t> tail;             // per request
   std::vector<int64_t> tail_before;      // tails before the latest layer-0 append
   std::vector<StreamState> streams;      // [max_requests * max_streams]
@@ -409,10 +410,19 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
     const size_t n = (size_t)cfg->max_requests * cfg->pages_per_request;
     try {
       h->page_table.assign(cfg->page_table, cfg->page_table + n);
-      std::vector<uint8_t> taken((size_t)cfg->n_phys_pages, 0);  // entries must be distinct: a page named twice
-      for (int32_t pp : h->page_table) {                         // would alias two logical pages
-        if (pp < 0 || pp >= cfg->n_phys_pages || taken[pp]) return fail(PASTA_E_INVAL);
-        taken[pp] = 1;
+      // a request's assigned pages come first, -1 ("no page") after them; assigned pages must be
+      // distinct over the whole table: a page named twice would alias two logical pages
+      std::vector<uint8_t> taken((size_t)cfg->n_phys_pages, 0);
+      h->req_pages.assign(cfg->max_requests, 0);
+      for (int r = 0; r < cfg->max_requests; ++r) {
+        bool ended = false;
+        for (int k = 0; k < cfg->pages_per_request; ++k) {
+          const int32_t pp = h->page_table[(size_t)r * cfg->pages_per_request + k];
+          if (pp == -1) { ended = true; continue; }
+          if (ended || pp < 0 || pp >= cfg->n_phys_pages || taken[pp]) return fail(PASTA_E_INVAL);
+          taken[pp] = 1;
+          h->req_pages[r] = k + 1;
+        }
       }
     } catch (const std::bad_alloc&) { return fail(PASTA_E_NOMEM); }
     h->cfg.page_table = nullptr;  // the caller's array is not kept
@@ -485,7 +495,7 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
       if (r < 0 || r >= c.max_requests || s < 0 || s >= c.max_streams) return PASTA_E_INVAL;
       if (par < -1 || par >= c.max_streams || par == s) return PASTA_E_INVAL;
       const int64_t slot = t2[r];
-      if (slot >= h->req_capacity) return PASTA_E_CAPACITY;
+      if (slot >= (c.page_tokens ? (int64_t)h->req_pages[r] << h->page_shift : h->req_capacity)) return PASTA_E_CAPACITY;
       if (!commit) {  // replay: same slots as the layer-0 call, lists untouched
         if (slot >= h->tail[r]) return PASTA_E_STATE;
         slots[i] = (int32_t)slot;

@@ -359,10 +359,9 @@ def config4(n_requests: int = 16, seed: int = 1004, pmin: int = 256, pmax: int =
     perm = rng.permutation(n_phys).astype(np.int32)
     table = np.zeros((n_requests, ppr), np.int32)
     pos = 0
-    spare = perm[sum(need):]
     for r in range(n_requests):
         table[r, :need[r]] = perm[pos:pos + need[r]]
-        table[r, need[r]:] = spare[0]  # never addressed: beyond the request's tail
+        table[r, need[r]:] = -1  # no page assigned: beyond the request's tail
         pos += need[r]
     w = Workload(name="cfg4_ragged_paged16", dtype="bf16", Hq=32, Hkv=8, D=128, scale=1.0, seed=seed,
                  max_requests=n_requests, page_tokens=page_tokens, n_phys_pages=n_phys,

@@ -97,6 +97,17 @@ def test_create_validation_and_query_mode():
         B.PastaAttn(pc2, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc2), page_table=[[0, 1], [2, 0]])
     assert e.value.code == B.E_INVAL
     B.PastaAttn(pc2, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc2), page_table=[[0, 1], [2, 3]]).destroy()
+    # -1 = no page assigned: only behind the assigned ones, and the request's capacity ends there
+    with pytest.raises(B.PastaError) as e:
+        B.PastaAttn(pc2, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc2), page_table=[[-1, 1], [2, 3]])
+    assert e.value.code == B.E_INVAL
+    h = B.PastaAttn(pc2, FAKE, FAKE, FAKE, B.query_workspace_bytes(pc2), page_table=[[0, 1], [2, -1]])
+    assert len(_reserve(h, [0] * 32, [0] * 32)) == 32
+    assert len(_reserve(h, [1] * 16, [0] * 16)) == 16
+    with pytest.raises(B.PastaError) as e:
+        _reserve(h, [1], [0])
+    assert e.value.code == B.E_CAPACITY
+    h.destroy()
 
 
 def test_slots_follow_call_order_per_request():
