@@ -276,34 +276,78 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   };
   u32x4* ktw = lds.tile[w].kt;
   u32x4* vtw = lds.tile[w].vt;
-  // Block b straight into this wave's LDS tile, no registers in between: one such load writes
+  // Loads that go straight into this wave's LDS tile, no registers in between: one such load writes
   // 64 consecutive 16-byte pieces (lane l at piece l of the destination), so instruction i fills
   // rows 4 i .. 4 i + 3 and the swizzle moves to the global side -- the lane whose LDS place is
-  // position (lane & 15) of row r fetches piece (lane & 15) ^ (r & 15) of that row.
-  auto dma_block = [&](int b) {
-    long long off[8];
-    bool pnd[8];
+  // position (lane & 15) of row r fetches piece (lane & 15) ^ (r & 15) of that row.  They are
+  // BUFFER loads (32-bit offsets from the layer's base: the host sends no pool of 4 GiB or more per
+  // layer this way): the compiler counts a buffer load into LDS like any vector-memory load, whereas
+  // with the flat-encoded form in flight it turns every wait it inserts itself -- in front of the
+  // transposing LDS reads, in front of the first use of a register load -- into a wait for ALL loads,
+  // which would hold the first block's P V until the second block has arrived.  A block that holds
+  // rows of a deferred append (they live in the caller's k_new / v_new, anywhere in memory) goes
+  // through registers instead.
+  const __amdgpu_buffer_rsrc_t k_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kb), 0, -1, kRawBuffer);
+  const __amdgpu_buffer_rsrc_t v_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vb), 0, -1, kRawBuffer);
+  typedef __attribute__((address_space(3))) void* lds_ptr;
+  struct DmaRows { uint32_t off[8]; bool any_pend; };
+  auto dma_rows = [&](int b) -> DmaRows {  // K-side offsets of block b's rows for this lane's LDS places
+    DmaRows d;
+    bool pend = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = rbase + 4 * i;
-      const int j = min(b * kBlock + r, n_tok - 1);
-      off[i] = src_of(j, pnd[i]) + (piece ^ (r & 15)) * 16;
+      const int j = min(b * kBlock + r, n_tok - 1);  // rows past the end repeat the last one
+      bool pn;
+      const long long o = src_of(j, pn);
+      pend = pend || pn;
+      d.off[i] = (uint32_t)o + (uint32_t)((piece ^ (r & 15)) * 16);
     }
-    // all of K first: S = K Q^T can start while V is still on its way
+    d.any_pend = __builtin_amdgcn_ballot_w64(pend) != 0;
+    return d;
+  };
+  auto dma_half = [&](int b, const DmaRows& d, auto is_v) {  // K (or V) of block b -> kt (vt)
+    u32x4* dst = is_v.value ? vtw : ktw;
+    if (!d.any_pend) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_to_lds16((pnd[i] ? kpend : kb) + off[i], ktw + 64 * i);
+      for (int i = 0; i < 8; ++i) {  // the row offset is a multiple of 256: bits 4..7 hold the piece alone
+        const int r = rbase + 4 * i;
+        const uint32_t o = is_v.value ? d.off[i] ^ (uint32_t)(((r & 15) ^ v_swizzle(r)) << 4) : d.off[i];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v.value ? v_rs : k_rs, (lds_ptr)(dst + 64 * i), 16, o, 0, 0, 0);
+      }
+    } else {
+      // some row of the block is a deferred one: per-row 64-bit addresses through registers, waited
+      // for on the spot (rare: the newest rows of a list sit in its last block).  No flat-encoded
+      // load into LDS here either: one such path is enough to spoil the compiler's waits after it.
+      u32x4 tmp[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {  // the row offset is a multiple of 256: bits 4..7 hold the piece alone
-      const int r = rbase + 4 * i;
-      load_to_lds16((pnd[i] ? vpend : vb) + (off[i] ^ (((r & 15) ^ v_swizzle(r)) << 4)), vtw + 64 * i);
+      for (int i = 0; i < 8; ++i) {
+        const int r = rbase + 4 * i;
+        const int j = min(b * kBlock + r, n_tok - 1);
+        bool pn;
+        long long o = src_of(j, pn) + (piece ^ (r & 15)) * 16;
+        if (is_v.value) o ^= ((r & 15) ^ v_swizzle(r)) << 4;
+        tmp[i] = *reinterpret_cast<const u32x4*>((pn ? (is_v.value ? vpend : kpend) : (is_v.value ? vb : kb)) + o);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dst[64 * i + lane] = tmp[i];
     }
   };
-  // ---- everything this wave needs first is requested here, before anything is waited for:
-  // its share of the stacked Q rows (2 loads), its first block (16 loads into LDS), and its
-  // second block (16 loads into registers).  Loads return in issue order, so Q is waited for
-  // with the blocks still in flight.
+  auto load_half = [&](u32x4 (&dst)[8], int b, auto is_v) {  // K (or V) of block b -> registers, natural piece order
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int j = min(b * kBlock + rbase + 4 * i, n_tok - 1);
+      bool pn;
+      const long long o = src_of(j, pn) + piece * 16;
+      dst[i] = *reinterpret_cast<const u32x4*>((pn ? (is_v.value ? vpend : kpend) : (is_v.value ? vb : kb)) + o);
+    }
+  };
+  // ---- everything this wave needs first is requested here, before anything is waited for: its
+  // share of the stacked Q rows (2 loads), then -- in the order in which they are needed, because
+  // loads return in issue order -- K of its first block (into LDS), K of its second block (into
+  // registers), V of the first (LDS), V of the second (registers).
   {
-    const char* qg = reinterpret_cast<const char*>(p.q);
+    const __amdgpu_buffer_rsrc_t q_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.q), 0, -1, kRawBuffer);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {  // wave w fills pieces [128 w + 64 i, + 64) of lds.q: rows 8 w + 4 i + rbase
       const int r = 8 * w + 4 * i + rbase;
@@ -312,7 +356,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       if (r < R) {
         const int ra = row0 + r;  // row of the request's stack
         const int s = GATHER ? q_stream : (req_streams ? req_streams[ra / G] : ra / G);
-        load_to_lds16(qg + ((long long)s * p.Hq + (g * G + ra % G)) * 256 + gp * 16, dst);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(q_rs, (lds_ptr)dst, 16, (uint32_t)((s * p.Hq + (g * G + ra % G)) * 256 + gp * 16), 0, 0, 0);
       } else {
         dst[lane] = u32x4{0u, 0u, 0u, 0u};  // rows past R are zero
       }
@@ -320,19 +364,6 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   }
   BlockRegs br;
   const bool has1 = w < n_blocks, has2 = w + 4 < n_blocks;
-  // Block loads, then Q into LDS.  Everything from here to the end of the wave's first block is
-  // written once per (has1, has2) case, as straight-line code of its own: how many loads stand
-  // behind Q's, and behind the first block's, decides how long each is waited for, and only
-  // inside one straight-line case are those counts constants -- where the cases merge, every
-  // wait for a load that went straight into LDS becomes a wait for everything, the second block
-  // included.
-  auto issue_blocks_finish_q = [&](auto h1, auto h2) {
-    if constexpr (h1.value) dma_block(w);
-    if constexpr (h2.value) load_block(br, w + 4, std::false_type{});
-    PASTA_CLK(1);
-    // Q has landed once at most the block loads issued behind it are outstanding
-    wait_vmcnt<h2.value ? 32 : (h1.value ? 16 : 0)>();
-  };
 
   auto report_rows = [&]() {
     if (p.dbg_rows && g == 0 && row0 == 0 && !listed) {  // listed items reported their rows while expanding
@@ -367,30 +398,23 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       vrd[mt] = reinterpret_cast<const char*>(vtw) + (4 * hh + r2) * 256 + (mt ^ r2) * 64 +
                 (2 * cblk + ((bl >> 1) & 1)) * 16 + (bl & 1) * 8;
   }
-
-  auto compute_block = [&](int b, auto first, auto h2) {  // h2: a second block is in flight behind the first
-    if constexpr (first.value) {
-      // the first block was loaded straight into the tile, K before V: K is there once only V's 8
-      // loads and the second block's 16 register loads (if any) are still outstanding
-      wait_vmcnt<h2.value ? 24 : 8>();
-      PASTA_CLK(3);
-    } else {
-      // registers -> this wave's LDS tile (rows rbase + 4 i); the registers then take the next block
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = rbase + 4 * i;
-        ktw[r * 16 + (piece ^ (r & 15))] = br.k[i];
-        vtw[r * 16 + (piece ^ v_swizzle(r))] = br.v[i];
-      }
-    }
+  auto tile_sync = [&]() {  // orders this wave's own LDS writes (or landed loads) before its reads
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if constexpr (!first.value) {
-      if (b + 4 < n_blocks) load_block(br, b + 4, std::true_type{});  // in flight while this block is computed
+  };
+  auto regs_to_tile = [&](const u32x4 (&src)[8], auto is_v) {  // rows rbase + 4 i of the block
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = rbase + 4 * i;
+      if constexpr (is_v.value) vtw[r * 16 + (piece ^ v_swizzle(r))] = src[i];
+      else ktw[r * 16 + (piece ^ (r & 15))] = src[i];
     }
-
-    // ---- S^T = K Q^T: lane (token l32 | row l32, half hh)
+  };
+  // ---- S^T = K Q^T of the block in the tile: lane (token l32 | row l32, half hh); then the tokens
+  // that do not exist (a block that reaches past the item's end) or may not be seen (dense-mask mode)
+  // are hidden.  Register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block.
+  auto s_block = [&](int b) -> f32x16 {
     f32x16 S;
 #pragma unroll
     for (int i = 0; i < 16; ++i) S[i] = 0.f;
@@ -418,8 +442,6 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
     }
-    // register i of lane (row, hh) is token 8 (i / 4) + 4 hh + i % 4 of the block.  Only a block
-    // that reaches past the item's end (or the dense-mask mode) has tokens to hide.
     const int tok0 = b * kBlock + 4 * hh;
     bool hide = b * kBlock + kBlock > n_tok;
     if constexpr (GATHER && DENSE) hide = hide || p.dense_mask != nullptr;
@@ -439,34 +461,23 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
         S[i] = seen ? S[i] : -INFINITY;
       }
     }
-    // online softmax in log2 units; the scale (> 0) is applied inside the exponent: 2^(s z - m)
+    return S;
+  };
+  auto row_max = [&](const f32x16& S) -> float {  // of this lane's 16 tokens
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * p.scale_log2e;
-    const float mn = fmaxf(m_run, mx);            // -inf while the row has seen nothing (dense-mask mode)
-    const float mref = mn == -INFINITY ? 0.f : mn;
-    const float corr = fast_exp2(m_run - mref);
-    m_run = mn;
-    float ps = 0.f;
+    return mx;
+  };
+  struct PBlock { bf16x8 ks[2]; };  // P^T as B operand: contraction step ks holds registers 8 ks .. 8 ks + 7
+  // 2^(scale S - mref), summed into ps, rounded to bf16 in registers
+  auto exp_pack = [&](f32x16& S, float mref, float& ps) -> PBlock {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       S[i] = fast_exp2(fmaf(S[i], p.scale_log2e, -mref));
       ps += S[i];
     }
-    l_run = l_run * corr + ps;
-    if (!__all(corr == 1.f)) {  // the running max moves rarely once a few blocks are in
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
-    }
-    if constexpr (first.value) {  // now V of the block loaded straight into the tile is needed
-      wait_vmcnt<h2.value ? 16 : 0>();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-    // P^T as B operand: contraction step ks holds registers 8 ks .. 8 ks + 7
-    bf16x8 Pb[2];
+    PBlock P;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       u32x4 pk;
@@ -474,10 +485,14 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       pk[1] = pack_bf16x2(S[8 * ks + 2], S[8 * ks + 3]);
       pk[2] = pack_bf16x2(S[8 * ks + 4], S[8 * ks + 5]);
       pk[3] = pack_bf16x2(S[8 * ks + 6], S[8 * ks + 7]);
-      Pb[ks] = *reinterpret_cast<const bf16x8*>(&pk);
+      P.ks[ks] = *reinterpret_cast<const bf16x8*>(&pk);
     }
-    // ---- O^T += V^T P^T.  Slot (ks, hh, e) is token 16 ks + 8 (e / 4) + 4 hh + e % 4: per
-    // transposing read, 4 consecutive token rows x 16 columns per 16-lane block.
+    return P;
+  };
+  // ---- O^T += V^T P^T for the V block in the tile.  Slot (ks, hh, e) is token
+  // 16 ks + 8 (e / 4) + 4 hh + e % 4: per transposing read, 4 consecutive token rows x 16 columns
+  // per 16-lane block.
+  auto pv_block = [&](const PBlock& P) {
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
@@ -491,29 +506,113 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
         a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
         a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
         a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
-        O[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a4), Pb[ks], O[mt], 0, 0, 0);
+        O[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a4), P.ks[ks], O[mt], 0, 0, 0);
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();  // the tile may be overwritten by the next block
   };
 
-  // this wave's blocks w, w + 4, ...
-  auto first_part = [&](auto h1, auto h2) {
-    issue_blocks_finish_q(h1, h2);
+  // ---- the wave's first block and, if it has one, its second: S of both, ONE softmax over the 64
+  // tokens (nothing to rescale), then P V of the first as soon as its V is there and P V of the
+  // second when the very last load has arrived -- all that is left to do at that point.  Written
+  // once per (has1, has2) case, as straight-line code of its own: how many loads stand behind the
+  // one that is waited for is a constant only inside one case.
+  auto first_blocks = [&](auto h1, auto h2) {
+    DmaRows d{};
+    if constexpr (h1.value) {
+      d = dma_rows(w);
+      dma_half(w, d, std::false_type{});                       // K1 -> tile
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (h2.value) {
+      load_half(br.k, w + 4, std::false_type{});               // K2 -> registers
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (h1.value) {
+      dma_half(w, d, std::true_type{});                        // V1 -> tile
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (h2.value) {
+      load_half(br.v, w + 4, std::true_type{});                // V2 -> registers
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    PASTA_CLK(1);
+    // Q has landed once at most the block loads issued behind it are outstanding
+    wait_vmcnt<h2.value ? 32 : (h1.value ? 16 : 0)>();
     report_rows();
     lds_barrier();  // Q visible to every wave; the only barrier before the end of the item, and it
                     // does not wait for the block loads still in flight
     PASTA_CLK(2);
     if constexpr (h1.value) {
-      compute_block(w, std::true_type{}, h2);
+      wait_vmcnt<h2.value ? 24 : 8>();                          // K1 is in the tile
+      tile_sync();
+      PASTA_CLK(3);
+      f32x16 S1 = s_block(w);
+      float mx = row_max(S1);
+      f32x16 S2;
+      if constexpr (h2.value) {
+        tile_sync();
+        regs_to_tile(br.k, std::false_type{});                  // K2 over K1 (LDS operations of a wave stay in order)
+        tile_sync();
+        S2 = s_block(w + 4);
+        mx = fmaxf(mx, row_max(S2));
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * p.scale_log2e;
+      m_run = mx;                                               // -inf: the row sees nothing here (dense-mask mode)
+      const float mref = mx == -INFINITY ? 0.f : mx;
+      float ps = 0.f;
+      const PBlock P1 = exp_pack(S1, mref, ps);
+      PBlock P2;
+      if constexpr (h2.value) P2 = exp_pack(S2, mref, ps);
+      l_run = ps;
+      PASTA_CLK(5);
+      wait_vmcnt<h2.value ? 8 : 0>();                           // V1 is in the tile
+      tile_sync();
+      pv_block(P1);
       PASTA_CLK(4);
+      if constexpr (h2.value) {
+        tile_sync();
+        regs_to_tile(br.v, std::true_type{});                   // V2 over V1
+        tile_sync();
+        if (LONG && w + 8 < n_blocks) load_block(br, w + 8, std::true_type{});
+        pv_block(P2);
+      }
+      tile_sync();
     }
   };
-  if (has2) first_part(std::true_type{}, std::true_type{});
-  else if (has1) first_part(std::true_type{}, std::false_type{});
-  else first_part(std::false_type{}, std::false_type{});
-  for (int b = w + 4; b < n_blocks; b += 4) compute_block(b, std::false_type{}, std::false_type{});
+  // a later block (long chunks only): registers -> tile, the block after it requested, online softmax
+  auto later_block = [&](int b) {
+    regs_to_tile(br.k, std::false_type{});
+    regs_to_tile(br.v, std::true_type{});
+    tile_sync();
+    if (b + 4 < n_blocks) load_block(br, b + 4, std::true_type{});  // in flight while this block is computed
+    f32x16 S = s_block(b);
+    // online softmax in log2 units; the scale (> 0) is applied inside the exponent: 2^(s z - m)
+    float mx = row_max(S);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * p.scale_log2e;
+    const float mn = fmaxf(m_run, mx);            // -inf while the row has seen nothing (dense-mask mode)
+    const float mref = mn == -INFINITY ? 0.f : mn;
+    const float corr = fast_exp2(m_run - mref);
+    m_run = mn;
+    float ps = 0.f;
+    const PBlock P = exp_pack(S, mref, ps);
+    l_run = l_run * corr + ps;
+    if (!__all(corr == 1.f)) {  // the running max moves rarely once a few blocks are in
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
+    }
+    pv_block(P);
+    tile_sync();  // the tile may be overwritten by the next block
+  };
+
+  // this wave's blocks w, w + 4, ...
+  if (has2) first_blocks(std::true_type{}, std::true_type{});
+  else if (has1) first_blocks(std::true_type{}, std::false_type{});
+  else first_blocks(std::false_type{}, std::false_type{});
+  if constexpr (LONG) {  // no other launch has items of more than eight blocks
+    for (int b = w + 8; b < n_blocks; b += 4) later_block(b);
+  }
   PASTA_CLK(6);
 
   // ---- combine the four waves.  Each wave parks its (unscaled) O^T in its OWN tile area as soon

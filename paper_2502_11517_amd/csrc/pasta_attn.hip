@@ -812,7 +812,11 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     }
 
     // ---- shared-prefix plan: only what the matrix-core kernel takes; the rest is private
-    const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G);
+    // (the matrix-core kernel addresses a layer's pool and the query rows with 32-bit byte offsets)
+    const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G) &&
+                      h->layer_elems * h->elem < ((int64_t)1 << 32) - 65536 &&
+                      (int64_t)n * c.n_q_heads * D * h->elem < ((int64_t)1 << 31);
+    if (dense && !mfma) return PASTA_E_INVAL;  // the mask is applied by the matrix-core kernel only
     int64_t pc_total = 0, pc_weighted = 0;  // the second counts a prefix once per row group of 32
     for (auto& q : reqs) {
       if (!mfma || q.pc < kTile || no_share) q.pc = 0;
