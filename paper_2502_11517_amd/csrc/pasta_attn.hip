@@ -11,7 +11,6 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <deque>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -40,6 +39,30 @@ struct StreamState {
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct ListView {  // one stream's visible list for this call
+  int32_t prefix_len;
+  const Range* ranges;   // maintained mode
+  int32_t n_ranges;
+  const int32_t *start, *count, *stride;  // explicit mode (ranges == nullptr)
+  Range at(int k) const { return ranges ? ranges[k] : Range{start[k], count[k], stride[k]}; }
+};
+
+
+
+// Host buffers of one decode_step's plan.  They live in the handle and keep their capacity from
+// call to call, so that a step in a serving loop touches no allocator; create reserves what a
+// plan small enough to ride in the kernel arguments can need.
+struct PlanBuf {
+  std::vector<ListView> lv;
+  std::vector<Range> trim;               // the lists that causal_skip shortens (never grown past its reserve: views point into it)
+  std::vector<uint8_t> seen, mask;
+  std::vector<int32_t> mask_base, req_idx_of, stream_req_idx, stream_local, req_streams, blob;
+  std::vector<DevReq> reqs;
+  std::vector<DevStream> streams;
+  std::vector<DevRange> ranges;
+  std::vector<DevItem> items;
+};
 
 }  // namespace
 
@@ -73,6 +96,7 @@ struct pasta_attn {
     int32_t pos[kAppendInline]{};
     std::vector<int32_t> req_pend0, req_src0;  // per request: first deferred slot, its row in k_new
   } pending;
+  PlanBuf pb;
   int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // forced chunk sizes (tokens; 0 = heuristic): set only by -DPASTA_TUNING builds
   // device-side readiness (deferred so that the host logic works without a GPU)
   bool device_ready = false;
@@ -435,6 +459,16 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
     h->tail.assign(cfg->max_requests, 0);
     h->tail_before.assign(cfg->max_requests, 0);
     h->streams.resize((size_t)cfg->max_requests * cfg->max_streams);
+    // plan buffers: what a plan that rides in the kernel arguments can need (larger plans grow them on demand)
+    const size_t ns = (size_t)cfg->max_requests * cfg->max_streams, nsc = std::min<size_t>(ns, 65535);
+    PlanBuf& pb = h->pb;
+    pb.lv.reserve(nsc); pb.mask_base.reserve(nsc); pb.stream_req_idx.reserve(nsc); pb.stream_local.reserve(nsc);
+    pb.req_streams.reserve(nsc); pb.streams.reserve(nsc);
+    pb.seen.reserve(ns);
+    pb.req_idx_of.reserve(cfg->max_requests); pb.reqs.reserve(cfg->max_requests);
+    pb.ranges.reserve(std::min<size_t>((size_t)cfg->max_ranges + nsc, kInlineMetaWords));
+    pb.items.reserve(kInlineMetaWords / (sizeof(DevItem) / 4));
+    pb.blob.reserve(kInlineMetaWords + 16);
   } catch (...) { return fail(PASTA_E_NOMEM); }
 #if defined(PASTA_TUNING) && PASTA_TUNING >= 2
   std::fprintf(stderr, "PASTA_CLOCKS byte offset in workspace: %zu\n", h->off_ml + (size_t)(h->part_rows_cap - 8192) * 8);
@@ -667,17 +701,8 @@ extern "C" int32_t pasta_attn_stream_list(pasta_attn* h, int32_t request_id, int
 // =============================================================================== decode
 namespace {
 
-struct ListView {  // one stream's visible list for this call
-  int32_t prefix_len;
-  const Range* ranges;   // maintained mode
-  int32_t n_ranges;
-  const int32_t *start, *count, *stride;  // explicit mode (ranges == nullptr)
-  Range at(int k) const { return ranges ? ranges[k] : Range{start[k], count[k], stride[k]}; }
-};
-
-}  // namespace
-
-extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args* a) {
+// `no_alloc`: the plan's host buffers may not grow (the call then fails with E_CAPACITY instead).
+int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_alloc) {
   if (!h || h->magic != kMagic) return PASTA_E_STATE;
   if (!a || a->struct_size != sizeof(pasta_decode_args)) return PASTA_E_INVAL;
   const pasta_attn_config& c = h->cfg;
@@ -702,16 +727,34 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
   const bool dense = a->flags & PASTA_DECODE_DENSE_MASK;
   if (dense && (c.dtype != PASTA_BF16 || c.head_dim != 128 || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
-  if (!plan_only) {  // before planning: the plan is sized to the device's compute-unit count
+  float2* part_ml = nullptr;   // where this call's partials go
+  float* part_acc = nullptr;
+  int64_t part_rows_cap = h->part_rows_cap;
+  if (no_alloc) {
+    if (plan_only || dense || !h->device_ready) return PASTA_E_INVAL;
+  } else if (!plan_only) {  // before planning: the plan is sized to the device's compute-unit count
     const int rc0 = ensure_device(h);
     if (rc0 != PASTA_OK) return rc0;
+    part_ml = (float2*)((char*)c.workspace + h->off_ml);
+    part_acc = (float*)((char*)c.workspace + h->off_acc);
   }
+  // a buffer of the plan may grow only where allocation is allowed
+  auto room = [&](const auto& v, size_t want) { return !no_alloc || want <= v.capacity(); };
 
   try {
     // ---- lists + validation
-    std::vector<ListView> lv(n);
-    std::deque<std::vector<Range>> trimmed;  // storage of the views that causal_skip shortens (stable addresses)
-    std::vector<uint8_t> seen((size_t)c.max_requests * c.max_streams, 0);
+    PlanBuf& pb = h->pb;
+    if (!room(pb.lv, n) || !room(pb.mask_base, n) || !room(pb.stream_req_idx, n) || !room(pb.streams, n)) return PASTA_E_CAPACITY;
+    std::vector<ListView>& lv = pb.lv;
+    lv.resize(n);
+    std::vector<Range>& trim = pb.trim;    // storage of the views that causal_skip shortens (stable: never past its reserve)
+    trim.clear();
+    if (a->causal_skip && trim.capacity() < (size_t)c.max_ranges) {
+      if (no_alloc) return PASTA_E_CAPACITY;
+      trim.reserve((size_t)c.max_ranges);
+    }
+    std::vector<uint8_t>& seen = pb.seen;
+    seen.assign((size_t)c.max_requests * c.max_streams, 0);  // (reserved at create)
     int64_t total_ranges = 0;
     for (int i = 0; i < n; ++i) {
       const int r = a->request_id[i], s = a->stream_id[i];
@@ -743,17 +786,18 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         const int skip = a->causal_skip ? a->causal_skip[i] : 0;
         if (skip < 0) return PASTA_E_INVAL;
         if (skip > 0) {  // a view without the stream's `skip` newest rows: they are the largest slots of its list
-          trimmed.emplace_back(ss.ranges);
-          std::vector<Range>& tr = trimmed.back();
+          if (trim.size() + ss.ranges.size() > (size_t)c.max_ranges) return PASTA_E_CAPACITY;
+          const size_t t0 = trim.size();
+          trim.insert(trim.end(), ss.ranges.begin(), ss.ranges.end());
           int left = skip;
-          while (left > 0 && !tr.empty()) {
-            const int take = std::min(left, tr.back().count);
-            tr.back().count -= take;
+          while (left > 0 && trim.size() > t0) {
+            const int take = std::min(left, trim.back().count);
+            trim.back().count -= take;
             left -= take;
-            if (tr.back().count == 0) tr.pop_back();
+            if (trim.back().count == 0) trim.pop_back();
           }
           if (left > ss.prefix_len) return PASTA_E_INVAL;
-          v = ListView{ss.prefix_len - left, tr.data(), (int32_t)tr.size(), nullptr, nullptr, nullptr};
+          v = ListView{ss.prefix_len - left, trim.data() + t0, (int32_t)(trim.size() - t0), nullptr, nullptr, nullptr};
         }
         if (v.prefix_len == 0 && v.n_ranges == 0) return PASTA_E_INVAL;
       }
@@ -763,8 +807,9 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
 
     // ---- dense-mask comparison mode: the lists become one 0/1 byte per (stream, slot), and every
     // stream's list becomes "all slots of its request"
-    std::vector<uint8_t> mask;
-    std::vector<int32_t> mask_base(n, 0);
+    std::vector<uint8_t>& mask = pb.mask;
+    std::vector<int32_t>& mask_base = pb.mask_base;
+    mask_base.assign(n, 0);
     if (dense) {
       size_t total = 0;
       for (int i = 0; i < n; ++i) {
@@ -786,9 +831,13 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     }
 
     // ---- group by request (order of first appearance)
-    std::vector<int32_t> req_idx_of(c.max_requests, -1);
-    std::vector<DevReq> reqs;
-    std::vector<int32_t> stream_req_idx(n), stream_local(n);
+    std::vector<int32_t>& req_idx_of = pb.req_idx_of;
+    req_idx_of.assign(c.max_requests, -1);  // (reserved at create, as is reqs)
+    std::vector<DevReq>& reqs = pb.reqs;
+    reqs.clear();
+    std::vector<int32_t>&stream_req_idx = pb.stream_req_idx, &stream_local = pb.stream_local;
+    stream_req_idx.resize(n);
+    stream_local.resize(n);
     for (int i = 0; i < n; ++i) {
       const int r = a->request_id[i];
       if (req_idx_of[r] < 0) {
@@ -804,7 +853,8 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       stream_local[i] = q.n_streams++;
       q.pc = std::min(q.pc, lv[i].prefix_len);
     }
-    std::vector<int32_t> req_streams(n);
+    std::vector<int32_t>& req_streams = pb.req_streams;
+    req_streams.resize(n);
     {
       int32_t pos = 0;
       for (auto& q : reqs) { q.stream0 = pos; pos += q.n_streams; }
@@ -836,9 +886,13 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       if (h->tune_priv_chunk >= 32) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / 32 * 32, kGatherMax);  // whole 32-token blocks
     }
     // private items
-    std::vector<DevStream> streams(n);
-    std::vector<DevRange> ranges;
-    std::vector<DevItem> items;
+    std::vector<DevStream>& streams = pb.streams;
+    std::vector<DevRange>& ranges = pb.ranges;
+    std::vector<DevItem>& items = pb.items;
+    streams.assign(n, DevStream{});
+    ranges.clear();
+    items.clear();
+    if (!room(ranges, (size_t)total_ranges + n)) return PASTA_E_CAPACITY;
     ranges.reserve((size_t)total_ranges + n);
     int64_t gather_total = 0;
     for (int i = 0; i < n; ++i) {
@@ -877,6 +931,7 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
         it.gather_pos = (int32_t)(gather_total + q.pc + t);
         it.slot0 = ranges[rcur].start + (t - ranges[rcur].cum) * ranges[rcur].stride;
         it.stride = it.n_ranges == 1 ? ranges[rcur].stride : 0;  // 0: rows come from the expanded list
+        if (!room(items, items.size() + 1)) return PASTA_E_CAPACITY;
         items.push_back(it);
       }
       ds.item_end = (int32_t)items.size();
@@ -902,12 +957,12 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
           n_prefix_wgs += (int64_t)q.n_chunks * Hkv * ((q.n_streams * G + 31) / 32);
           prefix_rows += (int64_t)q.n_chunks * Hkv * q.n_streams * G;
         }
-        if (prefix_rows + priv_rows <= h->part_rows_cap) break;
+        if (prefix_rows + priv_rows <= part_rows_cap) break;
         if (chunk_tokens > (int64_t)1 << 30) return PASTA_E_CAPACITY;
       }
     } else {
       for (auto& q : reqs) { q.n_chunks = 0; q.chunk_tokens = kTile; q.wg_begin = 0; q.part_base = 0; }
-      if (priv_rows > h->part_rows_cap) return PASTA_E_CAPACITY;
+      if (priv_rows > part_rows_cap) return PASTA_E_CAPACITY;
     }
 
     for (int i = 0; i < n; ++i) {  // the merge's view of each stream's request (known now that the chunks are)
@@ -917,7 +972,15 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
       streams[i].m_R = q.n_streams * G;
     }
     // ---- metadata blob
-    std::vector<int32_t> blob;
+    std::vector<int32_t>& blob = pb.blob;
+    blob.clear();
+    {
+      const size_t words = (streams.size() * sizeof(DevStream) + reqs.size() * sizeof(DevReq) + req_streams.size() * 4 +
+                            ranges.size() * sizeof(DevRange) + items.size() * sizeof(DevItem)) / 4 + 8;
+      if (no_alloc && words > (size_t)kInlineMetaWords) return PASTA_E_CAPACITY;  // larger plans need the pinned staging
+      if (!room(blob, words)) return PASTA_E_CAPACITY;
+      blob.reserve(words);
+    }
     DecodeParams p{};
     auto put = [&](const void* src, size_t bytes) -> int {
       const int off = (int)blob.size();
@@ -1010,8 +1073,8 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     p.lse = a->out_lse;
     p.dbg_rows = a->dbg_gather_rows;
     p.page_table = (const int32_t*)((const char*)c.workspace + h->off_page_table);
-    p.part_acc = (float*)((char*)c.workspace + h->off_acc);
-    p.part_ml = (float2*)((char*)c.workspace + h->off_ml);
+    p.part_acc = part_acc;
+    p.part_ml = part_ml;
     p.lay = h->lay;
     p.n_streams = n;
     p.n_reqs = (int)reqs.size();
@@ -1097,5 +1160,9 @@ extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args
     return PASTA_E_NOMEM;
   }
 }
+
+}  // namespace
+
+extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args* a) { return decode_impl(h, a, false); }
 
 #include "replay.hpp"
