@@ -267,6 +267,24 @@ typedef struct {
  * is asynchronous on cfg.hip_stream; the call returns without synchronising. */
 int32_t pasta_attn_decode_step(pasta_attn *h, const pasta_decode_args *a);
 
+/* The same decode step for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Identical arguments and results; what differs:
+ *   - the split partials (one (m, l, acc[head_dim]) fp32 row per split chunk and query row) go to
+ *     a static device array inside the library, PASTA_NOALLOC_SCRATCH_BYTES (16 MiB) per GPU the
+ *     library runs on, held until the process ends, instead of the workspace.  A step whose
+ *     private items alone need more rows than fit returns E_CAPACITY; shared-prefix chunks are
+ *     made longer until the rows fit.  The array keeps the last call's contents, nothing in it
+ *     has to start at zero, and ALL handles on one GPU share it: calls that overlap on one GPU
+ *     (different streams, different handles) race;
+ *   - the call makes no device or pinned-host allocation and grows no host buffer: the handle must
+ *     have been set up by an earlier append_kv on the device (else E_STATE), and the step's plan
+ *     must be small enough to ride in the kernel arguments (about 3 KB of stream / range / item
+ *     records: else E_CAPACITY);
+ *   - PASTA_DECODE_PLAN_ONLY and PASTA_DECODE_DENSE_MASK (host staging) are E_INVAL.
+ * Other errors as decode_step.                                                 */
+#define PASTA_NOALLOC_SCRATCH_BYTES (16u << 20)
+int32_t pasta_attn_decode_step_noalloc(pasta_attn *h, const pasta_decode_args *a);
+
 /* Synchronisation (Section 3, Efficiency: a thread that has decoded its sync
  * token waits for its forks; when they are complete the sync token enters the
  * pool and the thread resumes "conditioning on both forks' generations";

@@ -122,6 +122,8 @@ def load_library():
         L.pasta_attn_append_kv.argtypes = [C.c_void_p, C.POINTER(AppendArgs)]
         L.pasta_attn_decode_step.restype = C.c_int32
         L.pasta_attn_decode_step.argtypes = [C.c_void_p, C.POINTER(DecodeArgs)]
+        L.pasta_attn_decode_step_noalloc.restype = C.c_int32
+        L.pasta_attn_decode_step_noalloc.argtypes = [C.c_void_p, C.POINTER(DecodeArgs)]
         L.pasta_attn_sync.restype = C.c_int32
         L.pasta_attn_sync.argtypes = [C.c_void_p, C.POINTER(SyncArgs)]
         L.pasta_attn_stream_list.restype = C.c_int32
@@ -199,9 +201,14 @@ class PastaAttn:
             raise PastaError(rc, "pasta_attn_append_kv")
         return slots
 
+    def decode_step_noalloc(self, *args, **kw):
+        """The same step through the entry point that allocates nothing (partials in the library's
+        static device array); same arguments as decode_step."""
+        return self.decode_step(*args, _entry="pasta_attn_decode_step_noalloc", **kw)
+
     def decode_step(self, layer, request_id, stream_id, q, out, *, lists=None, out_lse=None, flags=0,
                     position=None, dbg_gather_offsets=None, dbg_gather_rows=None, dbg_plan=None,
-                    prof_events=None, causal_skip=None):
+                    prof_events=None, causal_skip=None, _entry="pasta_attn_decode_step"):
         """lists = (prefix_len, range_offsets, start, count, stride) for explicit visibility;
         None uses the lists append_kv has maintained."""
         rid, sid, pos, skip = _i32(request_id), _i32(stream_id), _i32(position), _i32(causal_skip)
@@ -216,9 +223,9 @@ class PastaAttn:
         a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, n, _hp(rid), _hp(sid), _hp(pos), _hp(skip), _hp(pl), _hp(offs),
                        _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), _hp(dbg_gather_offsets),
                        _dp(dbg_gather_rows), _hp(dbg_plan), ev0, ev1)
-        rc = self._lib.pasta_attn_decode_step(self._h, C.byref(a))
+        rc = getattr(self._lib, _entry)(self._h, C.byref(a))
         if rc != OK:
-            raise PastaError(rc, "pasta_attn_decode_step")
+            raise PastaError(rc, _entry)
 
     # ---- prepared calls: marshal once, call many times (tight serving loops) ----
     def prepare_append(self, layer, request_id, stream_id, k_new, v_new, parent_stream=None, flags=0,

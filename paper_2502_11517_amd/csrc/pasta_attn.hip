@@ -701,7 +701,16 @@ extern "C" int32_t pasta_attn_stream_list(pasta_attn* h, int32_t request_id, int
 // =============================================================================== decode
 namespace {
 
-// `no_alloc`: the plan's host buffers may not grow (the call then fails with E_CAPACITY instead).
+// The scratch of the entry point that allocates nothing: partial (m, l) and accumulator rows of one
+// decode step.  One array per GPU that the library runs on, held until the process ends; host code
+// reaches it only through the address that hipGetSymbolAddress returns for the current device.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// `no_alloc`: the partials go to the static scratch array instead of the workspace, and the call
+// must get by without any allocation, device or host (see pasta_attn_decode_step_noalloc).
 int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_alloc) {
   if (!h || h->magic != kMagic) return PASTA_E_STATE;
   if (!a || a->struct_size != sizeof(pasta_decode_args)) return PASTA_E_INVAL;
@@ -731,7 +740,21 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
   float* part_acc = nullptr;
   int64_t part_rows_cap = h->part_rows_cap;
   if (no_alloc) {
-    if (plan_only || dense || !h->device_ready) return PASTA_E_INVAL;
+    // nothing here may allocate: the handle must have been through its set-up (any append_kv does
+    // that), the plan must fit the kernel arguments, and the comparison mode with its host staging is out
+    if (plan_only || dense) return PASTA_E_INVAL;
+    if (!h->device_ready) return PASTA_E_STATE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return PASTA_E_DEVICE; }
+    if (!g_scratch_ptr[dev]) {  // once per device, with that device current
+      void* ptr = nullptr;
+      if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return PASTA_E_DEVICE; }
+      g_scratch_ptr[dev] = ptr;
+    }
+    part_rows_cap = (int64_t)(kScratchBytes / (sizeof(float2) + (size_t)D * sizeof(float)));
+    part_ml = (float2*)g_scratch_ptr[dev];
+    part_acc = (float*)((char*)g_scratch_ptr[dev] + align_up((size_t)part_rows_cap * sizeof(float2), 256));
+    part_rows_cap -= 64;  // (the alignment gap between the two arrays)
   } else if (!plan_only) {  // before planning: the plan is sized to the device's compute-unit count
     const int rc0 = ensure_device(h);
     if (rc0 != PASTA_OK) return rc0;
@@ -1164,5 +1187,9 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
 }  // namespace
 
 extern "C" int32_t pasta_attn_decode_step(pasta_attn* h, const pasta_decode_args* a) { return decode_impl(h, a, false); }
+
+extern "C" int32_t pasta_attn_decode_step_noalloc(pasta_attn* h, const pasta_decode_args* a) {
+  return decode_impl(h, a, true);
+}
 
 #include "replay.hpp"

@@ -53,7 +53,8 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "pasta_attn.h")).read()
     declared = set(re.findall(r"\bint32_t\s+(pasta_attn_\w+)\s*\(", hdr))
     assert declared == {"pasta_attn_create", "pasta_attn_append_kv", "pasta_attn_decode_step", "pasta_attn_destroy",
-                        "pasta_attn_sync", "pasta_attn_stream_list", "pasta_attn_replay"}
+                        "pasta_attn_sync", "pasta_attn_stream_list", "pasta_attn_replay",
+                        "pasta_attn_decode_step_noalloc"}
     syms = subprocess.run(["nm", "-D", "--defined-only", B.library_path()], capture_output=True, text=True).stdout
     exported = {l.split()[-1] for l in syms.splitlines() if " T " in l}
     assert declared <= exported
