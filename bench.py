@@ -29,6 +29,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
+MIN_SAMPLES = 8         # attention launches timed by event pairs, at least
+SPINUP_S = 0.25         # seconds of untimed decode steps ahead of the warm-up (clock ramp of an idle GPU)
 
 
 def main():
@@ -41,7 +43,11 @@ def main():
     ap.add_argument("--event-every", type=int, default=33,
                     help="time the attention kernel of every n-th step with a HIP event pair attached to its dispatch "
                          "(a timed dispatch costs its step about 5 us: at every 8th step the run reads 0.6 us per step "
-                         "slower than without events; 33 is co-prime with the 32 pools, so the samples cover all of them)")
+                         "slower than without events; 33 is co-prime with the 32 pools, so the samples cover all of them); "
+                         "short runs sample more often, so that there are always at least 8 samples")
+    ap.add_argument("--probe-launches", type=int, default=64,
+                    help="after the timed region: this many launches of the read-only form of the attention launch "
+                         "(same grid, same requests, no arithmetic), cycling the pools, each timed by its dispatch's events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma", action="store_true", help="route the prefix through the private-segment kernel")
     ap.add_argument("--eager-append", action="store_true",
@@ -82,7 +88,11 @@ def main():
     if args.workload != "config3":
         return decode_only(args, getattr(W, args.workload)(), dev)
     L = args.layers
-    tokens = -(-args.steps // L)  # token steps needed
+    every = max(1, args.event_every)
+    # steps beyond the timed region (same loop, untimed): as many as it takes to have MIN_SAMPLES timed launches
+    n_tail = max(0, (MIN_SAMPLES + 1) * every - args.steps)
+    n_all = args.steps + n_tail
+    tokens = -(-n_all // L)  # token steps needed
     w = W.config3(steps=max(tokens, 2), prefix=args.prefix, n_streams=args.streams)
     layout = B.HEAD_MAJOR if args.layout == "head" else B.TOKEN_MAJOR
     theta = 10000.0
@@ -112,8 +122,8 @@ def main():
     flags |= (B.DECODE_NO_SHARE if args.no_share else 0) | (B.DECODE_DENSE_MASK if args.dense_mask else 0)
     q_pos = [w.q_positions(t) if args.rope else None for t in range(tokens)]
 
-    # HIP events around the attention-partials kernels of sampled steps
-    n_ev = args.steps // args.event_every + 1
+    # HIP events around the attention-partials kernels of sampled steps (never step 0)
+    n_ev = n_all // every + 1
     evs = []
     for _ in range(2 * n_ev):
         e = C.c_void_p()
@@ -123,9 +133,9 @@ def main():
     ev_step = w.ev_stream[n0:n0 + w.n]
     req_step = w.ev_request[n0:n0 + w.n]
     calls = []
-    for i in range(args.steps):
+    for i in range(n_all):
         t, l = divmod(i, L)
-        pe = (evs[2 * (i // args.event_every)], evs[2 * (i // args.event_every) + 1]) if i % args.event_every == 0 else None
+        pe = (evs[2 * (i // every)], evs[2 * (i // every) + 1]) if sampled(i, every) else None
         app_flags = (0 if args.eager_append else B.APPEND_DEFER) | (B.APPEND_ROPE if args.rope else 0)
         calls.append((s.h.prepare_append(l, req_step, ev_step, k_steps[t][l], v_steps[t][l], flags=app_flags,
                                          position=ev_pos[n0 + t * w.n:n0 + (t + 1) * w.n] if args.rope else None),
@@ -140,32 +150,70 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- warm-up: decode only (no state change), cycling the layers
-    warm = [s.h.prepare_decode(l % L, w.dec_request, w.dec_stream, q_steps[0], out[l % L], flags=flags,
-                               position=q_pos[0])
-            for l in range(max(1, min(args.warmup, L)))]
+    # ---- warm-up: decode only (no state change).  Every pool is touched once whatever --warmup says (first
+    # touches of a pool cost page-table walks that are no part of a steady-state step), then `warmup` more steps.
+    warm = [s.h.prepare_decode(l, w.dec_request, w.dec_stream, q_steps[0], out[l], flags=flags, position=q_pos[0])
+            for l in range(L)]
+    # Then the device is kept busy for SPINUP_S with the same decode steps: an idle GPU starts a run at low
+    # clocks and takes milliseconds to ramp, far longer than a short timed region lasts.
+    t_spin = time.perf_counter()
+    n_spin = 0
+    while n_spin < L or time.perf_counter() - t_spin < SPINUP_S:
+        for i in range(64):
+            assert warm[(n_spin + i) % L]() == 0
+        n_spin += 64
+        torch.cuda.synchronize()
     for i in range(args.warmup):
-        assert warm[i % len(warm)]() == 0
+        assert warm[i % L]() == 0
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` append+decode passes
     t0 = time.perf_counter()
-    for app, dec in calls:
+    for app, dec in calls[:args.steps]:
         ra = app()
         rd = dec()
         if ra or rd:
             raise SystemExit(f"library error in timed loop: append {ra} decode {rd}")
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # ---- the same loop goes on, untimed, until enough launches have been timed by their events
+    for app, dec in calls[args.steps:]:
+        if app() or dec():
+            raise SystemExit("library error after the timed loop")
+    torch.cuda.synchronize()
 
     # ---- kernel time from the events
     ms = C.c_float()
-    durs = []
-    for j in range(0, args.steps, args.event_every):
-        a, b = evs[2 * (j // args.event_every)], evs[2 * (j // args.event_every) + 1]
-        assert hip.hipEventElapsedTime(C.byref(ms), a, b) == 0
-        durs.append(ms.value * 1e-3)
+    durs, n_in_region = [], 0
+    for j in range(n_all):
+        if sampled(j, every):
+            a, b = evs[2 * (j // every)], evs[2 * (j // every) + 1]
+            assert hip.hipEventElapsedTime(C.byref(ms), a, b) == 0
+            durs.append(ms.value * 1e-3)
+            n_in_region += j < args.steps
     kern_s = float(np.mean(durs))
+
+    # ---- what a plain read of the same bytes costs at this launch's shape: the read-only form of the
+    # attention launch (same grid, same requests by the same waves, no arithmetic), on the final state
+    probe_s = None
+    if args.probe_launches > 0 and not (args.no_mfma or args.dense_mask):
+        pflags = (flags | B.DECODE_READ_PROBE) & ~B.DECODE_ROPE_Q
+        scratch_out = torch.empty(w.n, w.Hq, w.D, dtype=torch.bfloat16, device=dev)
+        pev = []
+        for _ in range(2 * args.probe_launches):
+            e = C.c_void_p()
+            assert hip.hipEventCreate(C.byref(e)) == 0
+            pev.append(e)
+        pcalls = [s.h.prepare_decode(i % L, w.dec_request, w.dec_stream, q_steps[-1], scratch_out, flags=pflags,
+                                     prof_events=(pev[2 * i], pev[2 * i + 1])) for i in range(args.probe_launches)]
+        for c_ in pcalls:
+            assert c_() == 0
+        torch.cuda.synchronize()
+        pd = []
+        for i in range(args.probe_launches):
+            assert hip.hipEventElapsedTime(C.byref(ms), pev[2 * i], pev[2 * i + 1]) == 0
+            pd.append(ms.value * 1e-3)
+        probe_s = float(np.median(pd[len(pd) // 4:]))  # the first quarter warms the variant's code
 
     # algorithmic bytes of the attention-partials kernels per launch: every visible K and V row
     # once (prefix rows once for all streams) + Q read; averaged over the timed steps
@@ -176,7 +224,8 @@ def main():
         pc = int(pl.min())
         priv = int(sum(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum()) for i in range(w.n)))
         alg.append((pc + priv) * row_bytes + w.n * w.Hq * w.D * 2)
-    alg_bytes = float(np.mean([alg[i // L] for i in range(args.steps)]))
+    alg_bytes = float(np.mean([alg[j // L] for j in range(n_all) if sampled(j, every)]))  # of the timed launches
+    alg_step = float(np.mean([alg[i // L] for i in range(args.steps)]))                   # of the timed region's steps
     achieved = alg_bytes / kern_s / 1e9
 
     # ---- CPU baseline: the fp64 oracle as it stands, on the host cores, for a bounded sample
@@ -217,13 +266,15 @@ def main():
         got = W.bf16_bits_to_f32(to_host_bits(chk, w.dtype)).astype(np.float64)
         result_extra["parity_vs_oracle"] = {"max_abs": float(np.max(np.abs(got - ref))),
                                             "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
-    # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (if present)
-    traffic = None
+    # HBM traffic of the dominant kernel: NOT measured in this run -- read from the committed rocprofv3 --pmc
+    # summary (FETCH_SIZE + WRITE_SIZE per launch, scaled by a copy of known size), and labelled as such
+    traffic, traffic_src = None, None
     prof = os.path.join(ROOT, "profiles", "k_attn_config3.txt")
     if os.path.exists(prof) and not args.no_mfma:
         for line in open(prof):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
                 traffic = float(line.split("=")[1])
+                traffic_src = "profiles/k_attn_config3.txt (rocprofv3 --pmc, a separate run of this command)"
     res = {
         "metric": "multi-stream decode-attention stream-tokens/s (append + decode step, per layer)",
         "value": w.n * args.steps / elapsed,
@@ -240,21 +291,43 @@ def main():
         "config": {"workload": f"config 3: bf16 32q/8kv heads D=128, prefix {args.prefix}, {args.streams} streams L~U[64,512] "
                                "right-aligned round-robin, append+decode per step",
                    "n_layers_cycled": L, "kv_layout": args.layout, "visibility": "maintained lists",
+                   "before_the_timed_region": f"every pool touched once, {SPINUP_S} s of decode steps to bring the clocks up, "
+                                              f"then the {args.warmup} warm-up steps",
+                   "after_the_timed_region": f"{n_tail} more steps of the same loop, untimed, so that {len(durs)} launches "
+                                             f"carry event pairs (every {every}th step)",
                    "append": "eager (own launch)" if (args.eager_append or args.rope) else "deferred (rides with the decode launch)",
                    "visibility_mode": "dense mask over the whole pool" if args.dense_mask else
                                       ("lists, prefix not shared" if args.no_share else "lists, shared prefix"),
                    "rope": "K rotated at append, Q in the attention kernel, theta 1e4" if args.rope else "off (Q, K arrive rotated)",
                    "model_tokens_per_s": w.n * args.steps / elapsed / L},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": "k_attn (shared-prefix + private-segment partials, one launch)",
-                     "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
-        "whole_step": {"algorithmic_GBps": alg_bytes / (elapsed / args.steps) / 1e9},
+                     "kernel_us": kern_s * 1e6, "kernel_us_median": float(np.median(durs)) * 1e6,
+                     "kernel_us_min": float(np.min(durs)) * 1e6, "kernel_samples": len(durs),
+                     "kernel_samples_in_timed_region": n_in_region,
+                     "algorithmic_bytes": alg_bytes,
+                     "measured_read_us": None if probe_s is None else probe_s * 1e6,
+                     "measured_read_GBps": None if probe_s is None else alg_bytes / probe_s / 1e9,
+                     "frac_of_measured_read": None if probe_s is None else probe_s / kern_s},
+        "whole_step": {"algorithmic_GBps": alg_step / (elapsed / args.steps) / 1e9},
         "cpu_baseline": cpu,
     }
     res.update(result_extra)
     print(json.dumps(res))
     s.close()
+
+
+def event_period(steps, asked):
+    """Sampling period of the timed launches: the asked one, but short runs sample more often (at least 8
+    samples when the run has that many steps after step 0)."""
+    return max(1, min(asked, (steps - 1) // 8)) if steps > 1 else 1
+
+
+def sampled(i, every):
+    """Step i carries an event pair: every `every`-th step, never step 0 (the first launch after the warm-up's
+    synchronisation finds an empty queue)."""
+    return i > 0 and i % every == 0
 
 
 def decode_only(args, w, dev):
@@ -282,7 +355,8 @@ def decode_only(args, w, dev):
     q = to_device(w.q(0), w.dtype, dev)
     out = torch.empty(L, w.n, w.Hq, w.D, dtype=q.dtype, device=dev)
     flags = B.DECODE_NO_MFMA if args.no_mfma else 0
-    n_ev = args.steps // args.event_every + 1
+    every = event_period(args.steps, args.event_every)
+    n_ev = args.steps // every + 1
     evs = []
     for _ in range(2 * n_ev):
         e = C.c_void_p()
@@ -290,11 +364,18 @@ def decode_only(args, w, dev):
         evs.append(e)
     calls = []
     for i in range(args.steps):
-        j = i // args.event_every
-        pe = (evs[2 * j], evs[2 * j + 1]) if i % args.event_every == 0 else None
+        j = i // every
+        pe = (evs[2 * j], evs[2 * j + 1]) if sampled(i, every) else None
         calls.append(s.h.prepare_decode(i % L, w.dec_request, w.dec_stream, q, out[i % L], flags=flags, prof_events=pe))
+    warm = [s.h.prepare_decode(l, w.dec_request, w.dec_stream, q, out[l], flags=flags) for l in range(L)]
+    t_spin, n_spin = time.perf_counter(), 0
+    while n_spin < L or time.perf_counter() - t_spin < SPINUP_S:  # every pool once, and the clocks up
+        for i in range(16):
+            assert warm[(n_spin + i) % L]() == 0
+        n_spin += 16
+        torch.cuda.synchronize()
     for i in range(args.warmup):
-        assert calls[i % len(calls)]() == 0
+        assert warm[i % L]() == 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for c in calls:
@@ -304,10 +385,28 @@ def decode_only(args, w, dev):
     elapsed = time.perf_counter() - t0
     ms = C.c_float()
     durs = []
-    for j in range(0, args.steps, args.event_every):
-        assert hip.hipEventElapsedTime(C.byref(ms), evs[2 * (j // args.event_every)], evs[2 * (j // args.event_every) + 1]) == 0
-        durs.append(ms.value * 1e-3)
+    for j in range(args.steps):
+        if sampled(j, every):
+            assert hip.hipEventElapsedTime(C.byref(ms), evs[2 * (j // every)], evs[2 * (j // every) + 1]) == 0
+            durs.append(ms.value * 1e-3)
     kern_s = float(np.mean(durs))
+    probe_s = None
+    if args.probe_launches > 0 and not args.no_mfma and w.dtype == "bf16":
+        pev = []
+        for _ in range(2 * args.probe_launches):
+            e = C.c_void_p()
+            assert hip.hipEventCreate(C.byref(e)) == 0
+            pev.append(e)
+        pcalls = [s.h.prepare_decode(i % L, w.dec_request, w.dec_stream, q, out[i % L], flags=flags | B.DECODE_READ_PROBE,
+                                     prof_events=(pev[2 * i], pev[2 * i + 1])) for i in range(args.probe_launches)]
+        for c in pcalls:
+            assert c() == 0
+        torch.cuda.synchronize()
+        pd = []
+        for i in range(args.probe_launches):
+            assert hip.hipEventElapsedTime(C.byref(ms), pev[2 * i], pev[2 * i + 1]) == 0
+            pd.append(ms.value * 1e-3)
+        probe_s = float(np.median(pd[len(pd) // 4:]))
     # algorithmic bytes: per request the common prefix once, everything else once per stream
     pl, offs, st, ct, sd = w.lists(0)
     rows = 0
@@ -317,6 +416,15 @@ def decode_only(args, w, dev):
         rows += pc + sum(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum()) for i in idx)
     alg_bytes = rows * row_bytes + w.n * w.Hq * w.D * (2 if w.dtype == "bf16" else 4)
     achieved = alg_bytes / kern_s / 1e9
+    # the contraction side of the same launch: every visible row meets the query rows that see it, 2 D
+    # multiply-adds for the logit and 2 D for the weighted sum per (row, query row) pair
+    G = w.Hq // w.Hkv
+    pairs = 0
+    for r in np.unique(w.dec_request):
+        idx = np.nonzero(w.dec_request == r)[0]
+        pc = int(pl[idx].min())
+        pairs += pc * len(idx) + sum(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum()) for i in idx)
+    flops = 4.0 * w.D * pairs * w.Hq
     print(json.dumps({
         "metric": "multi-stream decode-attention stream-tokens/s (decode step only, per layer)",
         "value": w.n * args.steps / elapsed, "unit": "stream-tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -326,7 +434,16 @@ def decode_only(args, w, dev):
                    "n_layers_cycled": L, "kv_layout": args.layout},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "attention-partials launch", "kernel_us": kern_s * 1e6, "algorithmic_bytes": alg_bytes},
+                     "kernel": "attention-partials launch", "kernel_us": kern_s * 1e6,
+                     "kernel_us_median": float(np.median(durs)) * 1e6, "kernel_us_min": float(np.min(durs)) * 1e6,
+                     "kernel_samples": len(durs), "algorithmic_bytes": alg_bytes,
+                     "measured_read_us": None if probe_s is None else probe_s * 1e6,
+                     "measured_read_GBps": None if probe_s is None else alg_bytes / probe_s / 1e9,
+                     "frac_of_measured_read": None if probe_s is None else probe_s / kern_s},
+        "roofline_mfma": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                          "frac": flops / kern_s / 1e12 / 2500.0, "algorithmic_flops": flops,
+                          "note": "same launch priced as a bf16 contraction (stacked query rows x visible rows); "
+                                  "the larger of the two fractions says which roofline is nearer"},
         "cpu_baseline": None}))
     s.close()
 

@@ -215,10 +215,16 @@ enum {
    * implementation runs attention over its whole static pool under a mask): */
   PASTA_DECODE_NO_SHARE = 8u,  /* no shared-prefix items: every stream reads its whole
                                   visible set by itself (the prefix once per stream) */
-  PASTA_DECODE_DENSE_MASK = 16u /* every stream walks ALL slots [0, tail) of its request and
+  PASTA_DECODE_DENSE_MASK = 16u, /* every stream walks ALL slots [0, tail) of its request and
                                   masks what it may not see: the lists are turned into a 0/1
                                   byte mask per stream on the host, copied to the device, and
                                   applied to the logits.  BF16, head_dim 128 only. */
+  PASTA_DECODE_READ_PROBE = 32u /* measurement aid: in place of the attention launch, its read-only
+                                  form -- the same grid, the same requests for K and V by the same
+                                  waves, no arithmetic -- and no merge: `out` is NOT written.  What a
+                                  plain read of the step's bytes costs with this split of the work
+                                  (the prof events then time that launch).  A deferred append is
+                                  copied by a launch of its own first.  BF16, head_dim 128 only. */
 };
 
 typedef struct {

@@ -70,7 +70,7 @@ struct AttnLds {
 
 struct BlockRegs { u32x4 k[8], v[8]; };  // one lane's share of a 32-token block
 
-template <bool PAGED, bool GATHER, bool DENSE, bool LONG>
+template <bool PAGED, bool GATHER, bool DENSE, bool LONG, bool PROBE>
 __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
   const int tid = threadIdx.x;
@@ -516,6 +516,7 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   // second when the very last load has arrived -- all that is left to do at that point.  Written
   // once per (has1, has2) case, as straight-line code of its own: how many loads stand behind the
   // one that is waited for is a constant only inside one case.
+  u32x4 probe_acc = u32x4{0u, 0u, 0u, 0u};
   auto first_blocks = [&](auto h1, auto h2) {
     DmaRows d{};
     if constexpr (h1.value) {
@@ -542,7 +543,15 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     lds_barrier();  // Q visible to every wave; the only barrier before the end of the item, and it
                     // does not wait for the block loads still in flight
     PASTA_CLK(2);
-    if constexpr (h1.value) {
+    if constexpr (PROBE) {  // read-only form: the same requests, nothing computed
+      wait_vmcnt<0>();
+      tile_sync();
+      if constexpr (h1.value) probe_acc = probe_acc ^ ktw[lane] ^ vtw[lane];
+      if constexpr (h2.value) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) probe_acc = probe_acc ^ br.k[i] ^ br.v[i];
+      }
+    } else if constexpr (h1.value) {
       wait_vmcnt<h2.value ? 24 : 8>();                          // K1 is in the tile
       tile_sync();
       PASTA_CLK(3);
@@ -610,6 +619,22 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   if (has2) first_blocks(std::true_type{}, std::true_type{});
   else if (has1) first_blocks(std::true_type{}, std::false_type{});
   else first_blocks(std::false_type{}, std::false_type{});
+  if constexpr (PROBE) {
+    // What a plain read of this launch's bytes costs at this launch's shape (a measurement aid): every
+    // wave has requested its blocks exactly as above and now only folds them together; later blocks of
+    // long items follow through the registers.  The store below never happens for real data.
+    if constexpr (LONG) {
+      for (int b = w + 8; b < n_blocks; b += 4) {
+        load_block(br, b, std::true_type{});
+#pragma unroll
+        for (int i = 0; i < 8; ++i) probe_acc = probe_acc ^ br.k[i] ^ br.v[i];
+      }
+    }
+    if ((probe_acc[0] ^ probe_acc[1] ^ probe_acc[2] ^ probe_acc[3]) == 0x9E3779B9u && n_tok < 0)
+      p.part_ml[part_row0] = make_float2(0.f, 0.f);
+    PASTA_CLK(7);
+    return;
+  }
   if constexpr (LONG) {  // no other launch has items of more than eight blocks
     for (int b = w + 8; b < n_blocks; b += 4) later_block(b);
   }
@@ -677,8 +702,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
 // first, the private (gather) items' after them.
 // DENSE = the variant that also carries the dense-mask comparison mode (p.dense_mask); the plain
 // variant has none of that code.  LONG = the variant for launches with long items: its
-// steady-state loop addresses plain blocks through buffer loads.
-template <bool PAGED, bool DENSE, bool LONG = false>
+// steady-state loop addresses plain blocks through buffer loads.  PROBE = the read-only form of the
+// same launch (every request of the real one, no arithmetic, no output): what a plain read of these
+// bytes costs with this split of the work.
+template <bool PAGED, bool DENSE, bool LONG = false, bool PROBE = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   static_assert(!LONG || !DENSE, "the long-item variant exists for the list mode");
   __shared__ AttnLds lds;
@@ -721,8 +748,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   // (a raised wave priority for the shared-prefix items, so that the longer items issue their loads
   // first where a SIMD holds a wave of each kind, paid while the private items' compute was heavier;
   // with the present kernel it costs 0.25 us per launch and is gone)
-  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE, LONG>(p, lds, meta, blockIdx.x);
-  else attn_item<PAGED, true, DENSE, LONG>(p, lds, meta, blockIdx.x - n_prefix_wgs);
+  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE, LONG, PROBE>(p, lds, meta, blockIdx.x);
+  else attn_item<PAGED, true, DENSE, LONG, PROBE>(p, lds, meta, blockIdx.x - n_prefix_wgs);
   if (pend_u >= 0) pend_store(pend_u, pend_val);
 }
 

@@ -734,6 +734,8 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
   if (explicit_mode && a->causal_skip) return PASTA_E_INVAL;  // the lists say it all there
   const bool no_share = a->flags & (PASTA_DECODE_NO_SHARE | PASTA_DECODE_DENSE_MASK);
   const bool dense = a->flags & PASTA_DECODE_DENSE_MASK;
+  const bool probe = a->flags & PASTA_DECODE_READ_PROBE;
+  if (probe && (dense || no_alloc || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   if (dense && (c.dtype != PASTA_BF16 || c.head_dim != 128 || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
   float2* part_ml = nullptr;   // where this call's partials go
@@ -889,7 +891,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     const bool mfma = c.dtype == PASTA_BF16 && !(a->flags & PASTA_DECODE_NO_MFMA) && attn_kernel_supports(D, G) &&
                       h->layer_elems * h->elem < ((int64_t)1 << 32) - 65536 &&
                       (int64_t)n * c.n_q_heads * D * h->elem < ((int64_t)1 << 31);
-    if (dense && !mfma) return PASTA_E_INVAL;  // the mask is applied by the matrix-core kernel only
+    if ((dense || probe) && !mfma) return PASTA_E_INVAL;  // the mask and the read-only form belong to the matrix-core kernel
     int64_t pc_total = 0, pc_weighted = 0;  // the second counts a prefix once per row group of 32
     for (auto& q : reqs) {
       if (!mfma || q.pc < kTile || no_share) q.pc = 0;
@@ -1037,7 +1039,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     hipStream_t st = (hipStream_t)c.hip_stream;
     int meta_slot = -1;  // pinned staging slot that this call's kernels read, if any
     // a deferred append rides along with the matrix-core launch of its layer; otherwise K1 runs now
-    const bool take_pending = h->pending.active && mfma && h->pending.layer == a->layer;
+    const bool take_pending = h->pending.active && mfma && h->pending.layer == a->layer && !probe;
     if (h->pending.active && !take_pending) {
       rc = flush_pending(h);
       if (rc != PASTA_OK) return rc;
@@ -1153,7 +1155,10 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
         // prefix chunks of more than two 32-token blocks per wave: the variant whose loop has the
         // cheap addressing of plain blocks
         const bool long_items = n_prefix_wgs > 0 && chunk_tokens > 2 * 4 * 32;
-        if (h->lay.paged) {
+        if (probe) {
+          if (h->lay.paged) { if (long_items) launch(k_attn<true, false, true, true>); else launch(k_attn<true, false, false, true>); }
+          else { if (long_items) launch(k_attn<false, false, true, true>); else launch(k_attn<false, false, false, true>); }
+        } else if (h->lay.paged) {
           if (long_items) launch(k_attn<true, false, true>);
           else launch(k_attn<true, false>);
         } else {
@@ -1171,8 +1176,10 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     int64_t merge_parts = 0;  // every output row reads its request's prefix chunks and its stream's items
     for (int i = 0; i < n; ++i)
       merge_parts += (int64_t)(reqs[stream_req_idx[i]].n_chunks + streams[i].item_end - streams[i].item_begin) * c.n_q_heads;
-    rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p, merge_parts);
-    if (rc != PASTA_OK) return rc;
+    if (!probe) {
+      rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p, merge_parts);
+      if (rc != PASTA_OK) return rc;
+    }
     if (meta_slot >= 0) {
       if (hipEventRecord(h->ring_ev[meta_slot], st) != hipSuccess) return PASTA_E_DEVICE;
       h->ring_used[meta_slot] = true;

@@ -32,6 +32,10 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
     rf = d["roofline"]
     assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9 and 0 < rf["frac"] < 1
+    assert rf["kernel_samples"] >= 8 and rf["kernel_samples_in_timed_region"] >= 2 and rf["kernel_us_min"] <= rf["kernel_us_median"]
+    # the read-only form of the same launch is the measured ceiling: faster than the real launch
+    assert rf["measured_read_us"] is not None and rf["measured_read_us"] < rf["kernel_us"]
+    assert abs(rf["frac_of_measured_read"] - rf["measured_read_us"] / rf["kernel_us"]) < 1e-6
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["unit"] == d["unit"] and cb["sample"]
     assert d["value"] > 100 * cb["value"]
