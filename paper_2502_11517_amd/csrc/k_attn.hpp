@@ -290,9 +290,37 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   const __amdgpu_buffer_rsrc_t k_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kb), 0, -1, kRawBuffer);
   const __amdgpu_buffer_rsrc_t v_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vb), 0, -1, kRawBuffer);
   typedef __attribute__((address_space(3))) void* lds_ptr;
-  struct DmaRows { uint32_t off[8]; bool any_pend; };
+  // A PLAIN block -- 32 existing tokens of an item in a contiguous pool that is not a listed one, none
+  // of them a deferred row -- has rows in arithmetic progression: its addresses are a wave-uniform
+  // byte offset (scalar arithmetic, riding in the load's scalar offset) plus a lane part that is the
+  // same for every block of the item (computed once: four variants for K's swizzle, one for V's, one
+  // for loads into registers).  Every other block computes one address per row, about a dozen vector
+  // instructions each -- which, at 32 rows per wave, is what stands between the start of a work-group
+  // and its first request.
+  const uint32_t row_bytes32 = (uint32_t)__builtin_amdgcn_readfirstlane(stride * p.lay.slot_stride * 2);
+  const bool arith_item = !PAGED && !listed;
+  uint32_t lane_k[4], lane_v, lane_n;
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) lane_k[c4] = (uint32_t)rbase * row_bytes32 + (uint32_t)((piece ^ rbase ^ (4 * c4)) * 16);
+  lane_v = (uint32_t)rbase * row_bytes32 + (uint32_t)((piece ^ (rbase << 2)) * 16);
+  lane_n = (uint32_t)rbase * row_bytes32 + (uint32_t)(piece * 16);
+  auto plain_block = [&](int b) -> bool {
+    return arith_item && b * kBlock + kBlock <= n_tok && slot0 + (b * kBlock + kBlock - 1) * stride < pend0;
+  };
+  auto block_base = [&](int b) -> uint32_t {  // byte offset of a plain block's first row of this kv head
+    const long long e = elem_off(p.lay, req * p.lay.pool_tokens + slot0 + b * kBlock * stride, g) * 2;
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)e);
+  };
+  struct DmaRows { uint32_t off[8]; bool any_pend; bool plain; uint32_t base; };
   auto dma_rows = [&](int b) -> DmaRows {  // K-side offsets of block b's rows for this lane's LDS places
     DmaRows d;
+    d.plain = plain_block(b);
+    d.any_pend = false;
+    d.base = 0;
+    if (d.plain) {
+      d.base = block_base(b);
+      return d;
+    }
     bool pend = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -308,7 +336,12 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   };
   auto dma_half = [&](int b, const DmaRows& d, auto is_v) {  // K (or V) of block b -> kt (vt)
     u32x4* dst = is_v.value ? vtw : ktw;
-    if (!d.any_pend) {
+    if (d.plain) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v.value ? v_rs : k_rs, (lds_ptr)(dst + 64 * i), 16,
+                                                 is_v.value ? lane_v : lane_k[i & 3], d.base + (uint32_t)(4 * i) * row_bytes32, 0, 0);
+    } else if (!d.any_pend) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {  // the row offset is a multiple of 256: bits 4..7 hold the piece alone
         const int r = rbase + 4 * i;
@@ -334,6 +367,13 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     }
   };
   auto load_half = [&](u32x4 (&dst)[8], int b, auto is_v) {  // K (or V) of block b -> registers, natural piece order
+    if (plain_block(b)) {
+      const uint32_t base = block_base(b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        dst[i] = __builtin_amdgcn_raw_buffer_load_b128(is_v.value ? v_rs : k_rs, lane_n, base + (uint32_t)(4 * i) * row_bytes32, 0);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int j = min(b * kBlock + rbase + 4 * i, n_tok - 1);
