@@ -219,6 +219,10 @@ enum {
                                   masks what it may not see: the lists are turned into a 0/1
                                   byte mask per stream on the host, copied to the device, and
                                   applied to the logits.  BF16, head_dim 128 only. */
+  /* Two flags for testing the kernels one by one (with dbg_part_ml / dbg_part_acc below): */
+  PASTA_DECODE_PARTIALS_ONLY = 64u, /* the attention launch(es) only, no merge: `out` is NOT written */
+  PASTA_DECODE_MERGE_ONLY = 128u,   /* the merge launch only, over the partial rows as the buffers hold them
+                                       (no attention launch, a deferred append is copied by a launch of its own) */
   PASTA_DECODE_READ_PROBE = 32u /* measurement aid: in place of the attention launch, its read-only
                                   form -- the same grid, the same requests for K and V by the same
                                   waves, no arithmetic -- and no merge: `out` is NOT written.  What a
@@ -260,7 +264,20 @@ typedef struct {
   int64_t *dbg_plan;            /* HOST [8] or NULL: out, launch plan: {prefix tiles,
                                    prefix work-groups, private items, partial rows,
                                    tokens per prefix chunk, common-prefix tokens
-                                   summed over requests, metadata bytes, 0} */
+                                   summed over requests, metadata bytes, first private
+                                   partial row} */
+  float *dbg_part_ml;           /* DEVICE [rows][2] fp32 or NULL (both or neither) */
+  float *dbg_part_acc;          /* DEVICE [rows][head_dim] fp32 or NULL: when given, the step's split partials live
+                                   here instead of in the workspace; rows = dbg_plan[3] of the same call planned with
+                                   PASTA_DECODE_PLAN_ONLY.  One row per (split part, query row): m = the part's largest
+                                   logit times log2(e) (softmax_scale applied; -inf and l = 0 for a part in which the
+                                   row sees nothing), l = sum of 2^(logit log2 e - m), acc = the same weights times V,
+                                   not normalised.  Rows of a step over ONE request: the shared-prefix part of (kv head
+                                   g, chunk c, stacked query row r = stream index * G + head in group) is row
+                                   (g * n_chunks + c) * R + r, with R = n_streams * G and n_chunks = ceil(dbg_plan[5] /
+                                   dbg_plan[4]); the private part of (item j, kv head g, head in group i) is row
+                                   dbg_plan[7] + (j * Hkv + g) * G + i, the items of a stream being consecutive
+                                   128-token pieces of its list beyond the common prefix, stream after stream. */
   void *prof_event_start;       /* hipEvent_t or NULL (both or neither): they receive the start and the */
   void *prof_event_stop;        /* end of the attention-partials kernel's execution (attached to its
                                    dispatch; with PASTA_DECODE_NO_MFMA or F32: recorded on the stream

@@ -20,6 +20,7 @@ OK, E_INVAL, E_CAPACITY, E_NOMEM, E_DEVICE, E_STATE = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
 DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q, DECODE_NO_SHARE, DECODE_DENSE_MASK, DECODE_READ_PROBE = 1, 2, 4, 8, 16, 32
+DECODE_PARTIALS_ONLY, DECODE_MERGE_ONLY = 64, 128
 APPEND_RESERVE_ONLY, APPEND_DEFER, APPEND_ROPE = 1, 2, 4
 SYNC_RETIRE = 1
 OP_TEXT, OP_PROMISE, OP_SYNC = 0, 1, 2
@@ -101,7 +102,8 @@ class DecodeArgs(C.Structure):
         ("prefix_len", C.c_void_p), ("range_offsets", C.c_void_p), ("range_start", C.c_void_p),
         ("range_count", C.c_void_p), ("range_stride", C.c_void_p), ("q", C.c_void_p), ("out", C.c_void_p),
         ("out_lse", C.c_void_p), ("dbg_gather_offsets", C.c_void_p), ("dbg_gather_rows", C.c_void_p),
-        ("dbg_plan", C.c_void_p), ("prof_event_start", C.c_void_p), ("prof_event_stop", C.c_void_p),
+        ("dbg_plan", C.c_void_p), ("dbg_part_ml", C.c_void_p), ("dbg_part_acc", C.c_void_p),
+        ("prof_event_start", C.c_void_p), ("prof_event_stop", C.c_void_p),
     ]
 
 
@@ -208,7 +210,7 @@ class PastaAttn:
 
     def decode_step(self, layer, request_id, stream_id, q, out, *, lists=None, out_lse=None, flags=0,
                     position=None, dbg_gather_offsets=None, dbg_gather_rows=None, dbg_plan=None,
-                    prof_events=None, causal_skip=None, _entry="pasta_attn_decode_step"):
+                    prof_events=None, causal_skip=None, dbg_partials=None, _entry="pasta_attn_decode_step"):
         """lists = (prefix_len, range_offsets, start, count, stride) for explicit visibility;
         None uses the lists append_kv has maintained."""
         rid, sid, pos, skip = _i32(request_id), _i32(stream_id), _i32(position), _i32(causal_skip)
@@ -220,9 +222,10 @@ class PastaAttn:
         else:
             pl = offs = st = ct = sd = None
         ev0, ev1 = prof_events if prof_events is not None else (None, None)
+        pml, pacc = dbg_partials if dbg_partials is not None else (None, None)
         a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, n, _hp(rid), _hp(sid), _hp(pos), _hp(skip), _hp(pl), _hp(offs),
                        _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), _hp(dbg_gather_offsets),
-                       _dp(dbg_gather_rows), _hp(dbg_plan), ev0, ev1)
+                       _dp(dbg_gather_rows), _hp(dbg_plan), _dp(pml), _dp(pacc), ev0, ev1)
         rc = getattr(self._lib, _entry)(self._h, C.byref(a))
         if rc != OK:
             raise PastaError(rc, _entry)
@@ -252,7 +255,7 @@ class PastaAttn:
         ev0, ev1 = prof_events if prof_events is not None else (None, None)
         a = DecodeArgs(C.sizeof(DecodeArgs), flags, layer, int(rid.shape[0]), _hp(rid), _hp(sid), _hp(pos), None, _hp(pl),
                        _hp(offs), _hp(st), _hp(ct), _hp(sd), _dp(q), _dp(out), _dp(out_lse), None, None, None,
-                       ev0, ev1)
+                       None, None, ev0, ev1)
         fn, h, ref = self._lib.pasta_attn_decode_step, self._h, C.byref(a)
 
         def call(_keep=(rid, sid, pos, pl, offs, st, ct, sd, a, q, out, out_lse)):

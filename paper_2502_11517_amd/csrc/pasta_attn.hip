@@ -735,6 +735,10 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
   const bool no_share = a->flags & (PASTA_DECODE_NO_SHARE | PASTA_DECODE_DENSE_MASK);
   const bool dense = a->flags & PASTA_DECODE_DENSE_MASK;
   const bool probe = a->flags & PASTA_DECODE_READ_PROBE;
+  const bool partials_only = a->flags & PASTA_DECODE_PARTIALS_ONLY, merge_only = a->flags & PASTA_DECODE_MERGE_ONLY;
+  if ((partials_only && merge_only) || ((partials_only || merge_only) && probe)) return PASTA_E_INVAL;
+  if ((a->dbg_part_ml == nullptr) != (a->dbg_part_acc == nullptr)) return PASTA_E_INVAL;
+  if (a->dbg_part_ml && (no_alloc || ((uintptr_t)a->dbg_part_ml & 7) || ((uintptr_t)a->dbg_part_acc & 15))) return PASTA_E_INVAL;
   if (probe && (dense || no_alloc || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   if (dense && (c.dtype != PASTA_BF16 || c.head_dim != 128 || (a->flags & PASTA_DECODE_NO_MFMA))) return PASTA_E_INVAL;
   const int G = h->G, D = c.head_dim, Hkv = c.n_kv_heads;
@@ -762,6 +766,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     if (rc0 != PASTA_OK) return rc0;
     part_ml = (float2*)((char*)c.workspace + h->off_ml);
     part_acc = (float*)((char*)c.workspace + h->off_acc);
+    if (a->dbg_part_ml) { part_ml = (float2*)a->dbg_part_ml; part_acc = a->dbg_part_acc; }
   }
   // a buffer of the plan may grow only where allocation is allowed
   auto room = [&](const auto& v, size_t want) { return !no_alloc || want <= v.capacity(); };
@@ -1030,7 +1035,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
       a->dbg_plan[4] = pc_total ? chunk_tokens : 0;
       a->dbg_plan[5] = pc_total;
       a->dbg_plan[6] = (int64_t)blob.size() * 4;
-      a->dbg_plan[7] = 0;
+      a->dbg_plan[7] = prefix_rows;
     }
     if (plan_only) return PASTA_OK;
 
@@ -1039,7 +1044,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     hipStream_t st = (hipStream_t)c.hip_stream;
     int meta_slot = -1;  // pinned staging slot that this call's kernels read, if any
     // a deferred append rides along with the matrix-core launch of its layer; otherwise K1 runs now
-    const bool take_pending = h->pending.active && mfma && h->pending.layer == a->layer && !probe;
+    const bool take_pending = h->pending.active && mfma && h->pending.layer == a->layer && !probe && !merge_only;
     if (h->pending.active && !take_pending) {
       rc = flush_pending(h);
       if (rc != PASTA_OK) return rc;
@@ -1142,7 +1147,9 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     const hipEvent_t ev0 = (hipEvent_t)a->prof_event_start, ev1 = (hipEvent_t)a->prof_event_stop;
     const bool ev_in_dispatch = mfma && ev0 && ev1;
     if (ev0 && !ev_in_dispatch && hipEventRecord(ev0, st) != hipSuccess) return PASTA_E_DEVICE;
-    if (mfma) {
+    if (merge_only) {
+      // (kernel-isolated test of the merge: the partial buffers are taken as they are)
+    } else if (mfma) {
       const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
       auto launch = [&](auto kernel) {
         if (ev_in_dispatch) hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kAttnThreads), 0, st, ev0, ev1, 0, p);
@@ -1176,7 +1183,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     int64_t merge_parts = 0;  // every output row reads its request's prefix chunks and its stream's items
     for (int i = 0; i < n; ++i)
       merge_parts += (int64_t)(reqs[stream_req_idx[i]].n_chunks + streams[i].item_end - streams[i].item_begin) * c.n_q_heads;
-    if (!probe) {
+    if (!probe && !partials_only) {
       rc = launch_merge(h, dim3((unsigned)Hkv, (unsigned)G, (unsigned)n), st, p, merge_parts);
       if (rc != PASTA_OK) return rc;
     }
