@@ -219,6 +219,10 @@ enum {
                                   masks what it may not see: the lists are turned into a 0/1
                                   byte mask per stream on the host, copied to the device, and
                                   applied to the logits.  BF16, head_dim 128 only. */
+  PASTA_DECODE_DEVICE_LISTS = 256u, /* maintained mode: take the lists from their device-resident copy even when the
+                                       step's plan would fit the kernel arguments (see "Maintained lists on the
+                                       device" below); E_INVAL with explicit lists, causal_skip or DENSE_MASK,
+                                       E_CAPACITY when the copy has no room */
   /* Two flags for testing the kernels one by one (with dbg_part_ml / dbg_part_acc below): */
   PASTA_DECODE_PARTIALS_ONLY = 64u, /* the attention launch(es) only, no merge: `out` is NOT written */
   PASTA_DECODE_MERGE_ONLY = 128u,   /* the merge launch only, over the partial rows as the buffers hold them
@@ -231,6 +235,15 @@ enum {
                                   copied by a launch of its own first.  BF16, head_dim 128 only. */
 };
 
+/* Maintained lists on the device.  The lists that append_kv keeps per (request, stream) have a copy in the
+ * workspace: every range with the running token count, and an index from token number to range.  Appends of up
+ * to 32 rows bring the entries they change up to date in their own K1 launch; larger appends, forks and joins
+ * mark a stream's copy for a rebuild, done (one stream-ordered copy) by the next decode step that reads it.  A
+ * decode step in maintained mode whose plan would not fit the kernel arguments then sends one fixed-size record
+ * per stream -- with the stream's newest range, which changes at every append, inline -- and the kernels find
+ * ranges and derive the private work items themselves: the bytes a step sends do not grow with the lists, no
+ * KV row and no list entry moves at a join (Section 3, "Efficiency").  Small plans ride in the kernel arguments
+ * as before (no dependent loads on the way to the first K/V request).                                      */
 typedef struct {
   uint32_t struct_size;
   uint32_t flags;               /* PASTA_DECODE_* */
@@ -277,7 +290,9 @@ typedef struct {
                                    (g * n_chunks + c) * R + r, with R = n_streams * G and n_chunks = ceil(dbg_plan[5] /
                                    dbg_plan[4]); the private part of (item j, kv head g, head in group i) is row
                                    dbg_plan[7] + (j * Hkv + g) * G + i, the items of a stream being consecutive
-                                   128-token pieces of its list beyond the common prefix, stream after stream. */
+                                   128-token pieces of its list beyond the common prefix, stream after stream (a
+                                   step that reads the device-resident lists cuts the visible head beyond the common
+                                   prefix and the range list into pieces separately). */
   void *prof_event_start;       /* hipEvent_t or NULL (both or neither): they receive the start and the */
   void *prof_event_stop;        /* end of the attention-partials kernel's execution (attached to its
                                    dispatch; with PASTA_DECODE_NO_MFMA or F32: recorded on the stream

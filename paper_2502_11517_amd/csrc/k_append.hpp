@@ -9,6 +9,7 @@
 namespace pasta {
 
 constexpr int kAppendInline = 32;  // destination rows that travel in the kernel arguments
+constexpr int kPatchMax = 64;      // most entries of the device-resident lists one launch brings up to date
 
 struct AppendParams {
   const uint4* k_new;   // [n_rows][Hkv][D] as 16-byte pieces
@@ -25,11 +26,25 @@ struct AppendParams {
   const double* rope_tab;             // theta^(-2f/D) / (2 pi), f < D/2 (device)
   const int32_t* pos_rows;            // position id per appended row (device), or null:
   int32_t inline_pos[kAppendInline];  // then the ids are here
+  // The append also extends the device-resident visibility lists (the lists that decode steps in
+  // maintained mode read): entries of the range arena and of the range index that this call's rows
+  // changed or created, computed by the host from its mirror.
+  DevRange* arena;
+  int32_t* cidx;
+  int n_rpatch, n_cpatch;
+  int32_t rp_idx[kPatchMax];
+  DevRange rp_val[kPatchMax];
+  int32_t cp_idx[kPatchMax];
+  int32_t cp_val[kPatchMax];
 };
+
+static_assert(sizeof(AppendParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 __global__ __launch_bounds__(256) void k_append(AppendParams p) {
   const long long total = (long long)p.n_rows * p.Hkv * p.pieces_per_head;
   long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < p.n_rpatch) p.arena[p.rp_idx[t]] = p.rp_val[t];
+  else if (t < p.n_rpatch + p.n_cpatch) p.cidx[p.cp_idx[t - p.n_rpatch]] = p.cp_val[t - p.n_rpatch];
   if (t >= 2 * total) return;
   const bool is_v = t >= total;
   if (is_v) t -= total;
@@ -48,6 +63,25 @@ __global__ __launch_bounds__(256) void k_append(AppendParams p) {
     val = (is_v ? p.v_new : p.k_new)[t];
   }
   *reinterpret_cast<uint4*>(reinterpret_cast<char*>(is_v ? p.v : p.k) + off_bytes) = val;
+}
+
+// Carries a piece of a decode step's plan to the device inside its own kernel arguments: a plan too large
+// for the attention launch's arguments, but small (a few KB: one fixed-size record per stream), gets to
+// device memory this way in one or two tiny launches -- no copy engine, and no kernel reading host memory.
+constexpr int kRelayWords = 960;
+struct RelayParams {
+  int32_t* dst;
+  int n_words;
+  int32_t words[kRelayWords];
+};
+static_assert(sizeof(RelayParams) <= 4096, "kernel arguments are limited to 4 KB");
+
+__global__ __launch_bounds__(256) void k_meta_relay(RelayParams p) {
+  typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+  kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  const int32_t __attribute__((address_space(4)))* src =
+      (const int32_t __attribute__((address_space(4)))*)(ka + __builtin_offsetof(RelayParams, words));
+  for (int i = threadIdx.x; i < p.n_words; i += 256) p.dst[i] = src[i];
 }
 
 }  // namespace pasta

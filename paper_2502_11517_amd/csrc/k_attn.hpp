@@ -64,6 +64,7 @@ struct AttnLds {
   u32x4 q[32 * 16];            // stacked Q rows, same swizzle (rows >= R are zero)
   float mw[4][32], lw[4][32];  // per-wave row max / row sum at the end of the item
   uint8_t mask[kGatherMax];    // dense-mask comparison mode: the item's slice of its stream's mask
+  int sel[2];                  // device-resident lists: which candidate ranges hold an item's first and last token
   int rows[kGatherMax];        // listed gather items: row code of every token
   DevRange ranges[kGatherMax]; // listed gather items: the ranges the item overlaps
 };
@@ -129,7 +130,22 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   } else {
     const int item = wi / p.Hkv;
     g = wi % p.Hkv;
-    const DevItem it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item];
+    // the work item: from the blob, or -- device-resident lists -- derived from the stream's record;
+    // a piece of a device-resident range list then finds its ranges among the candidates below
+    DevItem it;
+    int nr = 0, range0 = 0;      // ranges to bring into LDS: [range0, range0 + nr) of the blob or of the stream's arena
+    bool in_ranges = false;
+    DevStream dst{};
+    if (!p.dev_tables) {
+      it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item];
+      nr = it.n_ranges > 1 ? it.n_ranges : 0;
+      range0 = it.range_first;
+    } else {
+      const int si = dev_stream_of_item(p, meta, item);
+      dst = reinterpret_cast<const DevStream*>(meta + p.off_streams)[si];
+      it = dev_item(p, dst, si, item, in_ranges);
+      if (in_ranges) range0 = dev_item_candidates(p, dst, it.tok_begin, it.tok_count, kGatherMax, nr);
+    }
     if (p.single_req) {  // scalars from the kernel arguments
       req = p.req0.req; pend0 = p.req0.pend0; pend_src0 = p.req0.pend_src0;
     } else {
@@ -151,19 +167,44 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       for (int j = tid; j < kGatherMax; j += kAttnThreads)
         lds.mask[j] = j < n_tok ? p.dense_mask[mb + slot0 + j] : 0;  // published by the Q barrier
     }
-    if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> row code
-      const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
-      const int nr = it.n_ranges;
-      for (int r = tid; r < nr; r += kAttnThreads) lds.ranges[r] = ranges[it.range_first + r];
+    if (p.dev_tables && in_ranges) {
+      // candidates -> LDS; the two that hold the piece's first and last token are found on the way
+      const int t_lo = it.tok_begin, t_hi = it.tok_begin + it.tok_count - 1;
+      for (int r = tid; r < nr; r += kAttnThreads) {
+        const DevRange rg = dev_range_at(p, dst, range0 + r);
+        lds.ranges[r] = rg;
+        if (rg.cum <= t_lo && t_lo < rg.cum + rg.count) lds.sel[0] = r;
+        if (rg.cum <= t_hi && t_hi < rg.cum + rg.count) lds.sel[1] = r;
+      }
       __syncthreads();
+      const int ra = lds.sel[0], rb = lds.sel[1];
+      const DevRange r0 = lds.ranges[ra];
+      it.slot0 = r0.start + (t_lo - r0.cum) * r0.stride;
+      it.stride = r0.stride;
+      it.n_ranges = rb - ra + 1;
+      slot0 = it.slot0;
+      stride = it.stride;
+      listed = it.n_ranges > 1;
+      range0 = ra;                 // from here on: index into lds.ranges
+      nr = it.n_ranges;
+    }
+    if (listed) {  // ranges the item overlaps -> LDS, then every token of the item -> row code
+      const DevRange* lr = lds.ranges;
+      if (!p.dev_tables) {
+        const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
+        for (int r = tid; r < nr; r += kAttnThreads) lds.ranges[r] = ranges[range0 + r];
+        __syncthreads();
+      } else {
+        lr = lds.ranges + range0;
+      }
       for (int j = tid; j < n_tok; j += kAttnThreads) {
         const int tok = it.tok_begin + j;
         int lo = 0, hi = nr - 1;  // last range with cum <= tok
         while (lo < hi) {
           const int mid = (lo + hi + 1) >> 1;
-          if (lds.ranges[mid].cum <= tok) lo = mid; else hi = mid - 1;
+          if (lr[mid].cum <= tok) lo = mid; else hi = mid - 1;
         }
-        const DevRange rg = lds.ranges[lo];
+        const DevRange rg = lr[lo];
         const int slot = rg.start + (tok - rg.cum) * rg.stride;
         const int phys = phys_row(p.lay, p.page_table, req, slot);
         lds.rows[j] = slot >= pend0 ? -1 - (pend_src0 + (slot - pend0)) : phys;  // deferred rows: -(1 + row)

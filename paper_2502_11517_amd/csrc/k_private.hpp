@@ -57,22 +57,48 @@ __device__ __forceinline__ void private_item(const DecodeParams& p, PrivLds& lds
   const int sub = lane / LPR, dl = lane % LPR;
 
   const int32_t* meta = meta_of(p);
-  const DevItem it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item_idx];
-  const DevStream st = reinterpret_cast<const DevStream*>(meta + p.off_streams)[it.stream];
-  const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
+  // the work item and the ranges it overlaps: from the blob, or -- device-resident lists -- derived from
+  // the stream's record, the ranges picked among the candidates that the arena holds
+  DevItem it;
+  DevStream st;
+  int r_first = 0, nr = 1;         // blob: ranges [r_first, r_first + nr) of the blob; device: candidates
+  int tok_base = 0;                // index of the item's first token in the space that `cum` counts
+  bool synth = false;              // the piece is plain slots [slot0, slot0 + cnt): no range to look up
+  if (!p.dev_tables) {
+    it = reinterpret_cast<const DevItem*>(meta + p.off_items)[item_idx];
+    st = reinterpret_cast<const DevStream*>(meta + p.off_streams)[it.stream];
+    r_first = it.range_first;
+    nr = it.n_ranges;
+    tok_base = it.tok_begin;
+  } else {
+    const int si = dev_stream_of_item(p, meta, item_idx);
+    st = reinterpret_cast<const DevStream*>(meta + p.off_streams)[si];
+    bool in_ranges;
+    it = dev_item(p, st, si, item_idx, in_ranges);
+    tok_base = it.tok_begin;
+    synth = !in_ranges;
+    if (in_ranges) r_first = dev_item_candidates(p, st, it.tok_begin, it.tok_count, kPrivChunk, nr);
+  }
   const int cnt = it.tok_count;
+  // where the item's rows go in the debug gather map
+  const int gather0 = p.dev_tables ? it.gather_pos : st.gather_base + st.pc + it.tok_begin;
 
-  // -- the ranges this chunk overlaps: [range_first, range_first + nr), at most cnt
-  const int r_first = it.range_first;
-  const int nr = it.n_ranges;
-  for (int r = lane; r < nr; r += kWave) lds.ranges[wave][r] = ranges[r_first + r];
+  if (synth) {
+    if (lane == 0) lds.ranges[wave][0] = DevRange{it.slot0, cnt, 1, tok_base};
+    nr = 1;
+  } else if (!p.dev_tables) {
+    const DevRange* ranges = reinterpret_cast<const DevRange*>(meta + p.off_ranges);
+    for (int r = lane; r < nr; r += kWave) lds.ranges[wave][r] = ranges[r_first + r];
+  } else {
+    for (int r = lane; r < nr; r += kWave) lds.ranges[wave][r] = dev_range_at(p, st, r_first + r);
+  }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
   // -- expand token index -> physical row
   for (int j = lane; j < cnt; j += kWave) {
-    const int tok = it.tok_begin + j;
+    const int tok = tok_base + j;
     int lo = 0, hi = nr - 1;  // last range with cum <= tok
     while (lo < hi) {
       int mid = (lo + hi + 1) >> 1;
@@ -82,7 +108,7 @@ __device__ __forceinline__ void private_item(const DecodeParams& p, PrivLds& lds
     const int slot = rg.start + (tok - rg.cum) * rg.stride;
     const int phys = phys_row(p.lay, p.page_table, st.req, slot);
     lds.rows[wave][j] = phys;
-    if (p.dbg_rows && g == 0) p.dbg_rows[st.gather_base + st.pc + tok] = phys;
+    if (p.dbg_rows && g == 0) p.dbg_rows[gather0 + j] = phys;
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();

@@ -27,6 +27,7 @@ namespace {
 
 constexpr uint32_t kMagic = 0x50415354u;  // "PAST"
 constexpr int kRing = 8;                  // metadata staging buffers in flight
+constexpr int kRelayMaxWords = 2 * kRelayWords;  // largest plan that travels to the device inside kernel arguments
 constexpr int kNumCUs = 256;              // MI355X; planning default until the device has been asked
 constexpr int kTargetPrefixWgs = 768;     // most shared-prefix work-groups budgeted for
 
@@ -36,6 +37,17 @@ struct StreamState {
   bool open = false;
   int32_t prefix_len = 0;        // visible head [0, prefix_len)
   std::vector<Range> ranges;     // then these, span-ascending
+  int64_t range_tokens = 0;      // tokens in `ranges`
+  // The copy of the range list that lives on the device (workspace): ranges with running token counts in
+  // the arena, and an index "range that holds range token 32 j".  Small appends patch it through the K1
+  // launch, everything else (prefill, fork, join, relocation) marks it dirty and it is rebuilt from this
+  // mirror at the next decode step that wants it.  The newest range is never relied on: it grows with
+  // every append and rides with each call instead.
+  int32_t seg_off = -1, seg_cap = 0;    // arena segment (DevRange entries)
+  int32_t cseg_off = -1, cseg_cap = 0;  // index segment (int32 entries)
+  int32_t dev_ranges = 0;        // arena entries [0, dev_ranges) are exact
+  int32_t dev_cidx = 0;          // index entries [0, dev_cidx) are on the device; all later ones lie in the newest range
+  bool dirty = true;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -95,8 +107,20 @@ struct pasta_attn {
     bool rope = false;                 // PASTA_APPEND_ROPE: K still to be rotated by pos
     int32_t pos[kAppendInline]{};
     std::vector<int32_t> req_pend0, req_src0;  // per request: first deferred slot, its row in k_new
+    std::vector<int32_t> stage_p0, stage_s0, stage_last;  // (their buffers while a call is looked at)
   } pending;
   PlanBuf pb;
+  // device-resident lists: carve-up and bump allocation (entries)
+  size_t off_arena = 0, off_cidx = 0;
+  int64_t arena_cap = 0, cidx_cap = 0, arena_top = 0, cidx_top = 0;
+  bool tables_reset = false;             // the segments ran out: start over at the next call (all streams dirty)
+  std::vector<DevRange> stage_r;         // staging of one stream's lists for a rebuild
+  std::vector<int32_t> stage_c;
+  struct Undo { int64_t key; bool open; int32_t prefix_len; int32_t n_ranges; Range last; int64_t range_tokens;
+                int32_t dev_ranges, dev_cidx; bool dirty; bool replaced; std::vector<Range> saved; };
+  std::vector<Undo> undo;                // append_kv: what to restore if a later row of the call fails
+  std::vector<int64_t> t2;
+  std::vector<int32_t> dst_rows, slots;
   int tune_prefix_chunk = 0, tune_priv_chunk = 0;  // forced chunk sizes (tokens; 0 = heuristic): set only by -DPASTA_TUNING builds
   // device-side readiness (deferred so that the host logic works without a GPU)
   bool device_ready = false;
@@ -105,7 +129,7 @@ struct pasta_attn {
   int ring_ev_made = 0;                  // events created so far (all kRing once the device is ready)
   int device = 0, n_cus = kNumCUs;       // the device current at first use and its compute-unit count
   bool ring_used[kRing]{};
-  int ring_next = 0;
+  int ring_next = 0, relay_next = 0;
 };
 
 namespace {
@@ -174,6 +198,16 @@ void carve(pasta_attn* h) {
     h->mask_bytes = align_up((size_t)c.max_requests * c.max_streams * (size_t)cap_tokens + 256, 256);
     h->off_mask = off;
     off += h->mask_bytes;
+  }
+  {  // device-resident lists: room for every range twice over (segments grow by doubling) and for the index
+    const int64_t ns = (int64_t)c.max_requests * c.max_streams;
+    const int64_t cap_tokens = c.page_tokens ? (int64_t)c.pages_per_request * c.page_tokens : c.pool_tokens;
+    h->arena_cap = std::min<int64_t>(4 * ((int64_t)c.max_ranges + ns * 16), (int64_t)1 << 26);
+    h->cidx_cap = std::min<int64_t>(2 * (ns * (cap_tokens / kCidxTokens + 16)), (int64_t)1 << 26);
+    h->off_arena = off;
+    off += align_up((size_t)h->arena_cap * sizeof(DevRange), 256);
+    h->off_cidx = off;
+    off += align_up((size_t)h->cidx_cap * 4, 256);
   }
   if (c.rope_theta > 0.f) {
     h->off_rope = off;
@@ -247,6 +281,65 @@ int upload_meta(pasta_attn* h, const void* src, size_t bytes, const int32_t** de
   return PASTA_OK;
 }
 
+// Copies host data to a device address in the workspace, asynchronously on the caller's stream, through
+// the pinned ring (in pieces of one staging slot).
+int upload_to(pasta_attn* h, void* dev_dst, const void* src, size_t bytes) {
+  hipStream_t st = (hipStream_t)h->cfg.hip_stream;
+  for (size_t lo = 0; lo < bytes; lo += h->meta_bytes) {
+    const size_t n = std::min(h->meta_bytes, bytes - lo);
+    const int sl = h->ring_next;
+    h->ring_next = (sl + 1) % kRing;
+    if (h->ring_used[sl] && hipEventSynchronize(h->ring_ev[sl]) != hipSuccess) return PASTA_E_DEVICE;
+    char* host = h->pinned + (size_t)sl * h->meta_bytes;
+    std::memcpy(host, (const char*)src + lo, n);
+    if (hipMemcpyAsync((char*)dev_dst + lo, host, n, hipMemcpyHostToDevice, st) != hipSuccess) return PASTA_E_DEVICE;
+    if (hipEventRecord(h->ring_ev[sl], st) != hipSuccess) return PASTA_E_DEVICE;
+    h->ring_used[sl] = true;
+  }
+  return PASTA_OK;
+}
+
+constexpr int kNoRoom = 1;  // rebuild_tables: the segments ran out (not an error: the call plans from the host lists)
+
+// Rebuilds the device copy of one stream's range list and range index from the mirror.
+int rebuild_tables(pasta_attn* h, StreamState& st) {
+  const int64_t n = (int64_t)st.ranges.size();
+  const int64_t n_c = (st.range_tokens + kCidxTokens - 1) / kCidxTokens;
+  if (n > st.seg_cap) {
+    const int64_t cap = std::max<int64_t>(16, 2 * n);
+    if (h->arena_top + cap > h->arena_cap) { h->tables_reset = true; return kNoRoom; }
+    st.seg_off = (int32_t)h->arena_top;
+    st.seg_cap = (int32_t)cap;
+    h->arena_top += cap;
+  }
+  if (n_c > st.cseg_cap) {
+    const int64_t cap = std::max<int64_t>(16, 2 * n_c);
+    if (h->cidx_top + cap > h->cidx_cap) { h->tables_reset = true; return kNoRoom; }
+    st.cseg_off = (int32_t)h->cidx_top;
+    st.cseg_cap = (int32_t)cap;
+    h->cidx_top += cap;
+  }
+  std::vector<DevRange>& sr = h->stage_r;
+  std::vector<int32_t>& sc = h->stage_c;
+  sr.resize((size_t)n);
+  sc.resize((size_t)n_c);
+  int64_t cum = 0, tok = 0;
+  for (int64_t k = 0; k < n; ++k) {
+    const Range& g = st.ranges[(size_t)k];
+    sr[(size_t)k] = DevRange{g.start, g.count, g.stride, (int32_t)cum};
+    for (; tok < cum + g.count; tok += kCidxTokens) sc[(size_t)(tok / kCidxTokens)] = (int32_t)k;
+    cum += g.count;
+  }
+  int rc = PASTA_OK;
+  if (n) rc = upload_to(h, (char*)h->cfg.workspace + h->off_arena + (size_t)st.seg_off * sizeof(DevRange), sr.data(), (size_t)n * sizeof(DevRange));
+  if (rc == PASTA_OK && n_c) rc = upload_to(h, (char*)h->cfg.workspace + h->off_cidx + (size_t)st.cseg_off * 4, sc.data(), (size_t)n_c * 4);
+  if (rc != PASTA_OK) return rc;
+  st.dev_ranges = (int32_t)n;
+  st.dev_cidx = (int32_t)n_c;
+  st.dirty = false;
+  return PASTA_OK;
+}
+
 inline StreamState& sstate(pasta_attn* h, int req, int sid) {
   return h->streams[(size_t)req * h->cfg.max_streams + sid];
 }
@@ -261,6 +354,7 @@ inline int64_t host_phys(const pasta_attn* h, int req, int64_t slot) {
 // Adds an owned slot to a stream's list (slots arrive in increasing order).
 void add_slot(StreamState& s, int32_t slot) {
   if (s.ranges.empty() && slot == s.prefix_len) { s.prefix_len++; return; }
+  s.range_tokens++;
   if (!s.ranges.empty()) {
     Range& r = s.ranges.back();
     if (r.count == 1 && slot > r.start) { r.stride = slot - r.start; r.count = 2; return; }
@@ -319,11 +413,30 @@ int launch_merge(const pasta_attn* h, dim3 grid, hipStream_t st, const DecodePar
                  : launch_merge_g<uint16_t, 128>(h->G, grid, st, p, total_parts);
 }
 
+struct ListPatches {  // entries of the device-resident lists that an append brings up to date
+  int n_r = 0, n_c = 0;
+  int32_t r_idx[kPatchMax];
+  DevRange r_val[kPatchMax];
+  int32_t c_idx[kPatchMax];
+  int32_t c_val[kPatchMax];
+};
+
 int launch_append(pasta_attn* h, int layer, int n_rows, const void* k_new, const void* v_new,
-                  const int32_t* dst_rows, const int32_t* positions = nullptr) {  // positions: rotate K
+                  const int32_t* dst_rows, const int32_t* positions = nullptr,  // positions: rotate K
+                  const ListPatches* patches = nullptr) {
   const pasta_attn_config& c = h->cfg;
   hipStream_t st = (hipStream_t)c.hip_stream;
   AppendParams p{};
+  p.arena = (DevRange*)((char*)c.workspace + h->off_arena);
+  p.cidx = (int32_t*)((char*)c.workspace + h->off_cidx);
+  if (patches) {  // (only with rows that travel in the kernel arguments: one launch)
+    p.n_rpatch = patches->n_r;
+    p.n_cpatch = patches->n_c;
+    std::memcpy(p.rp_idx, patches->r_idx, sizeof(int32_t) * patches->n_r);
+    std::memcpy(p.rp_val, patches->r_val, sizeof(DevRange) * patches->n_r);
+    std::memcpy(p.cp_idx, patches->c_idx, sizeof(int32_t) * patches->n_c);
+    std::memcpy(p.cp_val, patches->c_val, sizeof(int32_t) * patches->n_c);
+  }
   p.k = (char*)c.k_pool + (size_t)layer * h->layer_elems * h->elem;
   p.v = (char*)c.v_pool + (size_t)layer * h->layer_elems * h->elem;
   p.lay = h->lay;
@@ -509,73 +622,151 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
   }
   const bool commit = a->layer == 0;  // layer 0 assigns the slots; other layers replay them
 
-  // ---- dry run on copies of the touched state
-  std::unordered_map<int64_t, StreamState> touched;
-  std::vector<int64_t> t2;
-  std::vector<int32_t> dst_rows, slots;
+  // ---- the rows, one by one, on the live state; what a failing call has to put back is logged
+  // (per touched stream: its state at first touch -- an append only ever changes a list's newest range
+  // or adds ranges behind it)
+  std::vector<int64_t>& t2 = h->t2;
+  std::vector<int32_t>&dst_rows = h->dst_rows, &slots = h->slots;
+  std::vector<pasta_attn::Undo>& undo = h->undo;
+  auto roll_back = [&]() {
+    for (size_t u = undo.size(); u-- > 0;) {
+      pasta_attn::Undo& e = undo[u];
+      StreamState& st = h->streams[(size_t)e.key];
+      if (e.replaced) st.ranges = std::move(e.saved);
+      st.ranges.resize((size_t)e.n_ranges);
+      if (e.n_ranges) st.ranges.back() = e.last;
+      st.open = e.open; st.prefix_len = e.prefix_len; st.range_tokens = e.range_tokens;
+      st.dev_ranges = e.dev_ranges; st.dev_cidx = e.dev_cidx; st.dirty = e.dirty;
+    }
+    undo.clear();
+  };
   try {
     t2 = commit ? h->tail : h->tail_before;
     dst_rows.resize(a->n_rows);
     slots.resize(a->n_rows);
-    auto view = [&](int req, int sid) -> StreamState& {
+    undo.clear();
+    auto touch = [&](int req, int sid) -> StreamState& {  // logs the stream's state the first time it is touched
       const int64_t key = (int64_t)req * c.max_streams + sid;
-      auto it = touched.find(key);
-      if (it == touched.end()) it = touched.emplace(key, sstate(h, req, sid)).first;
-      return it->second;
+      StreamState& st = h->streams[(size_t)key];
+      for (const auto& e : undo)
+        if (e.key == key) return st;
+      pasta_attn::Undo e{};
+      e.key = key; e.open = st.open; e.prefix_len = st.prefix_len; e.n_ranges = (int32_t)st.ranges.size();
+      if (e.n_ranges) e.last = st.ranges.back();
+      e.range_tokens = st.range_tokens; e.dev_ranges = st.dev_ranges; e.dev_cidx = st.dev_cidx; e.dirty = st.dirty;
+      undo.push_back(std::move(e));
+      return st;
     };
+    auto fail = [&](int code) { roll_back(); return code; };
     for (int i = 0; i < a->n_rows; ++i) {
       const int r = a->request_id[i], s = a->stream_id[i];
       const int par = a->parent_stream ? a->parent_stream[i] : -1;
-      if (r < 0 || r >= c.max_requests || s < 0 || s >= c.max_streams) return PASTA_E_INVAL;
-      if (par < -1 || par >= c.max_streams || par == s) return PASTA_E_INVAL;
+      if (r < 0 || r >= c.max_requests || s < 0 || s >= c.max_streams) return fail(PASTA_E_INVAL);
+      if (par < -1 || par >= c.max_streams || par == s) return fail(PASTA_E_INVAL);
       const int64_t slot = t2[r];
-      if (slot >= (c.page_tokens ? (int64_t)h->req_pages[r] << h->page_shift : h->req_capacity)) return PASTA_E_CAPACITY;
+      if (slot >= (c.page_tokens ? (int64_t)h->req_pages[r] << h->page_shift : h->req_capacity)) return fail(PASTA_E_CAPACITY);
       if (!commit) {  // replay: same slots as the layer-0 call, lists untouched
-        if (slot >= h->tail[r]) return PASTA_E_STATE;
+        if (slot >= h->tail[r]) return fail(PASTA_E_STATE);
         slots[i] = (int32_t)slot;
         dst_rows[i] = (int32_t)host_phys(h, r, slot);
         t2[r] = slot + 1;
         continue;
       }
-      StreamState& st = view(r, s);
-      if (par >= 0) {
-        if (st.open) return PASTA_E_INVAL;          // parent only on the row that opens the stream
-        const StreamState& ps = view(r, par);       // may rehash: re-fetch st below
-        if (!ps.open) return PASTA_E_INVAL;
-        StreamState& st2 = view(r, s);
-        st2.prefix_len = ps.prefix_len;             // ancestor rule: inherit what the parent sees now
-        st2.ranges = ps.ranges;
-        st2.open = true;
-      } else if (!st.open) {
-        st.open = true;                             // root: empty visible set
-        st.prefix_len = 0;
-        st.ranges.clear();
+      StreamState& st = touch(r, s);
+      if (par >= 0 || !st.open) {  // the row opens the stream: as a fork of `par`, or as a root (empty visible set)
+        if (par >= 0 && st.open) return fail(PASTA_E_INVAL);  // parent only on the row that opens the stream
+        const StreamState* ps = nullptr;
+        if (par >= 0) {
+          ps = &sstate(h, r, par);
+          if (!ps->open) return fail(PASTA_E_INVAL);
+        }
+        pasta_attn::Undo* ue = nullptr;
+        for (auto& e : undo)
+          if (e.key == (int64_t)r * c.max_streams + s) ue = &e;
+        if (!ue->replaced) { ue->replaced = true; ue->saved = std::move(st.ranges); st.ranges.clear(); }
+        if (ps) {  // ancestor rule: inherit what the parent sees now
+          st.prefix_len = ps->prefix_len;
+          st.ranges = ps->ranges;
+          st.range_tokens = ps->range_tokens;
+        } else {
+          st.prefix_len = 0;
+          st.ranges.clear();
+          st.range_tokens = 0;
+        }
+        st.open = true;
+        st.dirty = true;  // the device copy is rebuilt from the mirror when a decode step wants it
+        st.dev_ranges = st.dev_cidx = 0;
       }
-      StreamState& cur = view(r, s);
-      add_slot(cur, (int32_t)slot);
-      if ((int64_t)cur.ranges.size() > c.max_ranges) return PASTA_E_CAPACITY;
+      add_slot(st, (int32_t)slot);
+      if ((int64_t)st.ranges.size() > c.max_ranges) return fail(PASTA_E_CAPACITY);
       slots[i] = (int32_t)slot;
       dst_rows[i] = (int32_t)host_phys(h, r, slot);
       t2[r] = slot + 1;
     }
-  } catch (...) { return PASTA_E_NOMEM; }
+  } catch (...) { roll_back(); return PASTA_E_NOMEM; }
+
+  // ---- what the call changes in the device-resident lists.  A stream whose ranges only GREW needs
+  // nothing (its newest range rides with every decode call, and index entries that are not on the device
+  // mean "the newest range").  A stream that got NEW ranges has its arena and index entries brought up to
+  // date by this call's K1 launch when they are few and the launch exists; otherwise its copy is marked
+  // for a rebuild.
+  ListPatches patches;
+  bool need_k1 = false;  // patches exist: the copy cannot be left to a later decode launch
+  if (commit) {
+    const bool k1_possible = !reserve_only && a->n_rows <= kAppendInline;
+    for (auto& e : undo) {
+      StreamState& st = h->streams[(size_t)e.key];
+      const int32_t nb = e.n_ranges, na = (int32_t)st.ranges.size();
+      if (st.dirty) continue;
+      if (na == nb) {  // growth only
+        st.dev_ranges = std::min(st.dev_ranges, std::max(na - 1, 0));
+        continue;
+      }
+      const int64_t n_cidx = (st.range_tokens + kCidxTokens - 1) / kCidxTokens;
+      const int32_t k0 = std::min(st.dev_ranges, std::max(nb - 1, 0));  // first arena entry to (re)write
+      const int64_t want_r = na - k0, want_c = n_cidx - st.dev_cidx;
+      if (!k1_possible || na > st.seg_cap || n_cidx > st.cseg_cap || patches.n_r + want_r > kPatchMax ||
+          patches.n_c + want_c > kPatchMax) {
+        st.dirty = true;
+        continue;
+      }
+      int64_t cum = st.range_tokens;  // tokens before range k, walking down from the end
+      for (int32_t k = na - 1; k >= k0; --k) cum -= st.ranges[k].count;
+      int64_t tok = (int64_t)st.dev_cidx * kCidxTokens;  // next index entry's token (lies at or behind range k0's start)
+      for (int32_t k = k0; k < na; ++k) {
+        const Range& g = st.ranges[k];
+        patches.r_idx[patches.n_r] = st.seg_off + k;
+        patches.r_val[patches.n_r++] = DevRange{g.start, g.count, g.stride, (int32_t)cum};
+        for (; tok < cum + g.count && tok < st.range_tokens; tok += kCidxTokens) {
+          patches.c_idx[patches.n_c] = st.cseg_off + (int32_t)(tok / kCidxTokens);
+          patches.c_val[patches.n_c++] = k;
+        }
+        cum += g.count;
+      }
+      st.dev_ranges = na;
+      st.dev_cidx = (int32_t)n_cidx;
+      need_k1 = true;
+    }
+  }
 
   // ---- enqueue K1, or leave the copy to the next decode_step (PASTA_APPEND_DEFER)
   int rc = PASTA_OK;
+  auto fail_dev = [&](int code) { if (commit) roll_back(); return code; };
   // At most one deferred append is outstanding, and the slots it covers are the newest of their
   // requests: any later append -- also one that only reserves slots for the caller's own kernel --
   // first sends the deferred rows to the pool (a deferred append exists only on a ready device).
   rc = flush_pending(h);
-  if (rc != PASTA_OK) return rc;
+  if (rc != PASTA_OK) return fail_dev(rc);
   if (!reserve_only) {
     rc = ensure_device(h);
-    if (rc != PASTA_OK) return rc;
-    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline;
-    std::vector<int32_t> p0, s0;
+    if (rc != PASTA_OK) return fail_dev(rc);
+    bool defer = (a->flags & PASTA_APPEND_DEFER) && a->n_rows <= kAppendInline && !need_k1;
+    std::vector<int32_t>&p0 = h->pending.stage_p0, &s0 = h->pending.stage_s0;
     if (defer) {  // rows of one request must be consecutive in the call: slot t <-> row src0 + (t - pend0)
       p0.assign(c.max_requests, INT32_MAX);
       s0.assign(c.max_requests, 0);
-      std::vector<int32_t> last(c.max_requests, -2);
+      std::vector<int32_t>& last = h->pending.stage_last;
+      last.assign(c.max_requests, -2);
       for (int i = 0; i < a->n_rows && defer; ++i) {
         const int r = a->request_id[i];
         if (p0[r] == INT32_MAX) { p0[r] = slots[i]; s0[r] = i; }
@@ -596,8 +787,9 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
       pd.req_pend0.swap(p0);
       pd.req_src0.swap(s0);
     } else {
-      rc = launch_append(h, a->layer, a->n_rows, a->k_new, a->v_new, dst_rows.data(), rope ? a->position : nullptr);
-      if (rc != PASTA_OK) return rc;
+      rc = launch_append(h, a->layer, a->n_rows, a->k_new, a->v_new, dst_rows.data(), rope ? a->position : nullptr,
+                         need_k1 ? &patches : nullptr);
+      if (rc != PASTA_OK) return fail_dev(rc);
     }
   }
 
@@ -606,7 +798,7 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
   if (commit) {
     h->tail_before = h->tail;
     h->tail.swap(t2);
-    for (auto& kv : touched) h->streams[(size_t)kv.first] = std::move(kv.second);
+    undo.clear();
   }
   return PASTA_OK;
 }
@@ -664,7 +856,11 @@ extern "C" int32_t pasta_attn_sync(pasta_attn* h, const pasta_sync_args* a) {
           if (peek(q) == lo) advance(q);
         if ((int64_t)merged.ranges.size() > c.max_ranges) return PASTA_E_CAPACITY;
       }
-      dst = std::move(merged);
+      merged.range_tokens = 0;
+      for (const Range& g : merged.ranges) merged.range_tokens += g.count;
+      merged.seg_off = dst.seg_off; merged.seg_cap = dst.seg_cap;      // the device copy keeps its segments
+      merged.cseg_off = dst.cseg_off; merged.cseg_cap = dst.cseg_cap;  // and is rebuilt from the joined list
+      dst = std::move(merged);                                         // when a decode step next wants it
     }
     if (retire)
       for (int i = 0; i < a->n_join; ++i) {
@@ -672,6 +868,9 @@ extern "C" int32_t pasta_attn_sync(pasta_attn* h, const pasta_sync_args* a) {
         js.open = false;
         js.prefix_len = 0;
         js.ranges.clear();
+        js.range_tokens = 0;
+        js.dirty = true;
+        js.dev_ranges = js.dev_cidx = 0;
       }
   } catch (const std::bad_alloc&) {
     return PASTA_E_NOMEM;
@@ -915,6 +1114,39 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
       if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
       if (h->tune_priv_chunk >= 32) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / 32 * 32, kGatherMax);  // whole 32-token blocks
     }
+    // ---- where the lists come from.  Maintained lists have a copy on the device (range arena + range
+    // index, kept up to date by the appends): a step may then send a fixed-size record per stream and let
+    // the kernels derive the private work items, instead of sending every range and item.  A plan small
+    // enough to ride in the kernel arguments is sent whole all the same -- its items then cost the
+    // kernels no dependent loads -- unless the caller asks for the device lists.
+    bool dev_lists = false;
+    if (!explicit_mode && !a->causal_skip && !dense) {
+      int64_t words = (int64_t)n * (sizeof(DevStream) / 4 + 1) + (int64_t)reqs.size() * (sizeof(DevReq) / 4) + 8;
+      for (int i = 0; i < n; ++i) {
+        const StreamState& ss = sstate(h, a->request_id[i], a->stream_id[i]);
+        const int64_t priv = (int64_t)lv[i].prefix_len - reqs[stream_req_idx[i]].pc + ss.range_tokens;
+        words += ((int64_t)lv[i].n_ranges + 1) * 4 + (priv + priv_chunk - 1) / priv_chunk * (sizeof(DevItem) / 4);
+      }
+      dev_lists = (a->flags & PASTA_DECODE_DEVICE_LISTS) || words > kInlineMetaWords;
+    } else if (a->flags & PASTA_DECODE_DEVICE_LISTS) {
+      return PASTA_E_INVAL;
+    }
+    if (dev_lists && !plan_only) {  // the copies this step reads must be current (all but each list's newest range)
+      if (h->tables_reset) {        // the segments ran out earlier: start over
+        h->tables_reset = false;
+        h->arena_top = h->cidx_top = 0;
+        for (StreamState& ss : h->streams) { ss.seg_off = ss.cseg_off = -1; ss.seg_cap = ss.cseg_cap = 0; ss.dirty = true; }
+      }
+      for (int i = 0; i < n && dev_lists; ++i) {
+        StreamState& ss = sstate(h, a->request_id[i], a->stream_id[i]);
+        if (!ss.dirty && ss.dev_ranges >= (int32_t)ss.ranges.size() - 1) continue;
+        if (no_alloc) { dev_lists = false; break; }  // (a rebuild stages through buffers that may have to grow)
+        const int rb = rebuild_tables(h, ss);
+        if (rb == kNoRoom) dev_lists = false;
+        else if (rb != PASTA_OK) return rb;
+      }
+      if (!dev_lists && (a->flags & PASTA_DECODE_DEVICE_LISTS)) return PASTA_E_CAPACITY;
+    }
     // private items
     std::vector<DevStream>& streams = pb.streams;
     std::vector<DevRange>& ranges = pb.ranges;
@@ -922,9 +1154,11 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     streams.assign(n, DevStream{});
     ranges.clear();
     items.clear();
-    if (!room(ranges, (size_t)total_ranges + n)) return PASTA_E_CAPACITY;
-    ranges.reserve((size_t)total_ranges + n);
-    int64_t gather_total = 0;
+    if (!dev_lists) {
+      if (!room(ranges, (size_t)total_ranges + n)) return PASTA_E_CAPACITY;
+      ranges.reserve((size_t)total_ranges + n);
+    }
+    int64_t gather_total = 0, n_items_total = 0;
     for (int i = 0; i < n; ++i) {
       DevStream& ds = streams[i];
       const DevReq& q = reqs[stream_req_idx[i]];
@@ -934,6 +1168,28 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
       ds.pos = rope_q ? a->position[i] : 0;
       ds.mask_base = mask_base[i];
       ds.pc = q.pc;
+      if (dev_lists) {
+        const StreamState& ss = sstate(h, a->request_id[i], a->stream_id[i]);
+        const int64_t extra = (int64_t)lv[i].prefix_len - q.pc, T = ss.range_tokens;
+        if (gather_total + q.pc + extra + T > INT32_MAX) return PASTA_E_CAPACITY;
+        ds.extra = (int32_t)extra;
+        ds.n_ranges = (int32_t)ss.ranges.size();
+        ds.seg_off = ss.seg_off;
+        ds.range_tokens = (int32_t)T;
+        ds.cseg_off = ss.cseg_off;
+        ds.n_cidx = ss.dev_cidx;
+        if (ds.n_ranges) {
+          const Range& g = ss.ranges.back();
+          ds.last[0] = g.start; ds.last[1] = g.count; ds.last[2] = g.stride; ds.last[3] = (int32_t)(T - g.count);
+        }
+        ds.item_begin = (int32_t)n_items_total;
+        n_items_total += (extra + priv_chunk - 1) / priv_chunk + (T + priv_chunk - 1) / priv_chunk;
+        ds.item_end = (int32_t)n_items_total;
+        ds.gather_base = (int32_t)gather_total;
+        if (a->dbg_gather_offsets) a->dbg_gather_offsets[i] = gather_total;
+        gather_total += (int64_t)q.pc + extra + T;
+        continue;
+      }
       ds.range_begin = (int32_t)ranges.size();
       int32_t cum = 0;
       if (lv[i].prefix_len > q.pc) {
@@ -965,6 +1221,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
         items.push_back(it);
       }
       ds.item_end = (int32_t)items.size();
+      n_items_total = (int64_t)items.size();
       if (gather_total + q.pc + cum > INT32_MAX) return PASTA_E_CAPACITY;
       ds.gather_base = (int32_t)gather_total;
       if (a->dbg_gather_offsets) a->dbg_gather_offsets[i] = gather_total;
@@ -973,7 +1230,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     if (a->dbg_gather_offsets) a->dbg_gather_offsets[n] = gather_total;
 
     // split-K chunks of the common prefixes; grow the chunk until the partial rows fit
-    const int64_t priv_rows = (int64_t)items.size() * c.n_q_heads;
+    const int64_t priv_rows = n_items_total * c.n_q_heads;
     int64_t n_prefix_wgs = 0, prefix_rows = 0;
     if (pc_total > 0) {
       for (;; chunk_tokens += kTile) {
@@ -1030,7 +1287,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
       for (auto& q : reqs) tiles += (int64_t)(q.pc + kTile - 1) / kTile * Hkv;
       a->dbg_plan[0] = tiles;
       a->dbg_plan[1] = n_prefix_wgs;
-      a->dbg_plan[2] = (int64_t)items.size();
+      a->dbg_plan[2] = n_items_total;
       a->dbg_plan[3] = prefix_rows + priv_rows;
       a->dbg_plan[4] = pc_total ? chunk_tokens : 0;
       a->dbg_plan[5] = pc_total;
@@ -1089,12 +1346,28 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
       // attention launch costs tens of microseconds on the stream (config 4: 97 -> 61 us per
       // step).  The slot is reused only after the launches that read it have completed.
       if (blob.size() * 4 > h->meta_bytes) return PASTA_E_CAPACITY;
-      meta_slot = h->ring_next;
-      h->ring_next = (meta_slot + 1) % kRing;
-      if (h->ring_used[meta_slot] && hipEventSynchronize(h->ring_ev[meta_slot]) != hipSuccess) return PASTA_E_DEVICE;
-      char* host = h->pinned + (size_t)meta_slot * h->meta_bytes;
-      std::memcpy(host, blob.data(), blob.size() * 4);
-      p.meta = (const int32_t*)host;
+      if (blob.size() <= (size_t)kRelayMaxWords) {
+        // ... unless it is only a few KB (device-resident lists: one record per stream): then it travels to a
+        // device staging slot inside the kernel arguments of one or two tiny launches
+        const int sl = h->relay_next;
+        h->relay_next = (sl + 1) % kRing;
+        int32_t* dev = (int32_t*)((char*)c.workspace + h->off_meta + (size_t)sl * h->meta_bytes);
+        for (size_t lo = 0; lo < blob.size(); lo += kRelayWords) {
+          RelayParams rp;
+          rp.dst = dev + lo;
+          rp.n_words = (int)std::min<size_t>(kRelayWords, blob.size() - lo);
+          std::memcpy(rp.words, blob.data() + lo, (size_t)rp.n_words * 4);
+          k_meta_relay<<<dim3(1), 256, 0, st>>>(rp);
+        }
+        p.meta = dev;
+      } else {
+        meta_slot = h->ring_next;
+        h->ring_next = (meta_slot + 1) % kRing;
+        if (h->ring_used[meta_slot] && hipEventSynchronize(h->ring_ev[meta_slot]) != hipSuccess) return PASTA_E_DEVICE;
+        char* host = h->pinned + (size_t)meta_slot * h->meta_bytes;
+        std::memcpy(host, blob.data(), blob.size() * 4);
+        p.meta = (const int32_t*)host;
+      }
     }
     p.k = (const char*)c.k_pool + (size_t)a->layer * h->layer_elems * h->elem;
     p.v = (const char*)c.v_pool + (size_t)a->layer * h->layer_elems * h->elem;
@@ -1108,8 +1381,12 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     p.lay = h->lay;
     p.n_streams = n;
     p.n_reqs = (int)reqs.size();
-    p.n_items = (int)items.size();
-    p.n_mfma_items = mfma ? (int)items.size() : 0;
+    p.n_items = (int)n_items_total;
+    p.n_mfma_items = mfma ? (int)n_items_total : 0;
+    p.arena = (const DevRange*)((const char*)c.workspace + h->off_arena);
+    p.cidx = (const int32_t*)((const char*)c.workspace + h->off_cidx);
+    p.dev_tables = dev_lists ? 1 : 0;
+    p.priv_chunk = (int)priv_chunk;
     p.n_prefix_wgs = (int)n_prefix_wgs;
     p.priv_part_base = (int)prefix_rows;
     p.Hq = c.n_q_heads;
@@ -1150,7 +1427,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     if (merge_only) {
       // (kernel-isolated test of the merge: the partial buffers are taken as they are)
     } else if (mfma) {
-      const unsigned grid = (unsigned)(items.size() * Hkv + n_prefix_wgs);
+      const unsigned grid = (unsigned)(n_items_total * Hkv + n_prefix_wgs);
       auto launch = [&](auto kernel) {
         if (ev_in_dispatch) hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kAttnThreads), 0, st, ev0, ev1, 0, p);
         else kernel<<<dim3(grid), kAttnThreads, 0, st>>>(p);
@@ -1174,8 +1451,8 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
         }
       }
       if (take_pending) h->pending.active = false;
-    } else if (!items.empty()) {
-      const unsigned waves = (unsigned)items.size() * Hkv;
+    } else if (n_items_total > 0) {
+      const unsigned waves = (unsigned)n_items_total * Hkv;
       rc = launch_private(h, dim3((waves + 3) / 4), st, p);
       if (rc != PASTA_OK) return rc;
     }

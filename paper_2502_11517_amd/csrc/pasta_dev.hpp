@@ -57,10 +57,21 @@ struct DevStream {      // one per decoding stream, call order
   int32_t m_pre0;       // part_base + local * G: first shared-prefix partial row of the stream (kv head 0, chunk 0, head 0)
   int32_t m_n_pre;      // split-K chunks of the request's common prefix
   int32_t m_R;          // stacked rows of the request: shared-prefix part i of kv head g is row m_pre0 + (g * m_n_pre + i) * m_R + gi
-};                      // 14 words
-struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it
-  int32_t start, count, stride, cum;
+  // ---- device-resident lists (DecodeParams::dev_tables): the stream's ranges are not in the blob but in the
+  // arena that the appends keep up to date, and its private work items are derived by the kernels
+  int32_t extra;        // prefix_len - pc: visible head beyond the common prefix (private, contiguous slots pc ..)
+  int32_t n_ranges;     // ranges of the list: k < n_ranges - 1 at arena[seg_off + k], the newest one in `last`
+  int32_t seg_off;
+  int32_t range_tokens; // tokens in the ranges
+  int32_t cseg_off;     // cidx[cseg_off + j] = index of the range that holds range token 32 j ...
+  int32_t n_cidx;       // ... for j < n_cidx; later ones lie in the newest range
+  int32_t last[4];      // the newest range (start, count, stride, cum): it grows with every append, so it rides
+                        // with the call instead of being written to the arena each time
+};                      // 24 words
+struct DevRange {       // slots start + j*stride, j < count; cum = private tokens before it (device-resident
+  int32_t start, count, stride, cum;  // lists: tokens of the stream's RANGES before it)
 };
+constexpr int kCidxTokens = 32;  // granularity of the range index over a stream's range tokens
 struct DevItem {        // a chunk of one stream's private token list
   int32_t stream, tok_begin, tok_count;
   int32_t range_first;  // the range that holds token tok_begin
@@ -117,6 +128,10 @@ struct DecodeParams {
   int32_t s_items[32];  // single_req with <= 16 streams: stream i's private items are
                         //   [s_items[2i], s_items[2i] + s_items[2i+1]) -- spares the merge a table look-up
   const uint8_t* dense_mask;  // comparison mode: 0/1 per (stream, slot); null otherwise
+  const DevRange* arena;      // device-resident lists: range arena and range index (see DevStream)
+  const int32_t* cidx;
+  int dev_tables;             // 1: the blob holds no ranges and no items
+  int priv_chunk;             // tokens per private work item
   const double* rope_tab;  // theta^(-2f/D) / (2 pi), f < D/2 (device), for k_rope_prep
   int single_req;       // 1: the call holds one request; its DevReq is req0 and stream i of
   DevReq req0;          //    the call is stacked-row block i (no table look-ups on the way
@@ -168,6 +183,65 @@ __device__ __forceinline__ const int32_t* pend_pos_of(const DecodeParams& p) {
   typedef const char __attribute__((address_space(4))) * kernarg_ptr;
   kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   return (const int32_t*)(ka + __builtin_offsetof(DecodeParams, pend_pos));
+}
+
+// ---- device-resident lists: the pieces the kernels share
+__device__ __forceinline__ DevRange dev_range_at(const DecodeParams& p, const DevStream& st, int k) {
+  if (k >= st.n_ranges - 1) return DevRange{st.last[0], st.last[1], st.last[2], st.last[3]};
+  return p.arena[st.seg_off + k];
+}
+__device__ __forceinline__ int dev_cidx_at(const DecodeParams& p, const DevStream& st, int j) {
+  return j < st.n_cidx ? p.cidx[st.cseg_off + j] : st.n_ranges - 1;
+}
+// The call's stream whose private items include work item `item` (item_begin is ascending over the
+// streams of a call; streams without items have item_begin == item_end).  Every lane searches.
+__device__ __forceinline__ int dev_stream_of_item(const DecodeParams& p, const int32_t* meta, int item) {
+  const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
+  int lo = 0, hi = p.n_streams - 1;  // last stream with item_begin <= item
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (streams[mid].item_begin <= item) lo = mid; else hi = mid - 1;
+  }
+  return lo;  // (a stream without items shares its item_begin with the NEXT stream, which the search prefers)
+}
+// Work item `item` of stream i, derived: first the pieces of the visible head beyond the common prefix
+// (contiguous slots), then the pieces of the range list, both in steps of priv_chunk tokens.  For a piece
+// of the range list only tok_begin / tok_count / gather_pos are filled in here (tok_begin in range tokens):
+// its ranges are looked up by the caller (dev_item_candidates).
+__device__ __forceinline__ DevItem dev_item(const DecodeParams& p, const DevStream& st, int i, int item, bool& in_ranges) {
+  const int C = p.priv_chunk;
+  const int ci = item - st.item_begin;
+  const int n_extra = (st.extra + C - 1) / C;
+  DevItem it;
+  it.stream = i;
+  it.range_first = 0;
+  it.n_ranges = 1;
+  in_ranges = ci >= n_extra;
+  if (!in_ranges) {
+    it.tok_begin = ci * C;
+    it.tok_count = min(C, st.extra - ci * C);
+    it.gather_pos = st.gather_base + st.pc + ci * C;
+    it.slot0 = st.pc + ci * C;
+    it.stride = 1;
+  } else {
+    const int t0 = (ci - n_extra) * C;
+    it.tok_begin = t0;
+    it.tok_count = min(C, st.range_tokens - t0);
+    it.gather_pos = st.gather_base + st.pc + st.extra + t0;
+    it.slot0 = 0;
+    it.stride = 0;
+  }
+  return it;
+}
+// The ranges that can hold tokens [t0, t0 + n) of the stream's range list: all of them when they fit
+// `cap` entries, else the stretch that the range index points at.  Returns the first candidate's index.
+__device__ __forceinline__ int dev_item_candidates(const DecodeParams& p, const DevStream& st, int t0, int n, int cap, int& count) {
+  if (st.n_ranges <= cap) { count = st.n_ranges; return 0; }
+  const int first = dev_cidx_at(p, st, t0 / kCidxTokens);
+  const int j_hi = (t0 + n - 1) / kCidxTokens + 1;
+  const int hi = j_hi * kCidxTokens < st.range_tokens ? dev_cidx_at(p, st, j_hi) : st.n_ranges - 1;
+  count = min(hi - first + 1, cap);  // (n tokens overlap at most n ranges; cap >= n)
+  return first;
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -116,9 +116,13 @@ def _merge_case(n_streams, Hq, Hkv, prefix, lengths, seed, poison):
         m[far] -= 200.0                                       # weights that underflow to nothing
     # parts of each output row, in the documented layout
     pl, offs, st, ct, sd = w.lists(0)
+    # (a plan sent whole cuts a stream's list beyond the common prefix into 128-token pieces; a step that reads the
+    # device-resident lists cuts the visible head beyond the common prefix and the range list separately)
+    whole = [-(-(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum())) // 128) for i in range(n)]
+    split = [-(-(int(pl[i]) - pc) // 128) + -(-int(ct[offs[i]:offs[i + 1]].sum()) // 128) for i in range(n)]
+    counts = whole if sum(whole) == n_items else split
     items_of, j = [], 0
-    for i in range(n):
-        cnt = -(-(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum())) // 128)
+    for cnt in counts:
         items_of.append(list(range(j, j + cnt)))
         j += cnt
     assert j == n_items and priv0 + n_items * Hq == rows
