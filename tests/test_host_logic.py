@@ -441,3 +441,30 @@ def test_full_pool_and_maximum_number_of_query_rows():
               lists=(np.full(9, 10), np.zeros(10, np.int32), [], [], []))
     assert e.value.code == B.E_INVAL
     h.destroy()
+
+
+def test_device_list_plans_have_a_fixed_size_and_failed_appends_leave_the_lists_alone():
+    """PLAN_ONLY with PASTA_DECODE_DEVICE_LISTS: the metadata a step sends is one record per stream,
+    whatever the lists hold; without the flag a plan that would not fit the kernel arguments switches
+    by itself.  An append that fails half way (capacity) restores lists, tails and token counts."""
+    h = _handle(pool_tokens=4096, max_streams=4, max_ranges=4096)
+    _reserve(h, [0] * 100, [0] * 100)
+    _reserve(h, [0, 0], [1, 2], par=[0, 0])
+    sizes = []
+    for rounds in (10, 600):
+        for _ in range(rounds):
+            _reserve(h, [0, 0, 0], [1, 2, 1])        # 1, 2, 1 | 1, 2, 1: ranges of one and two slots
+        _, plan_dev = _plan(h, [0, 0], [1, 2], flags=B.DECODE_DEVICE_LISTS)
+        _, plan = _plan(h, [0, 0], [1, 2])
+        sizes.append((int(plan_dev[6]), int(plan[6]), int(plan_dev[2]), int(plan[2])))
+    assert sizes[0][0] == sizes[1][0] and sizes[0][1] > sizes[0][0]
+    assert sizes[1][1] == sizes[1][0]                # too large for the kernel arguments: switched by itself
+    before = [h.stream_list(0, s) for s in (1, 2)]
+    with pytest.raises(B.PastaError) as e:           # the pool has 4096 slots: this call runs out of them
+        _reserve(h, [0] * 3000, [1, 2] * 1500)
+    assert e.value.code == B.E_CAPACITY
+    after = [h.stream_list(0, s) for s in (1, 2)]
+    for b, a_ in zip(before, after):
+        assert b[0] == a_[0] and all(np.array_equal(x, y) for x, y in zip(b[1:], a_[1:]))
+    assert _plan(h, [0, 0], [1, 2], flags=B.DECODE_DEVICE_LISTS)[1][2] == sizes[1][2]   # same item count: token counts restored
+    h.destroy()
