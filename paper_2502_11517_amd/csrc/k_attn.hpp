@@ -71,7 +71,9 @@ struct AttnLds {
 
 struct BlockRegs { u32x4 k[8], v[8]; };  // one lane's share of a 32-token block
 
-template <bool PAGED, bool GATHER, bool DENSE, bool LONG, bool PROBE>
+// (FORM only keeps the instantiations of different kernels apart: the host pass of the compiler cannot
+// check this body -- it has no device builtins -- and refuses a specialization it has already tried)
+template <bool PAGED, bool GATHER, bool DENSE, bool LONG, bool PROBE, int FORM = 0>
 __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi) {
   constexpr int D = 128;
   const int tid = threadIdx.x;
@@ -779,16 +781,21 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   PASTA_CLK(7);
 }
 
+template <bool PAGED, bool PROBE>
+__device__ __forceinline__ void attn_item_wide(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi);
+
 // One launch for all partials of a decode step; the shared-prefix items' work-groups come
 // first, the private (gather) items' after them.
 // DENSE = the variant that also carries the dense-mask comparison mode (p.dense_mask); the plain
 // variant has none of that code.  LONG = the variant for launches with long items: its
 // steady-state loop addresses plain blocks through buffer loads.  PROBE = the read-only form of the
 // same launch (every request of the real one, no arithmetic, no output): what a plain read of these
-// bytes costs with this split of the work.
-template <bool PAGED, bool DENSE, bool LONG = false, bool PROBE = false>
+// bytes costs with this split of the work.  WIDE = every request with a shared prefix has more than
+// 32 stacked rows: the shared-prefix work-groups take four row groups each (attn_item_wide).
+template <bool PAGED, bool DENSE, bool LONG = false, bool PROBE = false, bool WIDE = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   static_assert(!LONG || !DENSE, "the long-item variant exists for the list mode");
+  static_assert(!WIDE || (!DENSE && !LONG), "the wide form replaces the shared-prefix items of the list mode");
   __shared__ AttnLds lds;
   const int32_t* meta = meta_of(p);
   // The deferred append's copy into the pool (K1's job).  No work-group of this launch reads those
@@ -829,9 +836,294 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
   // (a raised wave priority for the shared-prefix items, so that the longer items issue their loads
   // first where a SIMD holds a wave of each kind, paid while the private items' compute was heavier;
   // with the present kernel it costs 0.25 us per launch and is gone)
-  if ((int)blockIdx.x < n_prefix_wgs) attn_item<PAGED, false, DENSE, LONG, PROBE>(p, lds, meta, blockIdx.x);
-  else attn_item<PAGED, true, DENSE, LONG, PROBE>(p, lds, meta, blockIdx.x - n_prefix_wgs);
+  if ((int)blockIdx.x < n_prefix_wgs) {
+    if constexpr (WIDE) attn_item_wide<PAGED, PROBE>(p, lds, meta, blockIdx.x);
+    else attn_item<PAGED, false, DENSE, LONG, PROBE>(p, lds, meta, blockIdx.x);
+  } else attn_item<PAGED, true, DENSE, LONG, PROBE, WIDE ? 1 : 0>(p, lds, meta, blockIdx.x - n_prefix_wgs);
   if (pend_u >= 0) pend_store(pend_u, pend_val);
+}
+
+// K2 for a request with MORE than 32 stacked rows (many streams, or a wide GQA group): the rows are
+// served in groups of 32, and here the four waves of a work-group take one row group EACH over the
+// same tokens.  Work item = (request, kv head, split-K chunk, four row groups).  A round is four
+// 32-token blocks: wave w brings block 4 r + w into tile w (through its registers, requested one
+// round ahead), a barrier publishes the four tiles, every wave computes all four blocks for its own
+// 32 rows, a second barrier frees the tiles.  So the chunk crosses the memory system once per FOUR
+// row groups (the row-group form of attn_item reads it once per group -- from L2, but the L2-to-CU
+// traffic is what that form is bound by), and there is nothing to combine at the end: each wave
+// owns its rows' (m, l, O) for the whole chunk.  Q stays in registers (the B operands of S^T = K Q^T,
+// fetched once per item).
+template <bool PAGED, bool PROBE>
+__device__ __forceinline__ void attn_item_wide(const DecodeParams& p, AttnLds& lds, const int32_t* meta, int wi) {
+  constexpr int D = 128;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int G = p.Hq / p.Hkv;
+  PASTA_CLK(0);
+
+  // ---- decode the work item
+  DevReq rq;
+  const int32_t* req_streams = nullptr;
+  if (p.single_req) {
+    rq.req = p.req0.req; rq.pc = p.req0.pc; rq.n_streams = p.req0.n_streams; rq.stream0 = 0;
+    rq.wg_begin = p.req0.wg_begin; rq.n_chunks = p.req0.n_chunks;
+    rq.chunk_tokens = p.req0.chunk_tokens; rq.part_base = p.req0.part_base;
+    rq.pend0 = p.req0.pend0; rq.pend_src0 = p.req0.pend_src0;
+  } else {
+    const DevReq* reqs = reinterpret_cast<const DevReq*>(meta + p.off_reqs);
+    int qi = 0;
+    for (; qi < p.n_reqs - 1; ++qi) {
+      const int b = reqs[qi].wg_begin;
+      if (wi >= b && wi < b + reqs[qi].n_chunks * p.Hkv * ((reqs[qi].n_streams * G + 127) >> 7)) break;
+    }
+    rq = reqs[qi];
+    req_streams = meta + p.off_req_streams + rq.stream0;
+  }
+  const int R_all = rq.n_streams * G;
+  const int n_quads = (R_all + 127) >> 7;
+  const int wl = wi - rq.wg_begin;
+  const int tq = wl / p.Hkv;
+  const int c = __builtin_amdgcn_readfirstlane(tq / n_quads);
+  const int quad = tq % n_quads;
+  const int g = __builtin_amdgcn_readfirstlane(wl % p.Hkv);
+  const int req = __builtin_amdgcn_readfirstlane(rq.req);
+  const int row0 = __builtin_amdgcn_readfirstlane((quad * 4 + w) * 32);   // this WAVE's first stacked row
+  const int R = __builtin_amdgcn_readfirstlane(max(0, min(32, R_all - row0)));  // 0: a wave that only carries tiles
+  const int slot0 = __builtin_amdgcn_readfirstlane(c * rq.chunk_tokens);  // a multiple of 64
+  const int n_tok = __builtin_amdgcn_readfirstlane(min(rq.chunk_tokens, rq.pc - slot0));
+  const int n_blocks = (n_tok + kBlock - 1) / kBlock;
+  const long long part_row0 = rq.part_base + (long long)(g * rq.n_chunks + c) * R_all + row0;
+  const int pend0 = __builtin_amdgcn_readfirstlane(rq.pend0);  // slots from here on are rows of a deferred append
+  const int pend_src0 = __builtin_amdgcn_readfirstlane(rq.pend_src0);
+
+  const char* kb = reinterpret_cast<const char*>(p.k);
+  const char* vb = reinterpret_cast<const char*>(p.v);
+  const char* kpend = reinterpret_cast<const char*>(p.k_pend);
+  const char* vpend = reinterpret_cast<const char*>(p.v_pend);
+  const int piece = lane & 15, rbase = lane >> 4;
+
+  // ---- Q: lane (row l32, half hh) holds pieces 2 kk + hh of its row, the B operand of step kk
+  u32x4 qreg[8];
+  {
+    const int ra = row0 + l32;
+    const bool live = l32 < R;
+    const int s = live ? (req_streams ? req_streams[ra / G] : ra / G) : 0;
+    const char* qrow = reinterpret_cast<const char*>(p.q) + (long long)(s * p.Hq + (g * G + (live ? ra % G : 0))) * (D * 2);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      qreg[kk] = *reinterpret_cast<const u32x4*>(qrow + (2 * kk + hh) * 16);
+      if (!live) qreg[kk] = u32x4{0u, 0u, 0u, 0u};  // rows past R are zero
+    }
+  }
+  if (p.dbg_rows && g == 0 && quad == 0) {
+    const DevStream* streams = reinterpret_cast<const DevStream*>(meta + p.off_streams);
+    for (int j = tid; j < n_tok; j += kAttnThreads) {
+      const int phys = phys_row(p.lay, p.page_table, req, slot0 + j);
+      for (int k = 0; k < rq.n_streams; ++k)
+        p.dbg_rows[streams[req_streams ? req_streams[k] : k].gather_base + slot0 + j] = phys;
+    }
+  }
+
+  // ---- block loads: lane -> piece (lane & 15) of rows (lane >> 4) + 4 i.  A full block inside the
+  // chunk is two runs of 16 consecutive slots, each inside one page (pages of 16 tokens or more):
+  // wave-uniform base per run (page-table entries through scalar loads), lane part in the offset
+  // register, row step in the scalar offset.  The chunk's ragged last block takes one address per row.
+  const uint32_t row_bytes = (uint32_t)p.lay.slot_stride * 2u;
+  const uint32_t lane_n = (uint32_t)rbase * row_bytes + (uint32_t)(piece * 16);
+  const bool runs_ok = !PAGED || p.lay.page_shift >= 4;
+  auto load_block = [&](BlockRegs& br, int b) {
+    if (runs_ok && b * kBlock + kBlock <= n_tok && slot0 + b * kBlock + kBlock <= pend0) {
+      int pp[2] = {0, 0};
+      if constexpr (PAGED) {
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+          pp[hb] = scalar_load_i32(p.page_table, req * p.lay.pages_per_request + ((slot0 + b * kBlock + 16 * hb) >> p.lay.page_shift));
+      }
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) {
+        const int t = slot0 + b * kBlock + 16 * hb;
+        const int phys = PAGED ? ((pp[hb] << p.lay.page_shift) | (t & p.lay.page_mask)) : req * p.lay.pool_tokens + t;
+        const long long off = elem_off(p.lay, phys, g) * 2;
+        const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kb + off), 0, 0x7fffffff, kRawBuffer);
+        const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vb + off), 0, 0x7fffffff, kRawBuffer);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          br.k[4 * hb + i] = __builtin_amdgcn_raw_buffer_load_b128(kr, lane_n, (uint32_t)(4 * i) * row_bytes, 0);
+          br.v[4 * hb + i] = __builtin_amdgcn_raw_buffer_load_b128(vr, lane_n, (uint32_t)(4 * i) * row_bytes, 0);
+        }
+      }
+      return;
+    }
+    long long off[8];
+    bool pnd[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int t = slot0 + min(b * kBlock + rbase + 4 * i, n_tok - 1);  // rows past the end repeat the last one
+      pnd[i] = t >= pend0;  // (a single stream that has not forked: its newest row is part of its prefix)
+      const long long off_pool = elem_off(p.lay, pnd[i] ? 0 : phys_row(p.lay, p.page_table, req, t), g) * 2;
+      const long long off_pend = ((long long)(pend_src0 + (t - pend0)) * p.Hkv + g) * D * 2;
+      off[i] = (pnd[i] ? off_pend : off_pool) + piece * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      br.k[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? kpend : kb) + off[i]);
+      br.v[i] = *reinterpret_cast<const u32x4*>((pnd[i] ? vpend : vb) + off[i]);
+    }
+  };
+  BlockRegs br;
+  const int n_rounds = (n_blocks + 3) >> 2;
+  if (w < n_blocks) load_block(br, w);
+
+  if constexpr (PROBE) {  // read-only form: the same requests, nothing computed
+    u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+    for (int b = w; b < n_blocks; b += 4) {
+      if (b != w) load_block(br, b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc = acc ^ br.k[i] ^ br.v[i] ^ qreg[i];
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u && n_tok < 0) p.part_ml[part_row0] = make_float2(0.f, 0.f);
+    return;
+  }
+
+  f32x16 O[4];  // O^T M-tile mt: d = 32 mt + 8 (i / 4) + 4 hh + i % 4, row l32
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) O[mt][i] = 0.f;
+
+  u32x4* ktw = lds.tile[w].kt;
+  u32x4* vtw = lds.tile[w].vt;
+  // V^T reads (see attn_item): byte offset inside a tile's V half, per M-tile
+  int vrd[4];
+  {
+    const int bl = lane & 15, cblk = (lane >> 4) & 1, r2 = bl >> 2;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+      vrd[mt] = (4 * hh + r2) * 256 + (mt ^ r2) * 64 + (2 * cblk + ((bl >> 1) & 1)) * 16 + (bl & 1) * 8;
+  }
+  // One block after the other, online softmax in log2 units.  (Two blocks per softmax step, their S^T chains
+  // interleaved, took the same time: the launch is bound by what it has in flight, not by this chain.)
+  auto block_compute = [&](int t, int b) {  // block b, in tile t, for this wave's rows
+    const u32x4* kt = lds.tile[t].kt;
+    const char* vt = reinterpret_cast<const char*>(lds.tile[t].vt);
+    f32x16 S;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) S[i] = 0.f;
+    {
+      u32x4 a[2];
+      a[0] = kt[l32 * 16 + (hh ^ (l32 & 15))];
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        if (kk + 1 < 8) a[(kk + 1) & 1] = kt[l32 * 16 + ((2 * kk + 2 + hh) ^ (l32 & 15))];
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a[kk & 1]),
+                                                    *reinterpret_cast<const bf16x8*>(&qreg[kk]), S, 0, 0, 0);
+      }
+    }
+    if (b * kBlock + kBlock > n_tok) {  // the chunk's ragged last block: tokens past its end are hidden
+      asm volatile("" ::: "memory");
+      const int left = n_tok - (b * kBlock + 4 * hh);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[i] = (8 * (i >> 2) + (i & 3)) < left ? S[i] : -INFINITY;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * p.scale_log2e;  // finite: every block holds at least one token
+    const float mn = fmaxf(m_run, mx);
+    const float corr = fast_exp2(m_run - mn);
+    m_run = mn;
+    float ps = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      S[i] = fast_exp2(fmaf(S[i], p.scale_log2e, -mn));
+      ps += S[i];
+    }
+    l_run = l_run * corr + ps;
+    bf16x8 P[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 pk;
+      pk[0] = pack_bf16x2(S[8 * ks + 0], S[8 * ks + 1]);
+      pk[1] = pack_bf16x2(S[8 * ks + 2], S[8 * ks + 3]);
+      pk[2] = pack_bf16x2(S[8 * ks + 4], S[8 * ks + 5]);
+      pk[3] = pack_bf16x2(S[8 * ks + 6], S[8 * ks + 7]);
+      P[ks] = *reinterpret_cast<const bf16x8*>(&pk);
+    }
+    if (!__all(corr == 1.f)) {  // the running max moves rarely once a few blocks are in
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[mt][i] *= corr;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        s16x4 part[2];
+#pragma unroll
+        for (int e4 = 0; e4 < 2; ++e4)
+          part[e4] = lds_read_tr16(reinterpret_cast<const uint16_t*>(vt + vrd[mt] + (16 * ks + 8 * e4) * 256));
+        u32x4 a4;
+        a4[0] = reinterpret_cast<const uint32_t*>(&part[0])[0];
+        a4[1] = reinterpret_cast<const uint32_t*>(&part[0])[1];
+        a4[2] = reinterpret_cast<const uint32_t*>(&part[1])[0];
+        a4[3] = reinterpret_cast<const uint32_t*>(&part[1])[1];
+        O[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a4), P[ks], O[mt], 0, 0, 0);
+      }
+    }
+  };
+
+  for (int r = 0; r < n_rounds; ++r) {
+    if (4 * r + w < n_blocks) {  // this wave's block of the round: registers -> its tile
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int rr = rbase + 4 * i;
+        ktw[rr * 16 + (piece ^ (rr & 15))] = br.k[i];
+        vtw[rr * 16 + (piece ^ v_swizzle(rr))] = br.v[i];
+      }
+    }
+    if (4 * (r + 1) + w < n_blocks) load_block(br, 4 * (r + 1) + w);  // in flight while this round is computed
+    lds_barrier();  // the round's tiles are complete (it does not wait for the loads just requested)
+    if (r == 0) PASTA_CLK(1);
+    if (r == 1) PASTA_CLK(2);
+    if (R > 0) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (4 * r + t < n_blocks) block_compute(t, 4 * r + t);
+    }
+    lds_barrier();  // every wave is done with the tiles
+    if (r == 0) PASTA_CLK(3);
+    if (r == 1) PASTA_CLK(4);
+  }
+  PASTA_CLK(6);
+
+  // ---- this wave's rows leave through its own tile: [32 rows][32 pieces of 4 floats], piece c of
+  // row r at c ^ r, then 512-byte rows go out whole
+  if (R > 0) {
+    f32x4* otile = reinterpret_cast<f32x4*>(&lds.tile[w]);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int b4 = 0; b4 < 4; ++b4) {
+        const int cc = 8 * mt + 2 * b4 + hh;
+        otile[l32 * 32 + (cc ^ l32)] = f32x4{O[mt][4 * b4], O[mt][4 * b4 + 1], O[mt][4 * b4 + 2], O[mt][4 * b4 + 3]};
+      }
+    const float l_all = l_run + __shfl_xor(l_run, 32, kWave);
+    if (hh == 0 && l32 < R) p.part_ml[part_row0 + l32] = make_float2(m_run, l_all);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int pass = 0; pass < 16; ++pass) {
+      const int rr = 2 * pass + hh, cc = l32;
+      const f32x4 val = otile[rr * 32 + (cc ^ rr)];
+      if (rr < R) *reinterpret_cast<f32x4*>(p.part_acc + (part_row0 + rr) * D + 4 * cc) = val;
+    }
+  }
+  PASTA_CLK(7);
 }
 
 }  // namespace pasta

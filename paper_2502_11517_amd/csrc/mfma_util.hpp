@@ -66,7 +66,10 @@ __device__ __forceinline__ int32_t scalar_load_i32(const int32_t* ptr, int idx) 
 // Phase clocks for kernel tuning (compiled in only with -DPASTA_TUNING=2, which the library build never sets): thread 0 of every
 // work-group stores the 100 MHz wall clock at a few points into the tail of the partials buffer.
 #if defined(PASTA_TUNING) && PASTA_TUNING >= 2
-#define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < 512) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
+#ifndef PASTA_CLK_WGS
+#define PASTA_CLK_WGS 512  // work-groups that have a row of eight clocks
+#endif
+#define PASTA_CLK(n) do { if (threadIdx.x == 0 && blockIdx.x < PASTA_CLK_WGS) p.part_ml[p.clock_row0 + (long long)blockIdx.x * 8 + (n)] = \
     __builtin_bit_cast(float2, (unsigned long long)__builtin_amdgcn_s_memrealtime()); } while (0)
 #else
 #define PASTA_CLK(n) do {} while (0)

@@ -584,7 +584,7 @@ extern "C" int32_t pasta_attn_create(pasta_attn_config* cfg, pasta_attn** out) {
     pb.blob.reserve(kInlineMetaWords + 16);
   } catch (...) { return fail(PASTA_E_NOMEM); }
 #if defined(PASTA_TUNING) && PASTA_TUNING >= 2
-  std::fprintf(stderr, "PASTA_CLOCKS byte offset in workspace: %zu\n", h->off_ml + (size_t)(h->part_rows_cap - 8192) * 8);
+  std::fprintf(stderr, "PASTA_CLOCKS byte offset in workspace: %zu\n", h->off_ml + (size_t)(h->part_rows_cap - 16 * PASTA_CLK_WGS) * 8);
 #endif
   *out = h;
   return PASTA_OK;
@@ -1096,12 +1096,22 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
                       h->layer_elems * h->elem < ((int64_t)1 << 32) - 65536 &&
                       (int64_t)n * c.n_q_heads * D * h->elem < ((int64_t)1 << 31);
     if ((dense || probe) && !mfma) return PASTA_E_INVAL;  // the mask and the read-only form belong to the matrix-core kernel
-    int64_t pc_total = 0, pc_weighted = 0;  // the second counts a prefix once per row group of 32
+    int64_t pc_total = 0, pc_weighted = 0;  // the second counts a prefix once per work-group that reads it
     for (auto& q : reqs) {
       if (!mfma || q.pc < kTile || no_share) q.pc = 0;
       pc_total += q.pc;
-      pc_weighted += (int64_t)q.pc * ((q.n_streams * G + 31) / 32);
     }
+    // More than 32 stacked rows per request: the rows go in groups of 32.  When EVERY request with a
+    // shared prefix is that wide, the launch takes the form whose work-groups serve four row groups
+    // each (one per wave, over shared tiles); otherwise each row group is a work-group of its own.
+    bool wide = mfma && !dense && pc_total > 0 && !(a->flags & PASTA_DECODE_ROW_GROUPS);
+    for (auto& q : reqs)
+      if (q.pc > 0 && q.n_streams * G <= 32) wide = false;
+    auto row_units = [&](const DevReq& q) -> int64_t {  // shared-prefix work-groups per (chunk, kv head)
+      const int64_t n_rg = (q.n_streams * G + 31) / 32;
+      return wide ? (n_rg + 3) / 4 : n_rg;
+    };
+    for (auto& q : reqs) pc_weighted += (int64_t)q.pc * row_units(q);
     // Chunking.  Every chunk costs one partial row per stacked query row (written here, read
     // by the merge), so chunks should be long; but the step wants at least one shared-prefix
     // work-group per CU to keep enough loads in flight.  Tokens per chunk = the largest
@@ -1110,7 +1120,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     int64_t priv_chunk = kPrivChunk, chunk_tokens = kTile;
     if (mfma) {
       chunk_tokens = std::max<int64_t>(kTile, pc_weighted * Hkv / h->n_cus / kTile * kTile);
-      priv_chunk = 128;
+      priv_chunk = wide ? 256 : 128;  // (beside the long wide work-groups the private items get one slot per CU: longer items keep more in flight there)
       if (h->tune_prefix_chunk >= kTile) chunk_tokens = h->tune_prefix_chunk / kTile * kTile;
       if (h->tune_priv_chunk >= 32) priv_chunk = std::min<int64_t>(h->tune_priv_chunk / 32 * 32, kGatherMax);  // whole 32-token blocks
     }
@@ -1241,7 +1251,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
           q.chunk_tokens = (int32_t)chunk_tokens;
           q.wg_begin = (int32_t)n_prefix_wgs;
           q.part_base = (int32_t)prefix_rows;
-          n_prefix_wgs += (int64_t)q.n_chunks * Hkv * ((q.n_streams * G + 31) / 32);
+          n_prefix_wgs += (int64_t)q.n_chunks * Hkv * row_units(q);
           prefix_rows += (int64_t)q.n_chunks * Hkv * q.n_streams * G;
         }
         if (prefix_rows + priv_rows <= part_rows_cap) break;
@@ -1393,7 +1403,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
     p.Hkv = Hkv;
     p.scale_log2e = c.softmax_scale * kLog2e;
 #if defined(PASTA_TUNING) && PASTA_TUNING >= 2
-    p.clock_row0 = h->part_rows_cap - 8192 + (a->layer & 1) * 4096;  // the last 64 KiB of the (m, l) array, two halves
+    p.clock_row0 = h->part_rows_cap - 16 * PASTA_CLK_WGS + (a->layer & 1) * 8 * PASTA_CLK_WGS;  // the tail of the (m, l) array, two halves
 #endif
     p.single_req = reqs.size() == 1 ? 1 : 0;
     if (p.single_req && n <= 16) {  // item ranges of the streams as kernel-argument scalars
@@ -1439,15 +1449,18 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
         // prefix chunks of more than two 32-token blocks per wave: the variant whose loop has the
         // cheap addressing of plain blocks
         const bool long_items = n_prefix_wgs > 0 && chunk_tokens > 2 * 4 * 32;
-        if (probe) {
+        if (probe && !wide) {
           if (h->lay.paged) { if (long_items) launch(k_attn<true, false, true, true>); else launch(k_attn<true, false, false, true>); }
           else { if (long_items) launch(k_attn<false, false, true, true>); else launch(k_attn<false, false, false, true>); }
-        } else if (h->lay.paged) {
-          if (long_items) launch(k_attn<true, false, true>);
-          else launch(k_attn<true, false>);
+        } else if (!wide) {
+          if (h->lay.paged) { if (long_items) launch(k_attn<true, false, true>); else launch(k_attn<true, false>); }
+          else { if (long_items) launch(k_attn<false, false, true>); else launch(k_attn<false, false>); }
+        } else if (probe) {
+          if (h->lay.paged) launch(k_attn<true, false, false, true, true>);
+          else launch(k_attn<false, false, false, true, true>);
         } else {
-          if (long_items) launch(k_attn<false, false, true>);
-          else launch(k_attn<false, false>);
+          if (h->lay.paged) launch(k_attn<true, false, false, false, true>);
+          else launch(k_attn<false, false, false, false, true>);
         }
       }
       if (take_pending) h->pending.active = false;

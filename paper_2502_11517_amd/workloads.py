@@ -327,7 +327,7 @@ def config5():
 
 
 def config4(n_requests: int = 16, seed: int = 1004, pmin: int = 256, pmax: int = 4096,
-            page_tokens: int = 16):
+            page_tokens: int = 16, hq: int = 32, hkv: int = 8, smin: int = 1, smax: int = 8):
     """Ragged paged batch: 16 independent requests, bf16 32/8/128; per request a prefix uniform
     in [256,4096] and 1..8 streams with log-normal lengths (median 96, cap 1024), random
     interleave; 16-token pages placed by a seeded permutation of the page pool."""
@@ -339,7 +339,7 @@ def config4(n_requests: int = 16, seed: int = 1004, pmin: int = 256, pmax: int =
     per_req = []
     for r in range(n_requests):
         P = int(rng.integers(pmin, pmax + 1))
-        ns = int(rng.integers(1, 9))
+        ns = int(rng.integers(smin, smax + 1))
         L = np.clip(np.rint(np.exp(rng.normal(np.log(96.0), 1.0, size=ns))), 1, 1024).astype(int).tolist()
         order = _interleave_random(rng, L)
         fs, fp = _fork_events(order, 1, [ROOT] * ns)
@@ -363,7 +363,7 @@ def config4(n_requests: int = 16, seed: int = 1004, pmin: int = 256, pmax: int =
         table[r, :need[r]] = perm[pos:pos + need[r]]
         table[r, need[r]:] = -1  # no page assigned: beyond the request's tail
         pos += need[r]
-    w = Workload(name="cfg4_ragged_paged16", dtype="bf16", Hq=32, Hkv=8, D=128, scale=1.0, seed=seed,
+    w = Workload(name="cfg4_ragged_paged16", dtype="bf16", Hq=hq, Hkv=hkv, D=128, scale=1.0, seed=seed,
                  max_requests=n_requests, page_tokens=page_tokens, n_phys_pages=n_phys,
                  pages_per_request=ppr, page_table=table, max_streams=max_streams,
                  k_std=128 ** -0.5)

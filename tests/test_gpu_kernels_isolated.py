@@ -81,17 +81,23 @@ def test_partials_of_the_attention_launch_against_the_oracle(flags):
                 for i in range(n):
                     for gi in (0, G - 1):
                         check((g * n_chunks + c) * R + i * G + gi, phys, i, g * G + gi, f"prefix chunk {c} head {g} stream {i}")
-    # private parts: consecutive 128-token pieces of each stream's list beyond the common prefix
+    # private parts: consecutive pieces of each stream's list beyond the common prefix
+    piece = _piece_tokens(n, G, pc)
     j = 0
     for i in range(n):
         rest = maps[i][pc:]
-        for t0 in range(0, len(rest), 128):
+        for t0 in range(0, len(rest), piece):
             for g in range(Hkv):
                 for gi in range(G):
-                    check(priv0 + (j * Hkv + g) * G + gi, rest[t0:t0 + 128], i, g * G + gi, f"item {j} head {g}")
+                    check(priv0 + (j * Hkv + g) * G + gi, rest[t0:t0 + piece], i, g * G + gi, f"item {j} head {g}")
             j += 1
     assert j == n_items
     s.close()
+
+
+def _piece_tokens(n_streams, G, pc):
+    """Tokens per private work item, as the header documents: 128, or 256 beside the wide shared-prefix work-groups."""
+    return 256 if (pc and n_streams * G > 32) else 128
 
 
 def _merge_case(n_streams, Hq, Hkv, prefix, lengths, seed, poison):
@@ -118,8 +124,9 @@ def _merge_case(n_streams, Hq, Hkv, prefix, lengths, seed, poison):
     pl, offs, st, ct, sd = w.lists(0)
     # (a plan sent whole cuts a stream's list beyond the common prefix into 128-token pieces; a step that reads the
     # device-resident lists cuts the visible head beyond the common prefix and the range list separately)
-    whole = [-(-(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum())) // 128) for i in range(n)]
-    split = [-(-(int(pl[i]) - pc) // 128) + -(-int(ct[offs[i]:offs[i + 1]].sum()) // 128) for i in range(n)]
+    piece = _piece_tokens(n, G, pc)
+    whole = [-(-(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum())) // piece) for i in range(n)]
+    split = [-(-(int(pl[i]) - pc) // piece) + -(-int(ct[offs[i]:offs[i + 1]].sum()) // piece) for i in range(n)]
     counts = whole if sum(whole) == n_items else split
     items_of, j = [], 0
     for cnt in counts:

@@ -511,6 +511,64 @@ def test_long_prefix_chunks_paged_pool(page_tokens):
         s.close()
 
 
+# ------------------------------------------------------------------------- more than 32 stacked rows
+@pytest.mark.parametrize("Hq,Hkv,prefix,lengths", [
+    (16, 4, 4096 + 17, [130] * 9),    # 36 rows: a full group and one of 4 rows (two waves only carry tiles)
+    (16, 4, 100, [7] * 17),           # 68 rows, a prefix of less than one round
+    (16, 4, 64 * 33, [3] * 33),       # 132 rows: two work-groups per (chunk, kv head), the second with 4 rows
+    (64, 8, 1000, [40, 1, 300, 2, 9]),  # 8 heads per kv head, five streams: 40 rows
+    (8, 1, 777, [50] * 6),            # one kv head, 48 rows
+])
+def test_wide_requests_four_row_groups_per_work_group(Hq, Hkv, prefix, lengths):
+    """Requests with more than 32 stacked rows: the launch whose work-groups serve four 32-row groups each
+    (one per wave) against the oracle, and against the row-group-per-work-group form of the same step."""
+    w = W.single_request("wide", "bf16", Hq, Hkv, 128, 1.0, 41, prefix, lengths, "round_robin", k_std=128 ** -0.5)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    plan, plan_rg = np.zeros(8, np.int64), np.zeros(8, np.int64)
+    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY, dbg_plan=plan)
+    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY | B.DECODE_ROW_GROUPS, dbg_plan=plan_rg)
+    R = len(lengths) * (Hq // Hkv)
+    n_chunks = -(-prefix // plan[4])
+    assert plan[1] == n_chunks * Hkv * -(-R // 128)
+    assert plan_rg[1] == -(-prefix // plan_rg[4]) * Hkv * -(-R // 32)
+    cache = {}
+    _check_step(w, s, op, ref_cache=cache)
+    _check_step(w, s, op, explicit=False, ref_cache=cache)
+    _check_step(w, s, op, flags=B.DECODE_ROW_GROUPS, ref_cache=cache)
+    s.close()
+
+
+def test_wide_request_whose_prefix_ends_in_a_deferred_row():
+    """Five streams fork right after the root's newest token, and that token and the forks arrive in ONE deferred
+    append: the last row of the common prefix still sits in the caller's buffers when the wide work-groups
+    read it."""
+    w = W.single_request("fork_wide", "bf16", 64, 8, 128, 1.0, 5, 700, [1] * 5, "round_robin", k_std=128 ** -0.5)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill - 6)
+    s.append_events(w.n_prefill, flags=B.APPEND_DEFER)
+    pl, *_ = w.lists(0)
+    assert min(pl.tolist()) == 700
+    _check_step(w, s, op)
+    _check_pool(w, s, op)
+    s.close()
+
+
+@pytest.mark.parametrize("page_tokens", [16, 8])
+def test_wide_requests_in_a_ragged_paged_batch(page_tokens):
+    """Several requests of 5..9 streams x 8 heads per kv head, paged pools (pages of 8 tokens: one address per row)."""
+    w = W.config4(n_requests=3, seed=91, pmin=200, pmax=2500, page_tokens=page_tokens, hq=64, hkv=8, smin=5, smax=9)
+    s = _session(w)
+    op = OraclePool(w).append_events(w.n_prefill)
+    s.append_events(w.n_prefill)
+    cache = {}
+    _check_step(w, s, op, ref_cache=cache)
+    _check_step(w, s, op, explicit=False, ref_cache=cache)
+    s.close()
+
+
 # ------------------------------------------------------------------------- deferred append
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_deferred_append_rides_with_the_decode_launch(layout):
