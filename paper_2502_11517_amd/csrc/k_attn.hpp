@@ -354,27 +354,51 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     const long long e = elem_off(p.lay, req * p.lay.pool_tokens + slot0 + b * kBlock * stride, g) * 2;
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)e);
   };
-  struct DmaRows { uint32_t off[8]; bool any_pend; bool plain; uint32_t base; };
+  // Rows of a deferred append are the newest slots of their request, so in a list (ascending slots) they
+  // come LAST: a block holds them as a run at its end.  Up to four of them behind at least one pool row
+  // are PATCHED: the block is fetched from the pool as if nothing were deferred (in their places, and in
+  // the places past the item's end, the block's last pool row once more), the deferred rows themselves
+  // come through one register per lane, requested ahead of everything, and are written over their places
+  // when the block has landed.  (Fetching them into LDS under lane masks costs a loop per row group; on a
+  // step of a few streams that was 1.9 us of 11.)  Other mixes take that masked path.
+  struct DmaRows { uint32_t off[8]; bool any_pend; bool plain; uint32_t base; bool patch; int first_pend, n_pend; };
+  auto is_pend = [&](int j) -> bool {  // j < n_tok
+    if constexpr (GATHER) {
+      if (listed) return lds.rows[j] < 0;
+    }
+    return slot0 + j * stride >= pend0;
+  };
   auto dma_rows = [&](int b) -> DmaRows {  // K-side offsets of block b's rows for this lane's LDS places
     DmaRows d;
     d.plain = plain_block(b);
     d.any_pend = false;
+    d.patch = false;
+    d.first_pend = kBlock;
+    d.n_pend = 0;
     d.base = 0;
     if (d.plain) {
       d.base = block_base(b);
       return d;
     }
-    bool pend = false;
+    {
+      const int jl = b * kBlock + l32;
+      const uint32_t m = (uint32_t)__builtin_amdgcn_ballot_w64(jl < n_tok && is_pend(jl));  // both halves of the wave agree
+      if (m) {
+        d.first_pend = __builtin_ctz(m);
+        d.n_pend = min(kBlock, n_tok - b * kBlock) - d.first_pend;
+        d.patch = d.first_pend > 0 && d.n_pend <= 4;
+        d.any_pend = !d.patch;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = rbase + 4 * i;
-      const int j = min(b * kBlock + r, n_tok - 1);  // rows past the end repeat the last one
+      int j = min(b * kBlock + r, n_tok - 1);  // rows past the end repeat the last one
+      if (d.patch && r >= d.first_pend) j = b * kBlock + d.first_pend - 1;  // ... the last one in the pool
       bool pn;
       const long long o = src_of(j, pn);
-      pend = pend || pn;
       d.off[i] = (uint32_t)o + (uint32_t)((piece ^ (r & 15)) * 16);
     }
-    d.any_pend = __builtin_amdgcn_ballot_w64(pend) != 0;
     return d;
   };
   auto dma_half = [&](int b, const DmaRows& d, auto is_v) {  // K (or V) of block b -> kt (vt)
@@ -392,21 +416,23 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
         __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v.value ? v_rs : k_rs, (lds_ptr)(dst + 64 * i), 16, o, 0, 0, 0);
       }
     } else {
-      // some row of the block is a deferred one: per-row 64-bit addresses through registers, waited
-      // for on the spot (rare: the newest rows of a list sit in its last block).  No flat-encoded
-      // load into LDS here either: one such path is enough to spoil the compiler's waits after it.
-      u32x4 tmp[8];
+      // some row of the block is a deferred one (the newest rows of a list sit in its last block): those
+      // lanes fetch from the caller's rows through a descriptor of their own, the others from the pool --
+      // two loads into LDS under complementary lane masks (a lane that is switched off neither reads nor
+      // writes its LDS place), nothing waited for here.  The explicit waits further down count one load
+      // per row group; where a group needed two, they wait for a little more than they have to, never
+      // for less (loads return in issue order).
+      const __amdgpu_buffer_rsrc_t p_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(is_v.value ? vpend : kpend), 0, -1, kRawBuffer);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int r = rbase + 4 * i;
         const int j = min(b * kBlock + r, n_tok - 1);
         bool pn;
-        long long o = src_of(j, pn) + (piece ^ (r & 15)) * 16;
-        if (is_v.value) o ^= ((r & 15) ^ v_swizzle(r)) << 4;
-        tmp[i] = *reinterpret_cast<const u32x4*>((pn ? (is_v.value ? vpend : kpend) : (is_v.value ? vb : kb)) + o);
+        uint32_t o = (uint32_t)src_of(j, pn) + (uint32_t)((piece ^ (r & 15)) * 16);  // deferred rows: offset in k_new / v_new
+        if (is_v.value) o ^= (uint32_t)(((r & 15) ^ v_swizzle(r)) << 4);
+        if (pn) __builtin_amdgcn_raw_ptr_buffer_load_lds(p_rs, (lds_ptr)(dst + 64 * i), 16, o, 0, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(is_v.value ? v_rs : k_rs, (lds_ptr)(dst + 64 * i), 16, o, 0, 0, 0);
       }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) dst[64 * i + lane] = tmp[i];
     }
   };
   auto load_half = [&](u32x4 (&dst)[8], int b, auto is_v) {  // K (or V) of block b -> registers, natural piece order
@@ -602,8 +628,20 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
   u32x4 probe_acc = u32x4{0u, 0u, 0u, 0u};
   auto first_blocks = [&](auto h1, auto h2) {
     DmaRows d{};
+    u32x4 patch_k = u32x4{0u, 0u, 0u, 0u}, patch_v = u32x4{0u, 0u, 0u, 0u};  // deferred rows of the first block (lane: row lane / 16 of the run)
+    int patch_row = -1;                                        // this lane's row of the block, -1: none
     if constexpr (h1.value) {
       d = dma_rows(w);
+      if (d.patch) {
+        if ((lane >> 4) < d.n_pend) {
+          patch_row = d.first_pend + (lane >> 4);
+          bool pn;
+          const long long o = src_of(w * kBlock + patch_row, pn) + piece * 16;  // in k_new / v_new
+          patch_k = *reinterpret_cast<const u32x4*>(kpend + o);
+          patch_v = *reinterpret_cast<const u32x4*>(vpend + o);
+        }
+        __builtin_amdgcn_sched_barrier(0);                     // ahead of the block: loads return in issue order
+      }
       dma_half(w, d, std::false_type{});                       // K1 -> tile
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -637,6 +675,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
     } else if constexpr (h1.value) {
       wait_vmcnt<h2.value ? 24 : 8>();                          // K1 is in the tile
       tile_sync();
+      if (d.patch) {
+        if (patch_row >= 0) ktw[patch_row * 16 + (piece ^ (patch_row & 15))] = patch_k;
+        tile_sync();
+      }
       PASTA_CLK(3);
       f32x16 S1 = s_block(w);
       float mx = row_max(S1);
@@ -659,6 +701,10 @@ __device__ __forceinline__ void attn_item(const DecodeParams& p, AttnLds& lds, c
       PASTA_CLK(5);
       wait_vmcnt<h2.value ? 8 : 0>();                           // V1 is in the tile
       tile_sync();
+      if (d.patch) {
+        if (patch_row >= 0) vtw[patch_row * 16 + (piece ^ v_swizzle(patch_row))] = patch_v;
+        tile_sync();
+      }
       pv_block(P1);
       PASTA_CLK(4);
       if constexpr (h2.value) {

@@ -114,6 +114,8 @@ struct pasta_attn {
   size_t off_arena = 0, off_cidx = 0;
   int64_t arena_cap = 0, cidx_cap = 0, arena_top = 0, cidx_top = 0;
   bool tables_reset = false;             // the segments ran out: start over at the next call (all streams dirty)
+  bool lists_in_use = false;             // a decode step has read the device copy: appends keep it current from then on
+                                         // (before that they only mark what changed, and may be deferred freely)
   std::vector<DevRange> stage_r;         // staging of one stream's lists for a rebuild
   std::vector<int32_t> stage_c;
   struct Undo { int64_t key; bool open; int32_t prefix_len; int32_t n_ranges; Range last; int64_t range_tokens;
@@ -718,6 +720,10 @@ extern "C" int32_t pasta_attn_append_kv(pasta_attn* h, const pasta_append_args* 
       StreamState& st = h->streams[(size_t)e.key];
       const int32_t nb = e.n_ranges, na = (int32_t)st.ranges.size();
       if (st.dirty) continue;
+      if (!h->lists_in_use) {  // no step has read the device copy so far: nothing to keep current
+        if (na != nb) st.dirty = true;
+        continue;
+      }
       if (na == nb) {  // growth only
         st.dev_ranges = std::min(st.dev_ranges, std::max(na - 1, 0));
         continue;
@@ -1156,6 +1162,7 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
         else if (rb != PASTA_OK) return rb;
       }
       if (!dev_lists && (a->flags & PASTA_DECODE_DEVICE_LISTS)) return PASTA_E_CAPACITY;
+      if (dev_lists) h->lists_in_use = true;
     }
     // private items
     std::vector<DevStream>& streams = pb.streams;
