@@ -26,10 +26,19 @@
  * Efficiency, last paragraphs; contrast with the appendix "Naive Interpreter
  * Implementation").
  *
- * Everything runs on one GPU (gfx950).  All entry points return a status
- * code; none throws, aborts, or keeps global state.  "HOST" / "DEVICE" below
- * say where a pointer must point.  The library allocates NO device memory:
- * pool, workspace, Q and outputs are the caller's.
+ * Everything runs on one GPU (gfx950).  The library exports eight symbols:
+ * the four calls of the hot path (pasta_attn_create, pasta_attn_append_kv,
+ * pasta_attn_decode_step, pasta_attn_destroy), three calls of host control
+ * flow around it (pasta_attn_sync, pasta_attn_stream_list: the fork / sync
+ * lifecycle of the maintained lists; pasta_attn_replay: a whole response
+ * through the interpreter's control flow) and pasta_attn_decode_step_noalloc
+ * (the decode step for callers that may not allocate).  All entry points
+ * return a status code; none throws or aborts.  "HOST" / "DEVICE" below say
+ * where a pointer must point.  The library allocates NO device memory: pool,
+ * workspace, Q and outputs are the caller's (the one piece of device memory
+ * of its own is the fixed-size static array of the no-alloc entry point).
+ * The page table alone is a HOST array: it is written once, create copies it
+ * into the workspace, and the host-side planner reads it too.
  */
 #ifndef PASTA_ATTN_H
 #define PASTA_ATTN_H

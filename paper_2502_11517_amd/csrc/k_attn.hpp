@@ -877,6 +877,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void k_attn(DecodeParams p) {
       }
     }
   }
+  if constexpr (WIDE) {  // (the wide work-groups have no register to spare for carrying it, and are long enough not to care)
+    if (pend_u >= 0) { pend_store(pend_u, pend_val); pend_u = -1; }
+  }
   // shared-prefix items first: they are the longer ones (up to two blocks per wave against one)
   const int n_prefix_wgs = (int)gridDim.x - p.n_mfma_items * p.Hkv;  // a multiple of Hkv
   // (a raised wave priority for the shared-prefix items, so that the longer items issue their loads
