@@ -537,6 +537,18 @@ def test_wide_requests_four_row_groups_per_work_group(Hq, Hkv, prefix, lengths):
     _check_step(w, s, op, ref_cache=cache)
     _check_step(w, s, op, explicit=False, ref_cache=cache)
     _check_step(w, s, op, flags=B.DECODE_ROW_GROUPS, ref_cache=cache)
+    _check_step(w, s, op, explicit=False, flags=B.DECODE_DEVICE_LISTS, ref_cache=cache)  # items derived by the kernels
+    # the entry point that allocates nothing takes the same launch (its partial rows fit the static array here)
+    from paper_2502_11517_amd.harness import to_device
+    qd = to_device(w.q(0), w.dtype, s.device)
+    out = torch.empty_like(qd)
+    if w.n <= 24:  # (33 stream records do not fit the kernel arguments: that entry point then refuses the step)
+        s.h.decode_step_noalloc(0, w.dec_request, w.dec_stream, qd, out)
+        check_close(_out64(w, out), cache[next(iter(cache))][0], w.dtype, "wide, no-alloc entry point")
+    else:
+        with pytest.raises(B.PastaError) as e:
+            s.h.decode_step_noalloc(0, w.dec_request, w.dec_stream, qd, out)
+        assert e.value.code == B.E_CAPACITY
     s.close()
 
 
