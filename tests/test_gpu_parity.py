@@ -4,7 +4,6 @@ bit-exact; outputs must be within max-abs 2e-2 AND relative-L2 1e-2 for bf16, 1e
 for fp32."""
 from __future__ import annotations
 
-
 import numpy as np
 import pytest
 import torch
