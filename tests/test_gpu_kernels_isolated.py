@@ -43,13 +43,17 @@ def _partials(s, w, rows, flags=0, ml=None, acc=None):
     return ml, acc, out, lse
 
 
-@pytest.mark.parametrize("flags", [0, B.DECODE_NO_MFMA])
-def test_partials_of_the_attention_launch_against_the_oracle(flags):
+@pytest.mark.parametrize("flags,wide", [(0, False), (B.DECODE_NO_MFMA, False), (0, True)])
+def test_partials_of_the_attention_launch_against_the_oracle(flags, wide):
     """One request, 3 streams, a prefix of several split chunks, round-robin private rows: every
     shared-prefix partial of sampled (chunk, kv head, row) and every private partial row against
     oracle.partial over the same physical rows.  Also with the vector-ALU kernel (NO_MFMA), whose
-    items are all private."""
-    w = W.single_request("iso", "bf16", 8, 2, 128, 1.0, 91, 1500, [300, 77, 140], "round_robin", k_std=128 ** -0.5)
+    items are all private, and with 5 streams x 8 heads per kv head = 40 stacked rows (the work-groups
+    that serve four 32-row groups each: one full group and one of 8 rows)."""
+    if wide:
+        w = W.single_request("isow", "bf16", 16, 2, 128, 1.0, 92, 1500, [300, 77, 140, 20, 260], "round_robin", k_std=128 ** -0.5)
+    else:
+        w = W.single_request("iso", "bf16", 8, 2, 128, 1.0, 91, 1500, [300, 77, 140], "round_robin", k_std=128 ** -0.5)
     s = _session(w)
     op = OraclePool(w).append_events(w.n_prefill)
     s.append_events(w.n_prefill)
