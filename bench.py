@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--prefix", type=int, default=8192, help="config 3 with another shared-prefix length (side measurement)")
     ap.add_argument("--no-share", action="store_true",
                     help="comparison: no shared-prefix items, every stream reads its whole visible set itself")
+    ap.add_argument("--row-groups", action="store_true",
+                    help="comparison: requests with more than 32 stacked query rows are served one 32-row group per "
+                         "work-group (PASTA_DECODE_ROW_GROUPS) instead of four groups per work-group")
     ap.add_argument("--dense-mask", action="store_true",
                     help="comparison: every stream walks the whole pool under a 0/1 mask (the paper's own formulation)")
     ap.add_argument("--rope", action="store_true",
@@ -120,6 +123,7 @@ def main():
     out = torch.empty(L, w.n, w.Hq, w.D, dtype=torch.bfloat16, device=dev)
     flags = (B.DECODE_NO_MFMA if args.no_mfma else 0) | (B.DECODE_ROPE_Q if args.rope else 0)
     flags |= (B.DECODE_NO_SHARE if args.no_share else 0) | (B.DECODE_DENSE_MASK if args.dense_mask else 0)
+    flags |= B.DECODE_ROW_GROUPS if args.row_groups else 0
     q_pos = [w.q_positions(t) if args.rope else None for t in range(tokens)]
 
     # HIP events around the attention-partials kernels of sampled steps (never step 0)
@@ -354,7 +358,7 @@ def decode_only(args, w, dev):
         torch.cuda.synchronize()
     q = to_device(w.q(0), w.dtype, dev)
     out = torch.empty(L, w.n, w.Hq, w.D, dtype=q.dtype, device=dev)
-    flags = B.DECODE_NO_MFMA if args.no_mfma else 0
+    flags = (B.DECODE_NO_MFMA if args.no_mfma else 0) | (B.DECODE_ROW_GROUPS if args.row_groups else 0)
     every = event_period(args.steps, args.event_every)
     n_ev = args.steps // every + 1
     evs = []

@@ -232,9 +232,12 @@ enum {
                                        step's plan would fit the kernel arguments (see "Maintained lists on the
                                        device" below); E_INVAL with explicit lists, causal_skip or DENSE_MASK,
                                        E_CAPACITY when the copy has no room */
-  PASTA_DECODE_ROW_GROUPS = 512u,   /* comparison mode: a request with more than 32 stacked query rows
-                                       (streams x heads per kv head) is served one 32-row group per work-group,
-                                       also where the launch could give four groups to each work-group */
+  /* A request with more than 32 stacked query rows (streams x heads per kv head) is served in groups of 32 rows:
+   * one group per work-group, or -- when every request of the step with a shared prefix is that wide -- four
+   * groups per work-group.  The library picks by the step's shape; these two flags force either form (both:
+   * E_INVAL; FOUR_GROUPS has no effect on a step with a request of 32 rows or fewer): */
+  PASTA_DECODE_ROW_GROUPS = 512u,
+  PASTA_DECODE_FOUR_GROUPS = 1024u,
   /* Two flags for testing the kernels one by one (with dbg_part_ml / dbg_part_acc below): */
   PASTA_DECODE_PARTIALS_ONLY = 64u, /* the attention launch(es) only, no merge: `out` is NOT written */
   PASTA_DECODE_MERGE_ONLY = 128u,   /* the merge launch only, over the partial rows as the buffers hold them
@@ -303,8 +306,8 @@ typedef struct {
                                    dbg_plan[4]); the private part of (item j, kv head g, head in group i) is row
                                    dbg_plan[7] + (j * Hkv + g) * G + i, the items of a stream being consecutive
                                    128-token pieces of its list beyond the common prefix, stream after stream
-                                   (256-token pieces when R > 32 and the step has a shared-prefix part, unless
-                                   PASTA_DECODE_ROW_GROUPS; a step that reads the device-resident lists cuts the
+                                   (256-token pieces when the step takes the four-groups-per-work-group form,
+                                   see PASTA_DECODE_FOUR_GROUPS; a step that reads the device-resident lists cuts the
                                    visible head beyond the common prefix and the range list into pieces separately). */
   void *prof_event_start;       /* hipEvent_t or NULL (both or neither): they receive the start and the */
   void *prof_event_stop;        /* end of the attention-partials kernel's execution (attached to its

@@ -20,7 +20,7 @@ OK, E_INVAL, E_CAPACITY, E_NOMEM, E_DEVICE, E_STATE = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
 DECODE_PLAN_ONLY, DECODE_NO_MFMA, DECODE_ROPE_Q, DECODE_NO_SHARE, DECODE_DENSE_MASK, DECODE_READ_PROBE = 1, 2, 4, 8, 16, 32
-DECODE_PARTIALS_ONLY, DECODE_MERGE_ONLY, DECODE_DEVICE_LISTS, DECODE_ROW_GROUPS = 64, 128, 256, 512
+DECODE_PARTIALS_ONLY, DECODE_MERGE_ONLY, DECODE_DEVICE_LISTS, DECODE_ROW_GROUPS, DECODE_FOUR_GROUPS = 64, 128, 256, 512, 1024
 APPEND_RESERVE_ONLY, APPEND_DEFER, APPEND_ROPE = 1, 2, 4
 SYNC_RETIRE = 1
 OP_TEXT, OP_PROMISE, OP_SYNC = 0, 1, 2

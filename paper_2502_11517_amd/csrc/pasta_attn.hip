@@ -1108,15 +1108,31 @@ int32_t decode_impl(pasta_attn* h, const pasta_decode_args* a, const bool no_all
       pc_total += q.pc;
     }
     // More than 32 stacked rows per request: the rows go in groups of 32.  When EVERY request with a
-    // shared prefix is that wide, the launch takes the form whose work-groups serve four row groups
+    // shared prefix is that wide, the launch may take the form whose work-groups serve four row groups
     // each (one per wave, over shared tiles); otherwise each row group is a work-group of its own.
+    // The wide form pays where its waves are busy and its pipeline gets going -- every such request
+    // keeps three of four waves computing on average, and a chunk is four rounds or more -- and loses
+    // a few per cent elsewhere (measured on 12 to 32 streams over prefixes of 8k and 32k tokens); the
+    // caller may force either form.
     bool wide = mfma && !dense && pc_total > 0 && !(a->flags & PASTA_DECODE_ROW_GROUPS);
-    for (auto& q : reqs)
-      if (q.pc > 0 && q.n_streams * G <= 32) wide = false;
+    const bool force_wide = a->flags & PASTA_DECODE_FOUR_GROUPS;
+    if ((a->flags & PASTA_DECODE_ROW_GROUPS) && force_wide) return PASTA_E_INVAL;
+    for (auto& q : reqs) {
+      if (q.pc <= 0) continue;
+      const int R_all = q.n_streams * G;
+      if (R_all <= 32) wide = false;
+      const int n_rg = (R_all + 31) / 32, n_quads = (n_rg + 3) / 4;
+      if (!force_wide && n_rg < 3 * n_quads) wide = false;  // on average fewer than three of a work-group's four waves would compute
+    }
     auto row_units = [&](const DevReq& q) -> int64_t {  // shared-prefix work-groups per (chunk, kv head)
       const int64_t n_rg = (q.n_streams * G + 31) / 32;
       return wide ? (n_rg + 3) / 4 : n_rg;
     };
+    if (wide && !force_wide) {  // the chunk the wide form would get: at least four rounds of four 32-token blocks?
+      int64_t pw = 0;
+      for (auto& q : reqs) pw += (int64_t)q.pc * row_units(q);
+      if (pw * Hkv / h->n_cus < 4 * 4 * 32) wide = false;
+    }
     for (auto& q : reqs) pc_weighted += (int64_t)q.pc * row_units(q);
     // Chunking.  Every chunk costs one partial row per stacked query row (written here, read
     // by the merge), so chunks should be long; but the step wants at least one shared-prefix

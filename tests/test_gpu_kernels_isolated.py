@@ -25,7 +25,7 @@ def _session(w, **kw):
 
 def _plan(s, w):
     plan = np.zeros(8, np.int64)
-    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY, dbg_plan=plan)
+    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY | B.DECODE_ROW_GROUPS, dbg_plan=plan)
     return plan
 
 
@@ -50,6 +50,7 @@ def test_partials_of_the_attention_launch_against_the_oracle(flags, wide):
     oracle.partial over the same physical rows.  Also with the vector-ALU kernel (NO_MFMA), whose
     items are all private, and with 5 streams x 8 heads per kv head = 40 stacked rows (the work-groups
     that serve four 32-row groups each: one full group and one of 8 rows)."""
+    flags |= B.DECODE_FOUR_GROUPS if wide else 0
     if wide:
         w = W.single_request("isow", "bf16", 16, 2, 128, 1.0, 92, 1500, [300, 77, 140, 20, 260], "round_robin", k_std=128 ** -0.5)
     else:
@@ -76,7 +77,7 @@ def test_partials_of_the_attention_launch_against_the_oracle(flags, wide):
         assert np.linalg.norm(acc[row] - a) <= 6e-3 * np.linalg.norm(a), f"{what}: acc"
 
     if pc:  # shared-prefix parts: chunk c of [0, pc), all streams stacked
-        assert flags == 0 and pc == int(pl.min())
+        assert not (flags & B.DECODE_NO_MFMA) and pc == int(pl.min())
         n_chunks, R = -(-pc // chunk), n * G
         assert n_chunks >= 3
         for c in sorted({0, 1, n_chunks - 1}):
@@ -86,7 +87,7 @@ def test_partials_of_the_attention_launch_against_the_oracle(flags, wide):
                     for gi in (0, G - 1):
                         check((g * n_chunks + c) * R + i * G + gi, phys, i, g * G + gi, f"prefix chunk {c} head {g} stream {i}")
     # private parts: consecutive pieces of each stream's list beyond the common prefix
-    piece = _piece_tokens(n, G, pc)
+    piece = 256 if wide else 128
     j = 0
     for i in range(n):
         rest = maps[i][pc:]
@@ -97,11 +98,6 @@ def test_partials_of_the_attention_launch_against_the_oracle(flags, wide):
             j += 1
     assert j == n_items
     s.close()
-
-
-def _piece_tokens(n_streams, G, pc):
-    """Tokens per private work item, as the header documents: 128, or 256 beside the wide shared-prefix work-groups."""
-    return 256 if (pc and n_streams * G > 32) else 128
 
 
 def _merge_case(n_streams, Hq, Hkv, prefix, lengths, seed, poison):
@@ -128,7 +124,7 @@ def _merge_case(n_streams, Hq, Hkv, prefix, lengths, seed, poison):
     pl, offs, st, ct, sd = w.lists(0)
     # (a plan sent whole cuts a stream's list beyond the common prefix into 128-token pieces; a step that reads the
     # device-resident lists cuts the visible head beyond the common prefix and the range list separately)
-    piece = _piece_tokens(n, G, pc)
+    piece = 128  # (the plan above asked for the row-group form)
     whole = [-(-(int(pl[i]) - pc + int(ct[offs[i]:offs[i + 1]].sum())) // piece) for i in range(n)]
     split = [-(-(int(pl[i]) - pc) // piece) + -(-int(ct[offs[i]:offs[i + 1]].sum()) // piece) for i in range(n)]
     counts = whole if sum(whole) == n_items else split
@@ -145,7 +141,7 @@ def _merge_case(n_streams, Hq, Hkv, prefix, lengths, seed, poison):
     acc32 = acc.astype(np.float32)
     mld = torch.from_numpy(ml32).to(s.device)
     accd = torch.from_numpy(acc32).to(s.device)
-    _, _, out, lse = _partials(s, w, rows, flags=B.DECODE_MERGE_ONLY, ml=mld, acc=accd)
+    _, _, out, lse = _partials(s, w, rows, flags=B.DECODE_MERGE_ONLY | B.DECODE_ROW_GROUPS, ml=mld, acc=accd)
     from paper_2502_11517_amd.harness import to_host_bits
     got = to_f64(w, to_host_bits(out, w.dtype))
     lse = lse.cpu().numpy().astype(np.float64)

@@ -526,27 +526,28 @@ def test_wide_requests_four_row_groups_per_work_group(Hq, Hkv, prefix, lengths):
     op = OraclePool(w).append_events(w.n_prefill)
     s.append_events(w.n_prefill)
     plan, plan_rg = np.zeros(8, np.int64), np.zeros(8, np.int64)
-    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY, dbg_plan=plan)
+    s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY | B.DECODE_FOUR_GROUPS, dbg_plan=plan)
     s.h.decode_step(0, w.dec_request, w.dec_stream, None, None, flags=B.DECODE_PLAN_ONLY | B.DECODE_ROW_GROUPS, dbg_plan=plan_rg)
     R = len(lengths) * (Hq // Hkv)
     n_chunks = -(-prefix // plan[4])
     assert plan[1] == n_chunks * Hkv * -(-R // 128)
     assert plan_rg[1] == -(-prefix // plan_rg[4]) * Hkv * -(-R // 32)
     cache = {}
-    _check_step(w, s, op, ref_cache=cache)
-    _check_step(w, s, op, explicit=False, ref_cache=cache)
+    _check_step(w, s, op, flags=B.DECODE_FOUR_GROUPS, ref_cache=cache)
+    _check_step(w, s, op, explicit=False, flags=B.DECODE_FOUR_GROUPS, ref_cache=cache)
     _check_step(w, s, op, flags=B.DECODE_ROW_GROUPS, ref_cache=cache)
-    _check_step(w, s, op, explicit=False, flags=B.DECODE_DEVICE_LISTS, ref_cache=cache)  # items derived by the kernels
+    _check_step(w, s, op, ref_cache=cache)  # the form the library picks by itself
+    _check_step(w, s, op, explicit=False, flags=B.DECODE_DEVICE_LISTS | B.DECODE_FOUR_GROUPS, ref_cache=cache)  # items derived by the kernels
     # the entry point that allocates nothing takes the same launch (its partial rows fit the static array here)
     from paper_2502_11517_amd.harness import to_device
     qd = to_device(w.q(0), w.dtype, s.device)
     out = torch.empty_like(qd)
     if w.n <= 24:  # (33 stream records do not fit the kernel arguments: that entry point then refuses the step)
-        s.h.decode_step_noalloc(0, w.dec_request, w.dec_stream, qd, out)
+        s.h.decode_step_noalloc(0, w.dec_request, w.dec_stream, qd, out, flags=B.DECODE_FOUR_GROUPS)
         check_close(_out64(w, out), cache[next(iter(cache))][0], w.dtype, "wide, no-alloc entry point")
     else:
         with pytest.raises(B.PastaError) as e:
-            s.h.decode_step_noalloc(0, w.dec_request, w.dec_stream, qd, out)
+            s.h.decode_step_noalloc(0, w.dec_request, w.dec_stream, qd, out, flags=B.DECODE_FOUR_GROUPS)
         assert e.value.code == B.E_CAPACITY
     s.close()
 
@@ -562,7 +563,7 @@ def test_wide_request_whose_prefix_ends_in_a_deferred_row():
     s.append_events(w.n_prefill, flags=B.APPEND_DEFER)
     pl, *_ = w.lists(0)
     assert min(pl.tolist()) == 700
-    _check_step(w, s, op)
+    _check_step(w, s, op, flags=B.DECODE_FOUR_GROUPS)
     _check_pool(w, s, op)
     s.close()
 
@@ -575,8 +576,8 @@ def test_wide_requests_in_a_ragged_paged_batch(page_tokens):
     op = OraclePool(w).append_events(w.n_prefill)
     s.append_events(w.n_prefill)
     cache = {}
-    _check_step(w, s, op, ref_cache=cache)
-    _check_step(w, s, op, explicit=False, ref_cache=cache)
+    _check_step(w, s, op, flags=B.DECODE_FOUR_GROUPS, ref_cache=cache)
+    _check_step(w, s, op, explicit=False, flags=B.DECODE_FOUR_GROUPS, ref_cache=cache)
     s.close()
 
 

@@ -241,6 +241,35 @@ def test_plan_arithmetic_on_the_8k_prefix_8_stream_shape():
     assert plan[5] == 0 and plan[1] == 0 and plan[2] == sum(-(-v // 128) for v in vis)
 
 
+def test_requests_with_more_than_32_stacked_rows_choice_of_the_form():
+    """One 32-row group per work-group, or four: the plan's count of shared-prefix work-groups tells which.  The
+    library picks the four-group form where three of four waves compute on average and a chunk is four rounds
+    (512 tokens) or more; the two flags force either form."""
+    def wgs(Hq, Hkv, n, prefix, flags=0):
+        w = W.single_request("form", "bf16", Hq, Hkv, 128, 1.0, 3, prefix, [2] * n, "round_robin")
+        h = _handle(Hq=Hq, Hkv=Hkv, pool_tokens=w.pool_tokens, max_streams=w.max_streams)
+        ne = w.n_events(0)
+        _reserve(h, w.ev_request[:ne], w.ev_stream[:ne], w.ev_parent[:ne])
+        _, plan = _plan(h, w.dec_request, w.dec_stream, None, flags=flags)
+        R, chunks = n * (Hq // Hkv), -(-int(plan[5]) // int(plan[4]))
+        assert plan[1] in (chunks * Hkv * -(-R // 32), chunks * Hkv * -(-R // 128))
+        return "four" if (R > 32 and plan[1] == chunks * Hkv * -(-R // 128)) else "one"
+    assert wgs(64, 8, 16, 32768) == "four"          # 128 rows over 32k tokens: chunks of 1024
+    assert wgs(32, 8, 32, 32768) == "four"
+    assert wgs(32, 8, 24, 32768) == "four"          # 96 rows: three of four waves
+    assert wgs(32, 8, 16, 32768) == "one"           # 64 rows: two of four waves would compute
+    assert wgs(32, 8, 32, 8192) == "one"            # chunks of 256 tokens: two rounds
+    assert wgs(32, 8, 40, 32768) == "one"           # 160 rows: five groups over two quads
+    assert wgs(32, 8, 8, 32768) == "one"            # 32 rows: nothing to choose
+    assert wgs(32, 8, 16, 32768, B.DECODE_FOUR_GROUPS) == "four"
+    assert wgs(32, 8, 32, 8192, B.DECODE_FOUR_GROUPS) == "four"
+    assert wgs(64, 8, 16, 32768, B.DECODE_ROW_GROUPS) == "one"
+    assert wgs(32, 8, 8, 32768, B.DECODE_FOUR_GROUPS) == "one"
+    with pytest.raises(B.PastaError) as e:
+        wgs(64, 8, 16, 32768, B.DECODE_FOUR_GROUPS | B.DECODE_ROW_GROUPS)
+    assert e.value.code == B.E_INVAL
+
+
 def test_nested_fork_common_prefix_is_the_minimum():
     w = W.single_request("nested", "bf16", 8, 2, 128, 1.0, 5, 300, [6, 4, 5, 3, 7], "round_robin", nested=(200, 2))
     h = _handle(Hq=8, Hkv=2, pool_tokens=w.pool_tokens, max_streams=w.max_streams)
